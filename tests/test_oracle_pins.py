@@ -1,0 +1,264 @@
+"""Pins of the CPU oracle against what the paper's equations and plain mathematics fix.
+
+None of these tests re-types the oracle's own formula in the oracle's own style and
+calls it a check: each compares against brute force in pure Python, a library routine
+(torch fp64 softmax / matmul), a closed form, or an invariant of Eq. 1-3.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lychee_oracle as lo
+from paper_2602_04541_amd import workloads as wl
+from tests.helpers import bits_to_f64, round_to_bf16_bits, to_bf16_bits
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_form_cases.json")
+
+
+def _rand_bits(rng, shape, scale=1.0):
+    return round_to_bf16_bits(rng.standard_normal(shape).astype(np.float32) * scale)
+
+
+def _tiny(rng, B=2, Hq=4, Hkv=2, L=13, d=6, l_cap=None):
+    l_cap = l_cap or L
+    q = _rand_bits(rng, (B, Hq, d))
+    K = _rand_bits(rng, (B, Hkv, l_cap, d))
+    V = _rand_bits(rng, (B, Hkv, l_cap, d))
+    return q, K, V
+
+
+# --------------------------------------------------------------------------- golden
+@pytest.mark.parametrize("case", json.load(open(GOLDEN))["cases"], ids=lambda c: c["name"])
+def test_closed_form_cases(case):
+    d, k = case["d"], case["k"]
+    q = to_bf16_bits(case["q"])[None]                      # [1, Hq, d]
+    K = to_bf16_bits(case["K"])[None, None]                # [1, 1, L, d]
+    V = to_bf16_bits(case["V"])[None, None]
+    L = K.shape[2]
+    idx_in = None if case["idx_in"] is None else np.asarray(case["idx_in"], np.int32)[None, None]
+    out, idx_out, _ = lo.decode_attn(q, K, V, np.asarray(case["mask"], np.uint8), k, idx_in,
+                                     np.asarray([L], np.int32))
+    np.testing.assert_allclose(out[0], np.asarray(case["expect_out"]), rtol=0, atol=1e-14)
+    assert idx_out[0, 0].tolist() == case["expect_idx_out"]
+
+
+def test_tie_case_with_larger_budget():
+    # same logits (1,3,3,2,3): k = 4 keeps {1,2,3,4}; k = 7 > L pads with -1
+    s = np.array([1.0, 3.0, 3.0, 2.0, 3.0])
+    assert lo.topk(s, 4).tolist() == [1, 2, 3, 4]
+    assert lo.topk(s, 3).tolist() == [1, 2, 4]
+    assert lo.topk(s, 7).tolist() == [0, 1, 2, 3, 4, -1, -1]
+
+
+# ---------------------------------------------------------------- brute force, Eq. 1
+def test_scores_against_pure_python_loops():
+    rng = np.random.default_rng(1)
+    L, d = 7, 5                                            # non-square: a transposed read fails
+    q = _rand_bits(rng, (d,))
+    K = _rand_bits(rng, (L, d))
+    qf, Kf = bits_to_f64(q).tolist(), bits_to_f64(K).tolist()
+    want = [math.fsum(qf[i] * Kf[t][i] for i in range(d)) / math.sqrt(d) for t in range(L)]
+    np.testing.assert_allclose(lo.scores(q, K), want, rtol=1e-14, atol=1e-15)
+
+
+def test_softmax_weights_properties():
+    rng = np.random.default_rng(2)
+    s = rng.standard_normal(50) * 5
+    pos = rng.permutation(50)[:20].astype(np.int32)
+    w = lo.softmax_weights(s, pos)
+    assert abs(w.sum() - 1.0) < 1e-12 and (w > 0).all()
+    # strictly monotone in the logit; ratio of two weights is exp of the logit gap
+    order = np.argsort(s[pos])
+    assert (np.diff(w[order]) >= 0).all()
+    np.testing.assert_allclose(w[3] / w[7], math.exp(s[pos[3]] - s[pos[7]]), rtol=1e-12)
+    # shift invariance of softmax
+    np.testing.assert_allclose(lo.softmax_weights(s + 123.0, pos), w, rtol=1e-10)
+    # huge logits do not overflow
+    big = np.array([1000.0, 999.0, -1000.0])
+    wb = lo.softmax_weights(big, np.arange(3, dtype=np.int32))
+    np.testing.assert_allclose(wb, [1 / (1 + math.exp(-1)), math.exp(-1) / (1 + math.exp(-1)), 0.0],
+                               atol=1e-15)
+
+
+def test_weighted_values_against_pure_python_loops():
+    rng = np.random.default_rng(3)
+    L, d = 9, 4
+    V = _rand_bits(rng, (L, d))
+    pos = np.array([8, 0, 3], np.int32)
+    w = np.array([0.2, 0.5, 0.3])
+    Vf = bits_to_f64(V).tolist()
+    want = [math.fsum(w[j] * Vf[pos[j]][i] for j in range(3)) for i in range(d)]
+    np.testing.assert_allclose(lo.weighted_values(w, pos, V), want, rtol=1e-14)
+
+
+# ------------------------------------------------------------- library routine, Eq. 1
+@pytest.mark.parametrize("B,Hq,Hkv,L,d", [(2, 8, 2, 37, 16), (1, 6, 6, 5, 128), (3, 4, 1, 64, 8)])
+def test_all_retrieval_equals_library_gqa_attention(B, Hq, Hkv, L, d):
+    rng = np.random.default_rng(4)
+    q, K, V = _tiny(rng, B, Hq, Hkv, L, d)
+    out = lo.dense_attn(q, K, V, np.full(B, L, np.int32))
+    G = Hq // Hkv
+    qt = torch.from_numpy(bits_to_f64(q))
+    Kt = torch.from_numpy(bits_to_f64(K)).repeat_interleave(G, dim=1)
+    Vt = torch.from_numpy(bits_to_f64(V)).repeat_interleave(G, dim=1)
+    att = torch.softmax(torch.matmul(Kt, qt[..., None])[..., 0] / math.sqrt(d), dim=-1)
+    want = torch.matmul(att[:, :, None, :], Vt)[:, :, 0, :].numpy()
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-13)
+
+
+def test_outputs_are_convex_combinations_of_value_rows():
+    rng = np.random.default_rng(5)
+    q, K, V = _tiny(rng, 1, 4, 2, 21, 8)
+    out = lo.dense_attn(q, K, V, np.array([21], np.int32))
+    Vf = bits_to_f64(V)
+    for h in range(4):
+        g = h // 2
+        assert (out[0, h] <= Vf[0, g].max(0) + 1e-12).all()
+        assert (out[0, h] >= Vf[0, g].min(0) - 1e-12).all()
+
+
+# ------------------------------------------------------------------ Eq. 3 special cases
+def test_sparse_with_full_set_equals_dense():
+    rng = np.random.default_rng(6)
+    B, Hq, Hkv, L, d = 2, 4, 2, 19, 8
+    q, K, V = _tiny(rng, B, Hq, Hkv, L, d)
+    lens = np.full(B, L, np.int32)
+    full = np.tile(np.arange(L, dtype=np.int32), (B, Hkv, 1))
+    sparse, idx_out, _ = lo.decode_attn(q, K, V, np.zeros(Hq, np.uint8), L, full, lens)
+    dense = lo.dense_attn(q, K, V, lens)
+    np.testing.assert_allclose(sparse, dense, rtol=1e-13, atol=1e-14)
+    assert (idx_out == full).all()
+
+
+def test_sparse_ignores_rows_outside_the_set_and_the_order_of_the_set():
+    rng = np.random.default_rng(7)
+    B, Hq, Hkv, L, d, k = 1, 4, 2, 31, 8, 6
+    q, K, V = _tiny(rng, B, Hq, Hkv, L, d)
+    lens = np.full(B, L, np.int32)
+    idx = np.stack([np.sort(rng.permutation(L)[:k]) for _ in range(Hkv)])[None].astype(np.int32)
+    mask = np.zeros(Hq, np.uint8)
+    base, _, _ = lo.decode_attn(q, K, V, mask, k, idx, lens)
+    K2, V2 = K.copy(), V.copy()
+    for g in range(Hkv):
+        outside = np.setdiff1d(np.arange(L), idx[0, g])
+        K2[0, g, outside] = _rand_bits(rng, (outside.size, d), 50.0)
+        V2[0, g, outside] = _rand_bits(rng, (outside.size, d), 50.0)
+    again, _, _ = lo.decode_attn(q, K2, V2, mask, k, idx, lens)
+    assert (again == base).all()
+    shuffled = idx[:, :, rng.permutation(k)]
+    perm, idx_out, _ = lo.decode_attn(q, K, V, mask, k, shuffled, lens)
+    np.testing.assert_allclose(perm, base, rtol=1e-12, atol=1e-14)
+    assert (idx_out == shuffled).all()                      # handed on bit for bit
+    # -1 padding is skipped: a padded set gives what the short set gives
+    padded = np.concatenate([idx, np.full((1, Hkv, 3), -1, np.int32)], axis=2)
+    pad_out, _, _ = lo.decode_attn(q, K, V, mask, k + 3, padded, lens)
+    assert (pad_out == base).all()
+
+
+def test_sparse_against_library_on_the_gathered_rows():
+    rng = np.random.default_rng(8)
+    L, d, k = 40, 16, 9
+    q, K, V = _tiny(rng, 1, 1, 1, L, d)
+    idx = np.sort(rng.permutation(L)[:k]).astype(np.int32)
+    out, _, _ = lo.decode_attn(q, K, V, np.zeros(1, np.uint8), k, idx[None, None],
+                               np.array([L], np.int32))
+    Ks = torch.from_numpy(bits_to_f64(K[0, 0, idx]))
+    Vs = torch.from_numpy(bits_to_f64(V[0, 0, idx]))
+    qt = torch.from_numpy(bits_to_f64(q[0, 0]))
+    want = (torch.softmax(Ks @ qt / math.sqrt(d), 0) @ Vs).numpy()
+    np.testing.assert_allclose(out[0, 0], want, rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------------ Eq. 2, top-k
+def test_topk_against_python_sorted_for_every_k_with_ties():
+    rng = np.random.default_rng(9)
+    for L in (1, 2, 17, 64):
+        s = np.round(rng.standard_normal(L) * 2) / 2       # many exact ties
+        for k in range(1, L + 3):
+            ranked = sorted(range(L), key=lambda t: (-s[t], t))
+            want = sorted(ranked[:min(k, L)]) + [-1] * max(0, k - L)
+            assert lo.topk(s, k).tolist() == want
+
+
+def test_selection_uses_the_mean_logit_of_the_groups_retrieval_heads():
+    """App. F pooling, by linearity: top-k of (mean of the retrieval q's) . K."""
+    rng = np.random.default_rng(10)
+    B, Hq, Hkv, L, d, k = 1, 8, 2, 50, 16, 7
+    q, K, V = _tiny(rng, B, Hq, Hkv, L, d)
+    mask = np.array([1, 0, 1, 1, 0, 0, 0, 1], np.uint8)     # group 0: heads 0,2,3; group 1: head 7
+    idx_in = np.tile(np.arange(k, dtype=np.int32), (B, Hkv, 1))
+    _, idx_out, sel = lo.decode_attn(q, K, V, mask, k, idx_in, np.array([L], np.int32),
+                                     want_sel=True)
+    qf, Kf = bits_to_f64(q), bits_to_f64(K)
+    for g, heads in ((0, [0, 2, 3]), (1, [7])):
+        pooled_q = qf[0, heads].mean(0)
+        pooled_logit = Kf[0, g] @ pooled_q / math.sqrt(d)
+        np.testing.assert_allclose(sel[0, g], pooled_logit, rtol=1e-12, atol=1e-13)
+        want = np.sort(np.argsort(-pooled_logit, kind="stable")[:k])
+        assert idx_out[0, g].tolist() == want.tolist()
+
+
+def test_sets_pass_through_groups_without_a_retrieval_head():
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, L, d, k = 2, 6, 3, 20, 8, 5
+    q, K, V = _tiny(rng, B, Hq, Hkv, L, d)
+    mask = np.array([0, 0, 1, 0, 0, 0], np.uint8)           # only group 1 selects
+    idx_in = rng.integers(0, L, size=(B, Hkv, k)).astype(np.int32)
+    idx_in[0, 0, 3:] = -1
+    _, idx_out, _ = lo.decode_attn(q, K, V, mask, k, idx_in, np.full(B, L, np.int32))
+    assert (idx_out[:, 0] == idx_in[:, 0]).all() and (idx_out[:, 2] == idx_in[:, 2]).all()
+    assert not (idx_out[:, 1] == idx_in[:, 1]).all()
+
+
+# ----------------------------------------------------------- lengths, strides, workloads
+def test_ragged_lengths_equal_the_truncated_problem_and_strides_are_honoured():
+    rng = np.random.default_rng(12)
+    B, Hq, Hkv, L, d, k, cap = 2, 4, 2, 11, 8, 4, 16
+    q, K, V = _tiny(rng, B, Hq, Hkv, L, d, l_cap=cap)
+    lens = np.array([11, 6], np.int32)
+    mask = np.array([1, 0, 0, 1], np.uint8)
+    idx_in = np.tile(np.arange(k, dtype=np.int32), (B, Hkv, 1))
+    out, idx_out, _ = lo.decode_attn(q, K, V, mask, k, idx_in, lens)
+    for b in range(B):
+        Lb = int(lens[b])
+        o1, i1, _ = lo.decode_attn(q[b:b + 1], np.ascontiguousarray(K[b:b + 1, :, :Lb]),
+                                   np.ascontiguousarray(V[b:b + 1, :, :Lb]), mask, k,
+                                   idx_in[b:b + 1], lens[b:b + 1])
+        assert (o1 == out[b:b + 1]).all() and (i1 == idx_out[b:b + 1]).all()
+    # the same cache embedded in a wider buffer (token stride 2d, padded heads)
+    wide_k = np.zeros((B, Hkv + 1, cap, 2 * d), np.uint16)
+    wide_v = np.zeros_like(wide_k)
+    wide_k[:, :Hkv, :, :d], wide_v[:, :Hkv, :, :d] = K, V
+    o2, i2, _ = lo.decode_attn(q, wide_k[:, :Hkv, :, :d], wide_v[:, :Hkv, :, :d], mask, k,
+                               idx_in, lens)
+    assert (o2 == out).all() and (i2 == idx_out).all()
+
+
+def test_planted_rows_are_selected_on_the_small_workload():
+    w = wl.WORKLOADS["c1"]
+    inp = wl.make_layer(w)
+    q, K, V = (wl.bf16_bits(t) for t in (inp.q, inp.k_cache, inp.v_cache))
+    prev = np.tile(np.arange(w.k, dtype=np.int32), (1, w.n_kv_heads, 1))
+    out, idx_out, sel = lo.decode_attn(q, K, V, inp.mask, w.k, prev, inp.lengths, want_sel=True)
+    for g in range(w.n_kv_heads):
+        assert np.isin(inp.planted_pos[0, g], idx_out[0, g]).all()
+        assert (np.diff(idx_out[0, g]) > 0).all()
+        # planted logits sit near 3*||q*|| and far above the N(0,1) background
+        assert sel[0, g, inp.planted_pos[0, g]].min() > 20.0
+    assert np.isfinite(out).all()
+
+
+def test_oracle_rejects_bad_arguments():
+    rng = np.random.default_rng(13)
+    q, K, V = _tiny(rng, 1, 4, 2, 8, 4)
+    with pytest.raises(ValueError):                          # sparse heads but no set
+        lo.decode_attn(q, K, V, np.zeros(4, np.uint8), 2, None, np.array([8], np.int32))
+    with pytest.raises(ValueError):                          # length beyond the cache
+        lo.decode_attn(q, K, V, np.ones(4, np.uint8), 2, None, np.array([9], np.int32))
+    with pytest.raises(ValueError):                          # index beyond the length
+        lo.decode_attn(q, K, V, np.zeros(4, np.uint8), 2,
+                       np.full((1, 2, 2), 7, np.int32), np.array([5], np.int32))
