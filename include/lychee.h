@@ -1,0 +1,160 @@
+/*
+ * lychee.h — C ABI of the MI355X (gfx950) decode-step hybrid-head sparse attention.
+ *
+ * One decode step of LycheeDecode's attention (Sec. 3.1; Alg. 1, the per-head loop of
+ * App. B): in every layer the few *retrieval heads* attend over the whole KV cache
+ * (Eq. 1) and pick the k highest-scoring positions (Eq. 2); the *sparse heads* attend
+ * only over the k rows named by the set inherited from the previous layer (Eq. 3) and
+ * hand that set on unchanged.  Under grouped-query attention there is one set per KV
+ * head, ranked by the mean logit of the group's retrieval heads (App. F).  Head types
+ * are an input (the trained HardKuma assignment of Sec. 3.2, thresholded).
+ *
+ * Conventions shared by every call
+ *   - Pointers are DEVICE pointers unless a parameter says HOST.  The caller owns every
+ *     buffer; the library neither frees nor keeps them after the call's stream-ordered
+ *     work has finished.  Nothing is allocated inside a call.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t; NULL = the default stream)
+ *     and return without waiting for it.  They never read device memory from the host.
+ *   - bf16 means the upper 16 bits of an IEEE fp32.  Scores and accumulation are fp32;
+ *     `out` is rounded to nearest-even bf16.
+ *   - KV-cache element (b, g, t, i), g a KV head, t a position, i < 128, lives at
+ *         base + b*kv_stride_batch + g*kv_stride_head + t*kv_stride_tok + i   (elements).
+ *     K and V use the same strides.  The preferred layout is [B][H_kv][L_cap][128] with
+ *     256-byte aligned rows: each (b, g) is then one contiguous stream of 256-byte rows
+ *     (two 128-byte lines), which is what the streaming kernel is tuned for.
+ *   - Index sets are int32 [B][H_kv][k]: positions in [0, L_b), distinct, valid entries
+ *     first, -1 padding after (when k > L_b).  Sets written by the library are ascending
+ *     by position; ties in the score go to the lower position.  Entries of `idx_in` that
+ *     are negative or >= L_b are ignored (never dereferenced).
+ *   - Return value: 0, or a negative LYCHEE_E* code; on an error nothing was enqueued.
+ *   - Results are deterministic: the same inputs give bit-identical outputs.
+ *   - Two calls that share a workspace must be ordered on one stream.
+ */
+#ifndef LYCHEE_H
+#define LYCHEE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LYCHEE_OK            0
+#define LYCHEE_EINVAL       (-1)  /* a NULL / misaligned pointer or an inconsistent value       */
+#define LYCHEE_EUNSUPPORTED (-2)  /* a valid request this build does not serve                 */
+#define LYCHEE_EWORKSPACE   (-3)  /* workspace NULL, misaligned or smaller than required       */
+#define LYCHEE_EHIP         (-4)  /* a HIP runtime call failed (no device, launch error, ...)  */
+
+#define LYCHEE_HEAD_DIM      128  /* the only head dimension served                            */
+#define LYCHEE_MAX_KV_HEADS   64
+#define LYCHEE_MAX_GROUP       4  /* query heads per KV head served (1..4)                     */
+
+typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id and tuning, no buffers */
+
+/* Problem shape of one layer call (the inputs of Alg. 1 that are not tensors). */
+typedef struct lychee_shape {
+    int32_t batch;       /* B  >= 1                                                          */
+    int32_t n_q_heads;   /* H_q, a multiple of n_kv_heads with H_q / H_kv <= LYCHEE_MAX_GROUP */
+    int32_t n_kv_heads;  /* H_kv in [1, LYCHEE_MAX_KV_HEADS]                                 */
+    int32_t head_dim;    /* must be LYCHEE_HEAD_DIM                                          */
+    int32_t max_len;     /* host-known upper bound of lengths[]; sizes grids and workspace,
+                            so that no call has to read lengths[] on the host              */
+    int32_t k;           /* token budget of Eq. 2 / Eq. 3, >= 1                              */
+    int64_t kv_stride_batch, kv_stride_head, kv_stride_tok; /* elements; each a multiple of 8
+                            (16-byte vector loads), kv_stride_tok >= 128                    */
+} lychee_shape;
+
+/* Create / destroy a context bound to HIP device `device`.  Needs a GPU. */
+int lychee_create(lychee_ctx **ctx, int device);
+int lychee_destroy(lychee_ctx *ctx);
+
+/* Pure host functions (no GPU needed).
+ * lychee_check_shape: validates `shape`; if `head_type_mask` (HOST, [H_q]) is given it also
+ *   checks that sparse heads come with an inherited set (`has_idx_in` != 0).
+ * lychee_workspace_bytes: bytes of scratch any call below needs for `shape` (selection
+ *   scores, split partials, the step driver's set buffers); 0 if the shape is invalid.
+ *   The workspace must be 256-byte aligned; its contents are don't-care on entry. */
+int    lychee_check_shape(const lychee_shape *shape, const uint8_t *head_type_mask, int has_idx_in);
+size_t lychee_workspace_bytes(const lychee_shape *shape);
+
+/*
+ * One layer of Alg. 1's per-head loop (retrieval branch: Eq. 1, Eq. 2, o = A V; sparse
+ * branch: Eq. 3), for all sequences of a batch.
+ *   q               bf16 [B][H_q][128], 16-byte aligned
+ *   k_cache,v_cache bf16, strided as in `shape`, 16-byte aligned, read-only
+ *   head_type_mask  HOST uint8 [H_q]: 1 = retrieval head, 0 = sparse head
+ *   idx_in          int32 [B][H_kv][k], the sets inherited from the previous layer; may be
+ *                   NULL only if every head is a retrieval head (the first layer)
+ *   out             bf16 [B][H_q][128], 16-byte aligned
+ *   idx_out         int32 [B][H_kv][k]: for a KV head whose group holds a retrieval head,
+ *                   the min(k, L_b) positions with the highest mean retrieval logit; for any
+ *                   other KV head a verbatim copy of idx_in.  Must not alias idx_in.
+ *   lengths         int32 [B], 1 <= L_b <= max_len, the current token included (values
+ *                   outside that range are clamped into it)
+ * Errors: EINVAL (NULL / misaligned pointer, bad shape, sparse heads without idx_in,
+ * idx_out == idx_in), EUNSUPPORTED (head_dim, group size), EWORKSPACE, EHIP.
+ */
+int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
+                       const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
+                       const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Dense decode attention on the same buffers: every head runs Eq. 1 and o = A V, nothing
+ * is selected.  The in-run speed baseline; `shape->k` is ignored (any value >= 1). */
+int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
+                             const void *k_cache, const void *v_cache, void *out,
+                             const int32_t *lengths, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/*
+ * The attention of a whole decode step (Alg. 1, the layer loop restricted to its per-head
+ * loop): layers 0 .. n_layers-1 in order, the sets written by layer l feeding layer l+1
+ * (Sec. 3.1: the set is propagated to the next layer).  All layers share `shape` and
+ * `lengths`.
+ *   q, k_cache, v_cache, out   HOST arrays of n_layers device pointers
+ *   head_type_masks            HOST uint8 [n_layers][H_q]
+ *   idx_in                     sets entering layer 0, or NULL when layer 0 is all-retrieval
+ *                              (Sec. 3.1: every head of the first layer is a retrieval head)
+ *   idx_out                    the sets leaving the last layer; may be NULL
+ */
+int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
+                       const void *const *q, const void *const *k_cache,
+                       const void *const *v_cache, const uint8_t *head_type_masks,
+                       const int32_t *idx_in, void *const *out, int32_t *idx_out,
+                       const int32_t *lengths, void *workspace, size_t workspace_bytes,
+                       void *hip_stream);
+
+/* Debug helper (synchronous): counts entries of idx [B][H_kv][k] that break the index
+ * conventions (out of [0, L_b), duplicated, or valid after a -1) into *n_bad (HOST). */
+int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,
+                        const int32_t *lengths, int64_t *n_bad, void *hip_stream);
+
+/* Tuning: rows of the KV cache (retrieval) / entries of the set (sparse) one workgroup
+ * handles.  0 = choose from the shape.  Values are rounded up to a multiple of 64 and
+ * clamped to [128, 65536]; results never depend on them beyond fp32 rounding order. */
+int lychee_set_unit_rows(lychee_ctx *ctx, int32_t retrieval_rows, int32_t sparse_rows);
+
+/* Per-kernel timing with HIP events on the caller's stream.  While enabled, every launch of
+ * the library's kernels is bracketed by an event pair.  lychee_timing_read waits for the
+ * recorded events, adds up the milliseconds and launches per kernel class since the last
+ * read and clears the record.  Classes: 0 = attention units, 1 = combine, 2 = top-k select. */
+#define LYCHEE_KERNEL_ATTN    0
+#define LYCHEE_KERNEL_COMBINE 1
+#define LYCHEE_KERNEL_SELECT  2
+#define LYCHEE_N_KERNEL_CLASSES 3
+int lychee_timing_enable(lychee_ctx *ctx, int on);
+int lychee_timing_read(lychee_ctx *ctx, float *ms_per_class, int32_t *launches_per_class);
+
+/* Plain streaming kernels used to calibrate the measurements: a read of `bytes` bytes
+ * (sum folded into *sink, 4 bytes) and a copy of `bytes` bytes.  16-byte aligned, bytes a
+ * multiple of 16. */
+int lychee_probe_read(lychee_ctx *ctx, const void *src, size_t bytes, void *sink, void *hip_stream);
+int lychee_probe_copy(lychee_ctx *ctx, void *dst, const void *src, size_t bytes, void *hip_stream);
+
+const char *lychee_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LYCHEE_H */
