@@ -55,6 +55,15 @@ __device__ __forceinline__ float bf16_hi(uint32_t u)
     return __builtin_bit_cast(float, u & 0xFFFF0000u);
 }
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte streaming load: the cache rows are read once per step and never again.
+__device__ __forceinline__ uint4 load_stream16(const uint16_t *p)
+{
+    const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
 struct Tile {
     uint4 k[4];
     uint4 v[4];
@@ -138,6 +147,9 @@ __device__ __forceinline__ void consume_tile(const Tile &t, const uint4 (&qf)[NH
     }
 }
 
+// Tile buffers per wavefront: fewer heads leave more registers for loads in flight.
+__host__ __device__ constexpr int ring_depth(int nh) { return nh == 1 ? 6 : (nh == 2 ? 5 : (nh == 3 ? 4 : 3)); }
+
 // One unit.  GATHER = false: rows [r0, r1) of the cache (retrieval heads); true: entries
 // [r0, r1) of the inherited set, staged in `idx_s` (sparse heads).
 template <int NH, bool GATHER>
@@ -200,12 +212,12 @@ __device__ __forceinline__ void run_unit(const AttnPlan &p, int b, int g, int rg
                 row = ok ? tpos : 0;
             } else {
                 ok = r < r1;
-                row = ok ? r : (r1 - 1);
+                row = ok ? r : (r1 > 0 ? r1 - 1 : 0);
             }
             t.valid |= (ok ? 1 : 0) << j;
             const int64_t off = (int64_t)row * p.stride_t;
-            t.k[j] = reinterpret_cast<const uint4 *>(kbase + off)[c];
-            t.v[j] = reinterpret_cast<const uint4 *>(vbase + off)[c];
+            t.k[j] = load_stream16(kbase + off + c * 8);
+            t.v[j] = load_stream16(vbase + off + c * 8);
         }
     };
     auto consume = [&](const Tile &t, int tile) {
@@ -222,20 +234,24 @@ __device__ __forceinline__ void run_unit(const AttnPlan &p, int b, int g, int rg
         }
     };
 
-    // Wavefront w takes tiles w, w+4, ...; two tile buffers alternate so that one tile's
-    // loads are in flight while the other tile is consumed.
-    Tile ta, tb;
-    int tile = wave;
-    if (tile < n_tiles) issue(ta, tile);
-    while (tile < n_tiles) {
-        const int next = tile + kAttnWaves;
-        if (next < n_tiles) issue(tb, next);
-        consume(ta, tile);
-        if (next >= n_tiles) break;
-        const int next2 = next + kAttnWaves;
-        if (next2 < n_tiles) issue(ta, next2);
-        consume(tb, next);
-        tile = next2;
+    // Wavefront w takes tiles w, w+4, ...; a ring of kDepth tile buffers keeps kDepth-1
+    // tiles' loads in flight while one tile is consumed.
+    constexpr int kDepth = ring_depth(NH);
+    Tile ring[kDepth];
+    const int n_mine = n_tiles > wave ? (n_tiles - wave + kAttnWaves - 1) / kAttnWaves : 0;
+    // Loads are issued unconditionally (a tile past the end re-reads the unit's last row and
+    // is marked invalid): a conditional refill would make the ring registers loop-carried
+    // through a copy, and the copy would have to wait for the load it copies.
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) issue(ring[d], wave + d * kAttnWaves);
+    for (int i = 0; i < n_mine; i += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (i + d < n_mine) consume(ring[d], wave + (i + d) * kAttnWaves);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(ring[d], wave + (i + d + kDepth) * kAttnWaves);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).
