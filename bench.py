@@ -28,7 +28,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
-    ap.add_argument("--unit-rows", type=int, nargs=2, default=(0, 0), metavar=("R", "S"))
+    ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--no-pipeline", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -46,7 +47,9 @@ def main() -> int:
     w = wl.WORKLOADS[args.workload]
     n_layers = args.layers or w.n_layers
     ctx = lb.Context(0)
-    ctx.set_unit_rows(*args.unit_rows)
+    if args.wg_per_cu:
+        ctx.set_option(lb.OPT_WG_PER_CU, args.wg_per_cu)
+    ctx.set_option(lb.OPT_PIPELINE, 0 if args.no_pipeline else 1)
 
     t_gen = time.perf_counter()
     layers = [wl.make_layer(w, layer=l, device=dev) for l in range(n_layers)]
@@ -142,7 +145,7 @@ def main() -> int:
                                "layer 0 all-retrieval then %d retrieval heads per layer" % (
                                    w.name, n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.max_len,
                                    w.k, w.n_retrieval),
-                   "unit_rows": list(args.unit_rows)},
+                   "pipeline": not args.no_pipeline},
         "step_algorithmic_bytes": step_bytes,
         "step_achieved_gbps": round(step_bytes / sec / 1e9, 1),
         "step_hbm_frac": round(step_bytes / sec / 1e9 / HBM_PEAK_GBPS, 4),

@@ -49,12 +49,13 @@ extern "C" {
 #define LYCHEE_HEAD_DIM      128  /* the only head dimension served                            */
 #define LYCHEE_MAX_KV_HEADS   64
 #define LYCHEE_MAX_GROUP       4  /* query heads per KV head served (1..4)                     */
+#define LYCHEE_MAX_BATCH     256
 
 typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id and tuning, no buffers */
 
 /* Problem shape of one layer call (the inputs of Alg. 1 that are not tensors). */
 typedef struct lychee_shape {
-    int32_t batch;       /* B  >= 1                                                          */
+    int32_t batch;       /* B in [1, LYCHEE_MAX_BATCH]                                       */
     int32_t n_q_heads;   /* H_q, a multiple of n_kv_heads with H_q / H_kv <= LYCHEE_MAX_GROUP */
     int32_t n_kv_heads;  /* H_kv in [1, LYCHEE_MAX_KV_HEADS]                                 */
     int32_t head_dim;    /* must be LYCHEE_HEAD_DIM                                          */
@@ -130,15 +131,32 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
 int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,
                         const int32_t *lengths, int64_t *n_bad, void *hip_stream);
 
-/* Tuning: rows of the KV cache (retrieval) / entries of the set (sparse) one workgroup
- * handles.  0 = choose from the shape.  Values are rounded up to a multiple of 64 and
- * clamped to [128, 65536]; results never depend on them beyond fp32 rounding order. */
-int lychee_set_unit_rows(lychee_ctx *ctx, int32_t retrieval_rows, int32_t sparse_rows);
+/* Options of a context.  Results never depend on them beyond fp32 rounding order of the
+ * split merge (index sets do not depend on them at all).
+ *   WG_PER_CU  workgroups per compute unit in every launch (1..3, default 2)
+ *   PIPELINE   lychee_decode_step: 1 (default) = one launch per layer, in which the streaming
+ *              of layer t runs beside the select / gather / combine work of layers t-1..t-3
+ *              (outputs of layer l are complete three launches after its streaming);
+ *              0 = layer after layer, three dependent launches each, as lychee_decode_attn
+ *   COST_*     balancing weights of the small work units, in 64-row blocks of streaming
+ *   N_WG       workgroups per launch, overriding WG_PER_CU (0 = CUs x WG_PER_CU; at most 768)
+ *   GATHER_BLOCK  set entries whose gather is balanced against 64 streamed rows (a multiple
+ *              of 16 in [16, 128], default 48: a gathered row costs more than a streamed one) */
+#define LYCHEE_OPT_WG_PER_CU 1
+#define LYCHEE_OPT_PIPELINE  2
+#define LYCHEE_OPT_COST_S2   3
+#define LYCHEE_OPT_COST_C    4
+#define LYCHEE_OPT_COST_S1   5
+#define LYCHEE_OPT_GATHER_BLOCK 6
+#define LYCHEE_OPT_N_WG       7
+int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
 
 /* Per-kernel timing with HIP events on the caller's stream.  While enabled, every launch of
  * the library's kernels is bracketed by an event pair.  lychee_timing_read waits for the
- * recorded events, adds up the milliseconds and launches per kernel class since the last
- * read and clears the record.  Classes: 0 = attention units, 1 = combine, 2 = top-k select. */
+ * recorded events, adds up the milliseconds and launches per launch class since the last
+ * read and clears the record.  Every launch runs the same work-unit kernel; its class says
+ * what it carried: 0 = streaming / gather work (plus whatever else shared the launch),
+ * 1 = select phase 1 and combine only, 2 = select phase 2 only. */
 #define LYCHEE_KERNEL_ATTN    0
 #define LYCHEE_KERNEL_COMBINE 1
 #define LYCHEE_KERNEL_SELECT  2

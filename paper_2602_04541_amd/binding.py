@@ -19,11 +19,12 @@ LIB_PATH = os.path.join(_HERE, "liblychee.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 KERNEL_ATTN, KERNEL_COMBINE, KERNEL_SELECT = 0, 1, 2
+OPT_WG_PER_CU, OPT_PIPELINE, OPT_COST_S2, OPT_COST_C, OPT_COST_S1, OPT_GATHER_BLOCK, OPT_N_WG = 1, 2, 3, 4, 5, 6, 7
 
 EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
     "lychee_decode_attn", "lychee_dense_decode_attn", "lychee_decode_step",
-    "lychee_validate_idx", "lychee_set_unit_rows", "lychee_timing_enable",
+    "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
 ]
 
@@ -59,7 +60,7 @@ def _load() -> ctypes.CDLL:
     lib.lychee_dense_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_validate_idx.argtypes = [vp, shp, vp, vp, ctypes.POINTER(i64), vp]
-    lib.lychee_set_unit_rows.argtypes = [vp, i32, i32]
+    lib.lychee_set_option.argtypes = [vp, i32, i32]
     lib.lychee_timing_enable.argtypes = [vp, ctypes.c_int]
     lib.lychee_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     lib.lychee_probe_read.argtypes = [vp, vp, sz, vp, vp]
@@ -186,8 +187,8 @@ class Context:
                                         ctypes.byref(n_bad), _stream(stream)), "lychee_validate_idx")
         return int(n_bad.value)
 
-    def set_unit_rows(self, retrieval_rows: int = 0, sparse_rows: int = 0) -> None:
-        _check(_lib.lychee_set_unit_rows(self._h, retrieval_rows, sparse_rows), "lychee_set_unit_rows")
+    def set_option(self, option: int, value: int) -> None:
+        _check(_lib.lychee_set_option(self._h, option, value), "lychee_set_option")
 
     def timing_enable(self, on: bool) -> None:
         _check(_lib.lychee_timing_enable(self._h, int(on)), "lychee_timing_enable")

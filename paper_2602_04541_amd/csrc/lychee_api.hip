@@ -15,42 +15,66 @@ using namespace lychee;
 struct lychee_ctx {
     int device = 0;
     int n_cu = 256;
-    int32_t unit_r = 0, unit_s = 0;  // 0 = automatic
+    int32_t wg_per_cu = 2;
+    int32_t pipeline = 1;
+    int32_t cost_s2 = 3, cost_c = 1, cost_s1 = 1;
+    int32_t g_block_rows = 48;
+    int32_t n_wg = 0;  // 0 = n_cu * wg_per_cu
     bool timing = false;
     struct Rec {
         int cls;
         hipEvent_t start, stop;
     };
-    std::vector<Rec> recs;       // events recorded since the last read
+    std::vector<Rec> recs;         // events recorded since the last read
     std::vector<hipEvent_t> pool;  // events free for reuse
 };
 
 namespace {
 
+constexpr int kWsWg = 768;      // partial slots per head the workspace provides
+constexpr int kSelRing = 3;     // layers whose selection scores are alive at once (pipelined step)
+constexpr int kPartRing = 4;
+constexpr int kListRing = 2;
+
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+int32_t slice_cap(int32_t max_len)
+{
+    const int64_t per = (max_len + kSlices - 1) / kSlices;
+    return (int32_t)round_up(per, kSliceQuantum);
+}
+
 struct Workspace {
-    size_t sel_off, part_o_off, part_ml_off, idx_a_off, idx_b_off, total;
-    int32_t sel_stride, s_max;
+    size_t sel_off[kSelRing], part_o_off[kPartRing], part_ml_off[kPartRing], part_count_off[kPartRing];
+    size_t list_off[kListRing], list_count_off[kListRing], idx_off[2], total;
+    int32_t sel_stride, list_cap;
 };
 
 Workspace carve(const lychee_shape &s)
 {
     Workspace w;
     w.sel_stride = (int32_t)round_up(s.max_len, 64);
-    w.s_max = (int32_t)((s.max_len + kMinUnitRows - 1) / kMinUnitRows);
+    w.list_cap = slice_cap(s.max_len);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
         off = (size_t)round_up((int64_t)(off + bytes), 256);
         return at;
     };
-    w.sel_off = take((size_t)s.batch * s.n_kv_heads * w.sel_stride * sizeof(float));
-    w.part_o_off = take((size_t)s.batch * s.n_q_heads * w.s_max * kHeadDim * sizeof(float));
-    w.part_ml_off = take((size_t)s.batch * s.n_q_heads * w.s_max * 2 * sizeof(float));
-    w.idx_a_off = take((size_t)s.batch * s.n_kv_heads * s.k * sizeof(int32_t));
-    w.idx_b_off = take((size_t)s.batch * s.n_kv_heads * s.k * sizeof(int32_t));
+    const size_t heads = (size_t)s.batch * s.n_q_heads;
+    const size_t groups = (size_t)s.batch * s.n_kv_heads;
+    for (int i = 0; i < kSelRing; ++i) w.sel_off[i] = take(groups * w.sel_stride * sizeof(float));
+    for (int i = 0; i < kPartRing; ++i) {
+        w.part_o_off[i] = take(heads * kWsWg * kHeadDim * sizeof(float));
+        w.part_ml_off[i] = take(heads * kWsWg * 2 * sizeof(float));
+        w.part_count_off[i] = take(heads * sizeof(int32_t));
+    }
+    for (int i = 0; i < kListRing; ++i) {
+        w.list_off[i] = take(groups * kSlices * (size_t)w.list_cap * sizeof(uint2));
+        w.list_count_off[i] = take(groups * kSlices * sizeof(int32_t));
+    }
+    for (int i = 0; i < 2; ++i) w.idx_off[i] = take(groups * s.k * sizeof(int32_t));
     w.total = off;
     return w;
 }
@@ -64,7 +88,7 @@ int check_shape(const lychee_shape *s)
     if (s->head_dim != kHeadDim) return LYCHEE_EUNSUPPORTED;
     if (s->n_kv_heads > kMaxKvHeads) return LYCHEE_EUNSUPPORTED;
     if (s->n_q_heads / s->n_kv_heads > kMaxGroup) return LYCHEE_EUNSUPPORTED;
-    if (s->max_len > (1 << 24) || s->batch > (1 << 16)) return LYCHEE_EUNSUPPORTED;
+    if (s->max_len > (1 << 24) || s->batch > kMaxBatch) return LYCHEE_EUNSUPPORTED;
     if (s->kv_stride_tok < kHeadDim || s->kv_stride_batch < 0 || s->kv_stride_head < 0)
         return LYCHEE_EINVAL;
     if (s->kv_stride_tok % 8 || s->kv_stride_head % 8 || s->kv_stride_batch % 8) return LYCHEE_EINVAL;
@@ -73,103 +97,160 @@ int check_shape(const lychee_shape *s)
     return LYCHEE_OK;
 }
 
-// The unit sizes: enough equally sized units to load every CU a few times over.
-void choose_units(const lychee_ctx *ctx, const lychee_shape &s, int n_rgroups, int n_sgroups,
-                  int32_t &unit_r, int32_t &unit_s)
-{
-    const int64_t kk = s.k < s.max_len ? s.k : s.max_len;
-    const int64_t rows = (int64_t)s.batch * ((int64_t)n_rgroups * s.max_len + (int64_t)n_sgroups * kk);
-    const int64_t target_units = (int64_t)ctx->n_cu * 6;
-    int64_t u = round_up((rows + target_units - 1) / target_units, 64);
-    if (u < 256) u = 256;
-    if (u > 4096) u = 4096;
-    unit_r = ctx->unit_r > 0 ? ctx->unit_r : (int32_t)u;
-    unit_s = ctx->unit_s > 0 ? ctx->unit_s : (int32_t)u;
-    if (unit_s > kMaxSparseUnit) unit_s = kMaxSparseUnit;
-}
-
-struct LayerPlan {
-    AttnPlan attn;
-    CombinePlan comb;
-    SelectPlan sel;
-    bool do_select;
+// The head-type structure of one layer, as the kernels want it.
+struct Groups {
+    int n_rgroups = 0, n_sgroups = 0;
+    uint8_t rgroup[kMaxKvHeads], sgroup[kMaxKvHeads], rmask[kMaxKvHeads], rindex[kMaxKvHeads];
 };
 
-// Fills the three kernel plans of one layer call.  `mask` == nullptr means dense.
-void build_layer(const lychee_ctx *ctx, const lychee_shape &s, const Workspace &w, char *ws,
-                 const void *q, const void *k_cache, const void *v_cache, const uint8_t *mask,
-                 const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
-                 LayerPlan &lp)
+Groups make_groups(const lychee_shape &s, const uint8_t *mask)  // mask == nullptr: all retrieval
 {
+    Groups gr;
+    memset(&gr, 0, sizeof gr);
     const int G = s.n_q_heads / s.n_kv_heads;
-    AttnPlan &a = lp.attn;
-    memset(&a, 0, sizeof a);
-    a.q = static_cast<const uint16_t *>(q);
-    a.k_cache = static_cast<const uint16_t *>(k_cache);
-    a.v_cache = static_cast<const uint16_t *>(v_cache);
-    a.idx_in = idx_in;
-    a.lengths = lengths;
-    a.sel = reinterpret_cast<float *>(ws + w.sel_off);
-    a.part_o = reinterpret_cast<float *>(ws + w.part_o_off);
-    a.part_ml = reinterpret_cast<float *>(ws + w.part_ml_off);
-    a.stride_b = s.kv_stride_batch;
-    a.stride_h = s.kv_stride_head;
-    a.stride_t = s.kv_stride_tok;
-    a.batch = s.batch;
-    a.n_q_heads = s.n_q_heads;
-    a.n_kv_heads = s.n_kv_heads;
-    a.group = G;
-    a.k = s.k;
-    a.max_len = s.max_len;
-    a.sel_stride = w.sel_stride;
-    a.s_max = w.s_max;
-    a.scale = (float)(1.0 / sqrt((double)kHeadDim));
-    a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
-    a.emit_sel = mask != nullptr ? 1 : 0;
-    SelectPlan &sp = lp.sel;
-    memset(&sp, 0, sizeof sp);
     for (int g = 0; g < s.n_kv_heads; ++g) {
         uint32_t bits = 0;
         for (int i = 0; i < G; ++i)
             if (mask == nullptr || mask[g * G + i]) bits |= 1u << i;
-        a.rmask[g] = (uint8_t)bits;
-        sp.rindex[g] = 0xFF;
+        gr.rmask[g] = (uint8_t)bits;
+        gr.rindex[g] = 0xFF;
         if (bits != 0) {
-            sp.rindex[g] = (uint8_t)a.n_rgroups;
-            a.rgroup[a.n_rgroups++] = (uint8_t)g;
+            gr.rindex[g] = (uint8_t)gr.n_rgroups;
+            gr.rgroup[gr.n_rgroups++] = (uint8_t)g;
         }
-        if (bits != (1u << G) - 1u) a.sgroup[a.n_sgroups++] = (uint8_t)g;
+        if (bits != (1u << G) - 1u) gr.sgroup[gr.n_sgroups++] = (uint8_t)g;
     }
-    choose_units(ctx, s, a.n_rgroups, a.n_sgroups, a.unit_r, a.unit_s);
-    a.nsplit_r = (s.max_len + a.unit_r - 1) / a.unit_r;
-    const int kk = s.k < s.max_len ? s.k : s.max_len;
-    a.nsplit_s = (kk + a.unit_s - 1) / a.unit_s;
+    return gr;
+}
 
-    CombinePlan &c = lp.comb;
-    memset(&c, 0, sizeof c);
-    c.part_o = a.part_o;
-    c.part_ml = a.part_ml;
-    c.out = static_cast<uint16_t *>(out);
-    c.batch = s.batch;
-    c.n_q_heads = s.n_q_heads;
-    c.group = G;
-    c.s_max = w.s_max;
-    c.nsplit_r = a.nsplit_r;
-    c.nsplit_s = a.nsplit_s;
-    c.scale_log2e = a.scale_log2e;
-    memcpy(c.rmask, a.rmask, sizeof c.rmask);
+// One layer's tensors and where its intermediate results live.
+struct LayerIo {
+    const void *q, *k_cache, *v_cache;
+    void *out;
+    const int32_t *idx_in;
+    int32_t *idx_out;
+    Groups gr;
+    bool emit_sel, want_select;
+    int sel_slot, part_slot, list_slot;
+};
 
-    sp.sel = a.sel;
-    sp.idx_in = idx_in;
-    sp.lengths = lengths;
-    sp.idx_out = idx_out;
-    sp.batch = s.batch;
-    sp.n_kv_heads = s.n_kv_heads;
-    sp.k = s.k;
-    sp.max_len = s.max_len;
-    sp.sel_stride = w.sel_stride;
-    sp.n_rgroups = a.n_rgroups;
-    lp.do_select = mask != nullptr && idx_out != nullptr;
+struct Planner {
+    const lychee_ctx *ctx;
+    const lychee_shape &s;
+    const Workspace &w;
+    char *ws;
+    const int32_t *lengths;
+
+    LaunchPlan blank() const
+    {
+        LaunchPlan p;
+        memset(&p, 0, sizeof p);
+        Common &c = p.c;
+        c.lengths = lengths;
+        c.stride_b = s.kv_stride_batch;
+        c.stride_h = s.kv_stride_head;
+        c.stride_t = s.kv_stride_tok;
+        c.batch = s.batch;
+        c.n_q_heads = s.n_q_heads;
+        c.n_kv_heads = s.n_kv_heads;
+        c.group = s.n_q_heads / s.n_kv_heads;
+        c.k = s.k;
+        c.max_len = s.max_len;
+        c.sel_stride = w.sel_stride;
+        c.list_cap = w.list_cap;
+        int n_wg = ctx->n_wg > 0 ? ctx->n_wg : ctx->n_cu * ctx->wg_per_cu;
+        c.n_wg = n_wg > kWsWg ? kWsWg : n_wg;
+        c.part_stride = kWsWg;
+        c.g_block_rows = ctx->g_block_rows;
+        c.cost_s2 = ctx->cost_s2;
+        c.cost_c = ctx->cost_c;
+        c.cost_s1 = ctx->cost_s1;
+        c.scale = (float)(1.0 / sqrt((double)kHeadDim));
+        c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
+        return p;
+    }
+    float *part_o(int slot) const { return reinterpret_cast<float *>(ws + w.part_o_off[slot]); }
+    float *part_ml(int slot) const { return reinterpret_cast<float *>(ws + w.part_ml_off[slot]); }
+    int32_t *part_count(int slot) const { return reinterpret_cast<int32_t *>(ws + w.part_count_off[slot]); }
+    float *sel(int slot) const { return reinterpret_cast<float *>(ws + w.sel_off[slot]); }
+
+    void add_r(LaunchPlan &p, const LayerIo &io) const
+    {
+        if (io.gr.n_rgroups == 0) return;
+        RPart &r = p.r;
+        r.enabled = 1;
+        r.q = static_cast<const uint16_t *>(io.q);
+        r.k_cache = static_cast<const uint16_t *>(io.k_cache);
+        r.v_cache = static_cast<const uint16_t *>(io.v_cache);
+        r.sel = sel(io.sel_slot);
+        r.part_o = part_o(io.part_slot);
+        r.part_ml = part_ml(io.part_slot);
+        r.part_count = part_count(io.part_slot);
+        r.n_rgroups = io.gr.n_rgroups;
+        r.emit_sel = io.emit_sel ? 1 : 0;
+        memcpy(r.rgroup, io.gr.rgroup, sizeof r.rgroup);
+        memcpy(r.rmask, io.gr.rmask, sizeof r.rmask);
+    }
+    void add_g(LaunchPlan &p, const LayerIo &io) const
+    {
+        if (io.gr.n_sgroups == 0) return;
+        GPart &g = p.g;
+        g.enabled = 1;
+        g.q = static_cast<const uint16_t *>(io.q);
+        g.k_cache = static_cast<const uint16_t *>(io.k_cache);
+        g.v_cache = static_cast<const uint16_t *>(io.v_cache);
+        g.idx = io.idx_in;
+        g.part_o = part_o(io.part_slot);
+        g.part_ml = part_ml(io.part_slot);
+        g.part_count = part_count(io.part_slot);
+        g.n_sgroups = io.gr.n_sgroups;
+        memcpy(g.sgroup, io.gr.sgroup, sizeof g.sgroup);
+        memcpy(g.rmask, io.gr.rmask, sizeof g.rmask);
+    }
+    void add_c(LaunchPlan &p, const LayerIo &io) const
+    {
+        CPart &c = p.comb;
+        c.enabled = 1;
+        c.part_o = part_o(io.part_slot);
+        c.part_ml = part_ml(io.part_slot);
+        c.part_count = part_count(io.part_slot);
+        c.out = static_cast<uint16_t *>(io.out);
+    }
+    void add_s1(LaunchPlan &p, const LayerIo &io) const
+    {
+        if (!io.want_select || io.gr.n_rgroups == 0) return;
+        S1Part &a = p.s1;
+        a.enabled = 1;
+        a.sel = sel(io.sel_slot);
+        a.list = reinterpret_cast<uint2 *>(ws + w.list_off[io.list_slot]);
+        a.list_count = reinterpret_cast<int32_t *>(ws + w.list_count_off[io.list_slot]);
+        a.n_rgroups = io.gr.n_rgroups;
+    }
+    void add_s2(LaunchPlan &p, const LayerIo &io) const
+    {
+        if (!io.want_select) return;
+        S2Part &a = p.s2;
+        a.enabled = 1;
+        a.sel = sel(io.sel_slot);
+        a.list = reinterpret_cast<const uint2 *>(ws + w.list_off[io.list_slot]);
+        a.list_count = reinterpret_cast<const int32_t *>(ws + w.list_count_off[io.list_slot]);
+        a.idx_in = io.idx_in;
+        a.idx_out = io.idx_out;
+        a.n_rgroups = io.gr.n_rgroups;
+        memcpy(a.rindex, io.gr.rindex, sizeof a.rindex);
+    }
+};
+
+bool is_empty(const LaunchPlan &p)
+{
+    return !p.r.enabled && !p.g.enabled && !p.comb.enabled && !p.s1.enabled && !p.s2.enabled;
+}
+
+int launch_class(const LaunchPlan &p)
+{
+    if (p.r.enabled || p.g.enabled) return LYCHEE_KERNEL_ATTN;
+    if (p.comb.enabled || p.s1.enabled) return LYCHEE_KERNEL_COMBINE;
+    return LYCHEE_KERNEL_SELECT;
 }
 
 hipEvent_t take_event(lychee_ctx *ctx)
@@ -184,31 +265,34 @@ hipEvent_t take_event(lychee_ctx *ctx)
     return e;
 }
 
-template <typename F>
-hipError_t timed(lychee_ctx *ctx, int cls, hipStream_t stream, F &&launch)
+int submit(lychee_ctx *ctx, const LaunchPlan &p, hipStream_t stream)
 {
-    if (!ctx->timing) return launch();
-    lychee_ctx::Rec r{cls, take_event(ctx), take_event(ctx)};
-    if (r.start == nullptr || r.stop == nullptr) return hipErrorOutOfMemory;
-    hipError_t e = hipEventRecord(r.start, stream);
-    if (e != hipSuccess) return e;
-    e = launch();
-    if (e != hipSuccess) return e;
-    e = hipEventRecord(r.stop, stream);
+    if (is_empty(p)) return LYCHEE_OK;
+    if (!ctx->timing) return launch_units(p, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
+    lychee_ctx::Rec r{launch_class(p), take_event(ctx), take_event(ctx)};
+    if (r.start == nullptr || r.stop == nullptr) return LYCHEE_EHIP;
+    if (hipEventRecord(r.start, stream) != hipSuccess) return LYCHEE_EHIP;
+    if (launch_units(p, stream) != hipSuccess) return LYCHEE_EHIP;
+    if (hipEventRecord(r.stop, stream) != hipSuccess) return LYCHEE_EHIP;
     ctx->recs.push_back(r);
-    return e;
+    return LYCHEE_OK;
 }
 
-int run_layer(lychee_ctx *ctx, const LayerPlan &lp, hipStream_t stream)
+// One layer, three dependent launches: R+G, then S1+C, then S2.
+int run_layer(lychee_ctx *ctx, const Planner &pl, const LayerIo &io, hipStream_t stream)
 {
-    if (timed(ctx, LYCHEE_KERNEL_ATTN, stream, [&] { return launch_attn_units(lp.attn, stream); }) != hipSuccess)
-        return LYCHEE_EHIP;
-    if (timed(ctx, LYCHEE_KERNEL_COMBINE, stream, [&] { return launch_combine(lp.comb, stream); }) != hipSuccess)
-        return LYCHEE_EHIP;
-    if (lp.do_select &&
-        timed(ctx, LYCHEE_KERNEL_SELECT, stream, [&] { return launch_select(lp.sel, stream); }) != hipSuccess)
-        return LYCHEE_EHIP;
-    return LYCHEE_OK;
+    LaunchPlan a = pl.blank();
+    pl.add_r(a, io);
+    pl.add_g(a, io);
+    int rc = submit(ctx, a, stream);
+    if (rc != LYCHEE_OK) return rc;
+    LaunchPlan b = pl.blank();
+    pl.add_s1(b, io);
+    pl.add_c(b, io);
+    if ((rc = submit(ctx, b, stream)) != LYCHEE_OK) return rc;
+    LaunchPlan c = pl.blank();
+    pl.add_s2(c, io);
+    return submit(ctx, c, stream);
 }
 
 int check_common(lychee_ctx *ctx, const lychee_shape *shape, const void *workspace,
@@ -305,10 +389,10 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
     if (idx_in == idx_out) return LYCHEE_EINVAL;
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const Workspace w = carve(*shape);
-    LayerPlan lp;
-    build_layer(ctx, *shape, w, static_cast<char *>(workspace), q, k_cache, v_cache,
-                head_type_mask, idx_in, out, idx_out, lengths, lp);
-    return run_layer(ctx, lp, static_cast<hipStream_t>(hip_stream));
+    const Planner pl{ctx, *shape, w, static_cast<char *>(workspace), lengths};
+    LayerIo io{q, k_cache, v_cache, out, idx_in, idx_out, make_groups(*shape, head_type_mask),
+               true, true, 0, 0, 0};
+    return run_layer(ctx, pl, io, static_cast<hipStream_t>(hip_stream));
 }
 
 int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
@@ -325,10 +409,10 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
         return LYCHEE_EINVAL;
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const Workspace w = carve(*shape);
-    LayerPlan lp;
-    build_layer(ctx, *shape, w, static_cast<char *>(workspace), q, k_cache, v_cache, nullptr,
-                nullptr, out, nullptr, lengths, lp);
-    return run_layer(ctx, lp, static_cast<hipStream_t>(hip_stream));
+    const Planner pl{ctx, *shape, w, static_cast<char *>(workspace), lengths};
+    LayerIo io{q, k_cache, v_cache, out, nullptr, nullptr, make_groups(*shape, nullptr),
+               false, false, 0, 0, 0};
+    return run_layer(ctx, pl, io, static_cast<hipStream_t>(hip_stream));
 }
 
 int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
@@ -358,19 +442,43 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const Workspace w = carve(*shape);
     char *ws = static_cast<char *>(workspace);
-    int32_t *buf[2] = {reinterpret_cast<int32_t *>(ws + w.idx_a_off),
-                       reinterpret_cast<int32_t *>(ws + w.idx_b_off)};
+    const Planner pl{ctx, *shape, w, ws, lengths};
+    int32_t *buf[2] = {reinterpret_cast<int32_t *>(ws + w.idx_off[0]),
+                       reinterpret_cast<int32_t *>(ws + w.idx_off[1])};
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int32_t *cur_in = idx_in;
-    for (int l = 0; l < n_layers; ++l) {
-        int32_t *cur_out = (l == n_layers - 1 && idx_out != nullptr) ? idx_out : buf[l & 1];
-        LayerPlan lp;
-        build_layer(ctx, *shape, w, ws, q[l], k_cache[l], v_cache[l],
-                    head_type_masks + (size_t)l * shape->n_q_heads, cur_in, out[l], cur_out, lengths, lp);
-        if (l == n_layers - 1 && idx_out == nullptr) lp.do_select = false;
-        rc = run_layer(ctx, lp, stream);
-        if (rc != LYCHEE_OK) return rc;
-        cur_in = cur_out;
+
+    // layer l reads the sets idx(l) and writes idx(l+1); idx(0) = idx_in, idx(n) = idx_out
+    auto sets_of = [&](int l) -> int32_t * {
+        if (l == n_layers && idx_out != nullptr) return idx_out;
+        return buf[l & 1];
+    };
+    auto io_of = [&](int l) {
+        const bool want = l < n_layers - 1 || idx_out != nullptr;
+        return LayerIo{q[l], k_cache[l], v_cache[l], out[l],
+                       l == 0 ? idx_in : sets_of(l), sets_of(l + 1),
+                       make_groups(*shape, head_type_masks + (size_t)l * shape->n_q_heads),
+                       want, want, l % kSelRing, l % kPartRing, l % kListRing};
+    };
+    if (!ctx->pipeline) {
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = run_layer(ctx, pl, io_of(l), stream)) != LYCHEE_OK) return rc;
+        return LYCHEE_OK;
+    }
+    // Software pipeline over launches t: the streaming of layer t shares a launch with the
+    // select phases, the gather and the combine of earlier layers, whose inputs were all
+    // written by earlier launches:
+    //   R(t)  |  S1(t-1)  |  S2(t-2), G(t-2)  |  C(t-3)
+    // G(l) needs the sets S2(l-1) wrote one launch before; C(l) needs R(l) and G(l).
+    for (int t = 0; t < n_layers + 3; ++t) {
+        LaunchPlan p = pl.blank();
+        if (t < n_layers) pl.add_r(p, io_of(t));
+        if (t - 1 >= 0 && t - 1 < n_layers) pl.add_s1(p, io_of(t - 1));
+        if (t - 2 >= 0 && t - 2 < n_layers) {
+            pl.add_s2(p, io_of(t - 2));
+            pl.add_g(p, io_of(t - 2));
+        }
+        if (t - 3 >= 0 && t - 3 < n_layers) pl.add_c(p, io_of(t - 3));
+        if ((rc = submit(ctx, p, stream)) != LYCHEE_OK) return rc;
     }
     return LYCHEE_OK;
 }
@@ -397,19 +505,37 @@ int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_
     return LYCHEE_OK;
 }
 
-int lychee_set_unit_rows(lychee_ctx *ctx, int32_t retrieval_rows, int32_t sparse_rows)
+int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
 {
-    if (ctx == nullptr || retrieval_rows < 0 || sparse_rows < 0) return LYCHEE_EINVAL;
-    auto fix = [](int32_t v, int32_t hi) {
-        if (v == 0) return 0;
-        int64_t r = round_up(v, 64);
-        if (r < kMinUnitRows) r = kMinUnitRows;
-        if (r > hi) r = hi;
-        return (int32_t)r;
-    };
-    ctx->unit_r = fix(retrieval_rows, kMaxUnitRows);
-    ctx->unit_s = fix(sparse_rows, kMaxSparseUnit);
-    return LYCHEE_OK;
+    if (ctx == nullptr) return LYCHEE_EINVAL;
+    switch (option) {
+    case LYCHEE_OPT_WG_PER_CU:
+        if (value < 1 || value > 3) return LYCHEE_EINVAL;
+        ctx->wg_per_cu = value;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_PIPELINE:
+        ctx->pipeline = value != 0;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_N_WG:
+        if (value < 0 || value > kWsWg) return LYCHEE_EINVAL;
+        ctx->n_wg = value;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_GATHER_BLOCK:
+        if (value < 16 || value > 128 || value % 16) return LYCHEE_EINVAL;
+        ctx->g_block_rows = value;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_COST_S2:
+    case LYCHEE_OPT_COST_C:
+    case LYCHEE_OPT_COST_S1:
+        if (value < 0 || value > 4096) return LYCHEE_EINVAL;
+        (option == LYCHEE_OPT_COST_S2 ? ctx->cost_s2 : option == LYCHEE_OPT_COST_C ? ctx->cost_c : ctx->cost_s1) = value;
+        // the kernel's balancing needs costs that do not increase from S2 to C to S1
+        if (ctx->cost_c > ctx->cost_s2) ctx->cost_c = ctx->cost_s2;
+        if (ctx->cost_s1 > ctx->cost_c) ctx->cost_s1 = ctx->cost_c;
+        return LYCHEE_OK;
+    default:
+        return LYCHEE_EINVAL;
+    }
 }
 
 int lychee_timing_enable(lychee_ctx *ctx, int on)
@@ -467,7 +593,7 @@ const char *lychee_strerror(int code)
     switch (code) {
     case LYCHEE_OK: return "ok";
     case LYCHEE_EINVAL: return "invalid argument";
-    case LYCHEE_EUNSUPPORTED: return "unsupported shape (head_dim must be 128, at most 4 query heads per KV head, at most 64 KV heads)";
+    case LYCHEE_EUNSUPPORTED: return "unsupported shape (head_dim must be 128, at most 4 query heads per KV head, at most 64 KV heads, batch at most 256)";
     case LYCHEE_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LYCHEE_EHIP: return "HIP runtime error";
     default: return "unknown error";

@@ -1,0 +1,1108 @@
+// The work-unit kernel of liblychee for gfx950 (CDNA4).
+//
+// One launch runs a pooled list of work for a fixed grid of workgroups (about two per CU):
+//   R  retrieval streaming   Eq. 1, o = A V and the pooled selection score ranked by Eq. 2
+//   G  sparse gather         Eq. 3 on the inherited set
+//   C  combine               log-sum-exp merge of a head's partials into its bf16 output
+//   S1 select, phase 1       threshold from a sample of the scores, ordered filter into a list
+//   S2 select, phase 2       exact radix select over the list (ties to the lower position),
+//                            ordered write of the set; verbatim copy for groups that keep theirs
+// The parts of one launch are mutually independent (they may belong to different layers of a
+// decode step); everything that depends on another part's result runs in a later launch, so
+// there are no device-side waits, fences or atomics on global memory.
+//
+// Pooling (App. C describes pooling full and sparse block work into uniform splits).  The R
+// and G rows of a launch form one row space cut into 64-row blocks.  Every workgroup first
+// runs its few small units (C, S1, S2: distributed round-robin, most expensive first), then
+// an equal share of the pooled blocks, reduced by the cost of its small units, so that all
+// workgroups finish together.  A share is a contiguous run of blocks and may cross from one
+// (sequence, KV head) segment into the next; each (workgroup, segment) piece leaves one
+// partial per head in a slot that depends only on the shapes, never on timing.
+//
+// Data path of R and G.  Cache rows go from HBM to registers with 16-byte nontemporal loads:
+// a 64-lane wavefront covers 4 rows per load instruction (16 lanes x 16 bytes = one 256-byte
+// row) and 16 rows (K and V) per tile; a small ring of tiles keeps about one tile of loads in
+// flight per wavefront, which is what saturates a CU's share of HBM bandwidth on this chip
+// (deeper queues were measured to be slower).  A row is used by all heads of the GQA group
+// from registers, so no K/V staging in LDS is needed.  Scores use the packed-bf16 dot
+// instruction with fp32 accumulation; the 16 lanes of a row are summed by a fixed DPP
+// butterfly, so a key row's score has the same bits wherever it is processed and exact ties
+// stay exact ties.
+#include "lychee_internal.h"
+
+namespace lychee {
+namespace {
+
+// ------------------------------------------------------------------------------ LDS layout
+struct SharedAttn {
+    int32_t idx_s[kIdxChunk];
+    float red_o[kWaves * kMaxGroup * kHeadDim];
+    float red_ml[kWaves * kMaxGroup * 2];
+};
+struct SharedSelect {
+    uint32_t hist[4096];
+    int32_t slice_pre[kSlices + 1];
+    uint32_t found[2];
+};
+struct SharedCombine {
+    float w[kMaxWg];
+    float red[(kThreads / 32) * kHeadDim];
+};
+union SharedUnit {
+    SharedAttn attn;
+    SharedSelect sel;
+    SharedCombine comb;
+};
+struct SharedPool {
+    int32_t a[kMaxWg + 1];        // first pooled block of every workgroup
+    int32_t bpre[kMaxBatch + 1];  // first pooled block of every sequence
+    int32_t len[kMaxBatch];
+    uint32_t scan[kWaves + 1];
+    float fred[kWaves + 1];
+};
+
+// ------------------------------------------------------------------------------ primitives
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float x)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kCtrl, 0xF, 0xF, false));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the same bits.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_f32<0xB1>(x);   // quad_perm [1,0,3,2]  : lane ^ 1
+    x += dpp_f32<0x4E>(x);   // quad_perm [2,3,0,1]  : lane ^ 2
+    x += dpp_f32<0x141>(x);  // row_half_mirror      : the other quad of the 8-lane half
+    x += dpp_f32<0x140>(x);  // row_mirror           : the other half of the 16-lane row
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xFFFF0000u); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// 16-byte streaming load: cache rows are read once per step and never again.
+__device__ __forceinline__ uint4 load_stream16(const uint16_t *p)
+{
+    const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+__device__ __forceinline__ uint32_t ordered_key(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int clamp_len(int L, int max_len) { return L < 1 ? 1 : (L > max_len ? max_len : L); }
+
+// Inclusive prefix sum over the 256 threads of the workgroup; `total` = sum of all.
+__device__ __forceinline__ uint32_t block_scan(uint32_t v, uint32_t *wave_tot, uint32_t &total)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();  // wave_tot may still be read by the previous call
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = wave_tot[w];
+        before += (w < wave) ? t : 0u;
+        all += t;
+    }
+    total = all;
+    return x + before;
+}
+
+__device__ __forceinline__ float block_max(float v, float *scratch)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, scratch[w]);
+    return r;
+}
+
+__device__ __forceinline__ float block_sum(float v, float *scratch)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r += scratch[w];
+    return r;
+}
+
+#ifdef LYCHEE_TRACE
+__device__ unsigned long long g_trace[kMaxWg * 8];
+__device__ int g_trace_on = 1;
+#define TRACE(slot) do { if (threadIdx.x == 0 && g_trace_on) g_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define TRACE(slot) do { } while (0)
+#endif
+
+// ------------------------------------------------------------------------------ R and G
+struct Tile {
+    uint4 k[4];
+    uint4 v[4];
+    int valid;  // bit j: row slot j of this lane holds a real row
+};
+
+// Per-wavefront running state of the online softmax, one copy per row slot (lane >> 4).
+template <int NH>
+struct Acc {
+    float o[NH][8];
+    float m[NH];  // running maximum, raw dot-product units
+    float l[NH];  // running sum of exp
+};
+
+template <int NH>
+__device__ __forceinline__ void consume_tile(const Tile &t, const uint4 (&qf)[NH], Acc<NH> &acc,
+                                             float c_log2e, float (&sel_sum)[4])
+{
+    float s[NH][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool ok = (t.valid >> j) & 1;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            float a = dot2_bf16(t.k[j].x, qf[h].x, 0.0f);
+            a = dot2_bf16(t.k[j].y, qf[h].y, a);
+            a = dot2_bf16(t.k[j].z, qf[h].z, a);
+            a = dot2_bf16(t.k[j].w, qf[h].w, a);
+            s[h][j] = row16_sum(a);
+        }
+        float pooled = s[0][j];
+#pragma unroll
+        for (int h = 1; h < NH; ++h) pooled += s[h][j];
+        sel_sum[j] = pooled;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) s[h][j] = ok ? s[h][j] : -INFINITY;
+    }
+
+    // Raise the running maxima only when some row beats them (rare after the first tiles).
+    bool grow = false;
+    float mx[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        mx[h] = fmaxf(fmaxf(s[h][0], s[h][1]), fmaxf(s[h][2], s[h][3]));
+        grow |= mx[h] > acc.m[h];
+    }
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const float m_new = fmaxf(acc.m[h], mx[h]);
+            const float alpha = fast_exp2((acc.m[h] - m_new) * c_log2e);
+            acc.m[h] = m_new;
+            acc.l[h] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc.o[h][e] *= alpha;
+        }
+    }
+
+    float p[NH][4];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        const float mc = -acc.m[h] * c_log2e;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            p[h][j] = fast_exp2(fmaf(s[h][j], c_log2e, mc));
+            acc.l[h] += p[h][j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t w[4] = {t.v[j].x, t.v[j].y, t.v[j].z, t.v[j].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float v0 = bf16_lo(w[i]), v1 = bf16_hi(w[i]);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                acc.o[h][2 * i] = fmaf(p[h][j], v0, acc.o[h][2 * i]);
+                acc.o[h][2 * i + 1] = fmaf(p[h][j], v1, acc.o[h][2 * i + 1]);
+            }
+        }
+    }
+}
+
+#ifndef LYCHEE_RING_DEPTH
+#define LYCHEE_RING_DEPTH 2
+#endif
+
+// Streams rows [r0, r1) of one segment through the accumulators.  GATHER = false: cache rows
+// r0..r1-1; true: the cache rows named by set entries r0..r1-1, staged in idx_s[0 .. r1-r0).
+template <int NH, bool GATHER>
+__device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kbase,
+                                            const uint16_t *vbase, const uint4 (&qf)[NH],
+                                            Acc<NH> &acc, int L, int r0, int r1,
+                                            const int32_t *idx_s, float *sel_row, float sel_mul)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rs = lane >> 4;  // row slot: which of the 4 rows of a load this lane is in
+    const int ch = lane & 15;  // 16-byte chunk of the 256-byte row
+    // A tile is kBlockRows consecutive rows shared by the wavefronts: load j of wavefront w
+    // covers rows 4*(kWaves*j + w) .. +3 of the tile, so that the workgroup's load j reads
+    // kWaves KiB of contiguous memory.
+    const int n_mine = (r1 - r0 + kBlockRows - 1) / kBlockRows;
+    const float c_log2e = c.scale_log2e;
+
+    auto issue = [&](Tile &t, int tile) {
+        const int base = r0 + tile * kBlockRows + 4 * wave;
+        t.valid = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = base + 4 * kWaves * j + rs;
+            int row;
+            bool ok;
+            if (GATHER) {
+                const int tpos = (r < r1) ? idx_s[r - r0] : -1;
+                ok = (tpos >= 0) && (tpos < L);
+                row = ok ? tpos : 0;
+            } else {
+                ok = r < r1;
+                row = ok ? r : (r1 > 0 ? r1 - 1 : 0);
+            }
+            t.valid |= (ok ? 1 : 0) << j;
+            const int64_t off = (int64_t)row * c.stride_t + ch * 8;
+            t.k[j] = load_stream16(kbase + off);
+            t.v[j] = load_stream16(vbase + off);
+        }
+    };
+    auto consume = [&](const Tile &t, int tile) {
+        float sel_sum[4];
+#ifdef LYCHEE_PROBE_NOCOMPUTE
+        {   // probe build only: touch the loaded data and nothing else
+            uint32_t x = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x ^= t.k[j].x ^ t.k[j].y ^ t.k[j].z ^ t.k[j].w ^ t.v[j].x ^ t.v[j].y ^ t.v[j].z ^ t.v[j].w;
+            acc.o[0][0] += __builtin_bit_cast(float, x & 0x3F800000u);
+            sel_sum[0] = sel_sum[1] = sel_sum[2] = sel_sum[3] = acc.o[0][0];
+        }
+#else
+        consume_tile<NH>(t, qf, acc, c_log2e, sel_sum);
+#endif
+        if (!GATHER && sel_row != nullptr) {
+            // lane ch (< 4) of each row slot stores the score of this lane's row of load ch
+            float mine = sel_sum[0];
+            mine = (ch == 1) ? sel_sum[1] : mine;
+            mine = (ch == 2) ? sel_sum[2] : mine;
+            mine = (ch == 3) ? sel_sum[3] : mine;
+            const int r = r0 + tile * kBlockRows + 4 * wave + 4 * kWaves * ch + rs;
+            if (ch < 4 && r < r1) sel_row[r] = mine * sel_mul + 0.0f;  // +0 turns -0 into +0
+        }
+    };
+
+    // Loads are issued unconditionally (a tile past the end re-reads the segment's last row
+    // and is marked invalid): a conditional refill would make the ring registers loop-carried
+    // through a copy that has to wait for its load.
+    constexpr int kDepth = LYCHEE_RING_DEPTH;
+    Tile ring[kDepth];
+    if (n_mine == 0) return;
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) issue(ring[d], d);
+    TRACE(5);
+    for (int i = 0; i < n_mine; i += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (i + d < n_mine) consume(ring[d], i + d);
+            if (i == 0 && d == 0) TRACE(6);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(ring[d], i + d + kDepth);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// One (workgroup, segment) piece: rows/entries [r0, r1) of segment (b, g) for the heads in
+// hmask.  Leaves one un-normalised partial per head in `slot`; the piece that ends the
+// segment also records how many slots the segment has.
+template <int NH, bool GATHER>
+__device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, const uint16_t *k_cache,
+                                          const uint16_t *v_cache, const int32_t *idx_src,
+                                          float *sel_row, float *part_o, float *part_ml,
+                                          int32_t *part_count, int b, int g, uint32_t hmask, int L,
+                                          int r0, int r1, int slot, bool ends_segment,
+                                          SharedAttn &sh)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rs = lane >> 4;
+    const int ch = lane & 15;
+
+    int heads[NH];
+    {
+        uint32_t mk = hmask;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const int bit = __builtin_ctz(mk);
+            mk &= mk - 1;
+            heads[h] = g * c.group + bit;
+        }
+    }
+    uint4 qf[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+        qf[h] = reinterpret_cast<const uint4 *>(q + ((int64_t)b * c.n_q_heads + heads[h]) * kHeadDim)[ch];
+
+    Acc<NH> acc;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        acc.m[h] = kMinusBig;
+        acc.l[h] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc.o[h][e] = 0.0f;
+    }
+    const uint16_t *kbase = k_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
+    const uint16_t *vbase = v_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
+    const float sel_mul = c.scale / (float)NH;
+
+    if (GATHER) {
+        for (int e0 = r0; e0 < r1; e0 += kIdxChunk) {
+            const int e1 = e0 + kIdxChunk < r1 ? e0 + kIdxChunk : r1;
+            __syncthreads();  // the previous chunk's readers are done
+            for (int i = threadIdx.x; i < e1 - e0; i += kThreads) sh.idx_s[i] = idx_src[e0 + i];
+            __syncthreads();
+            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, nullptr, 0.0f);
+        }
+    } else {
+        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, sel_row, sel_mul);
+    }
+
+    TRACE(7);
+    // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).
+    const float c_log2e = c.scale_log2e;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        float mw = fmaxf(acc.m[h], __shfl_xor(acc.m[h], 16));
+        mw = fmaxf(mw, __shfl_xor(mw, 32));
+        const float a = fast_exp2((acc.m[h] - mw) * c_log2e);
+        acc.m[h] = mw;
+        float lw = acc.l[h] * a;
+        lw += __shfl_xor(lw, 16);
+        lw += __shfl_xor(lw, 32);
+        acc.l[h] = lw;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float ow = acc.o[h][e] * a;
+            ow += __shfl_xor(ow, 16);
+            ow += __shfl_xor(ow, 32);
+            acc.o[h][e] = ow;
+        }
+    }
+    // Merge the 4 wavefronts through LDS and write the piece's partial.
+    __syncthreads();  // red_o / idx_s readers of the previous piece are done
+    if (rs == 0) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            float *dst = sh.red_o + (wave * kMaxGroup + h) * kHeadDim + ch * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[e] = acc.o[h][e];
+            if (ch == 0) {
+                sh.red_ml[(wave * kMaxGroup + h) * 2 + 0] = acc.m[h];
+                sh.red_ml[(wave * kMaxGroup + h) * 2 + 1] = acc.l[h];
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < kHeadDim) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            float M = kMinusBig;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sh.red_ml[(w * kMaxGroup + h) * 2]);
+            float o = 0.0f, l = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float a = fast_exp2((sh.red_ml[(w * kMaxGroup + h) * 2] - M) * c_log2e);
+                o = fmaf(a, sh.red_o[(w * kMaxGroup + h) * kHeadDim + threadIdx.x], o);
+                l = fmaf(a, sh.red_ml[(w * kMaxGroup + h) * 2 + 1], l);
+            }
+            const int64_t bh = (int64_t)b * c.n_q_heads + heads[h];
+            const int64_t prow = bh * c.part_stride + slot;
+            part_o[prow * kHeadDim + threadIdx.x] = o;
+            if (threadIdx.x == 0) {
+                part_ml[prow * 2 + 0] = M;
+                part_ml[prow * 2 + 1] = l;
+                if (ends_segment) part_count[bh] = slot + 1;
+            }
+        }
+    }
+}
+
+template <bool GATHER>
+__device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const uint16_t *q,
+                                               const uint16_t *k_cache, const uint16_t *v_cache,
+                                               const int32_t *idx_src, float *sel_row, float *part_o,
+                                               float *part_ml, int32_t *part_count, int b, int g,
+                                               uint32_t hmask, int L, int r0, int r1, int slot,
+                                               bool ends_segment, SharedAttn &sh)
+{
+    switch (nh) {
+    case 1: run_piece<1, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    case 2: run_piece<2, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    case 3: run_piece<3, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    default: run_piece<4, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    }
+}
+
+// ------------------------------------------------------------------------------ C
+// out = (sum_s w_s o_s) / (sum_s w_s l_s),  w_s = 2^((m_s - M) log2(e)/sqrt(d)),  M = max_s m_s,
+// over the head's partial slots in ascending order (a fixed summation tree).
+__device__ __forceinline__ void combine_unit(const Common &c, const CPart &p, int bh, SharedCombine &sh,
+                                             SharedPool &pool)
+{
+    int count = p.part_count[bh];
+    count = count < 0 ? 0 : (count > c.part_stride ? c.part_stride : count);
+    const float *ml = p.part_ml + (int64_t)bh * c.part_stride * 2;
+    const float *po = p.part_o + (int64_t)bh * c.part_stride * kHeadDim;
+    float m_loc = kMinusBig;
+    for (int s = threadIdx.x; s < count; s += kThreads)
+        if (ml[2 * s + 1] > 0.0f) m_loc = fmaxf(m_loc, ml[2 * s]);
+    const float M = block_max(m_loc, pool.fred);
+    float l_loc = 0.0f;
+    for (int s = threadIdx.x; s < count; s += kThreads) {
+        const float ls = ml[2 * s + 1];
+        const float w = ls > 0.0f ? fast_exp2((ml[2 * s] - M) * c.scale_log2e) : 0.0f;
+        sh.w[s] = w;
+        l_loc = fmaf(w, ls, l_loc);
+    }
+    const float lsum = block_sum(l_loc, pool.fred);  // also publishes sh.w
+    constexpr int kLanes = kThreads / 32;  // interleaved slot subsets
+    const int lane8 = threadIdx.x >> 5;
+    const int c4 = threadIdx.x & 31;       // which 4 columns
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = lane8; s0 < count; s0 += 8 * kLanes) {
+        // 8 slots per thread and round, all loads issued before the first use
+        float wv[8];
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = s0 + kLanes * u;
+            wv[u] = s < count ? sh.w[s] : 0.0f;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (wv[u] > 0.0f) v[u] = reinterpret_cast<const float4 *>(po + (int64_t)s * kHeadDim)[c4];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            acc.x = fmaf(wv[u], v[u].x, acc.x);
+            acc.y = fmaf(wv[u], v[u].y, acc.y);
+            acc.z = fmaf(wv[u], v[u].z, acc.z);
+            acc.w = fmaf(wv[u], v[u].w, acc.w);
+        }
+    }
+    reinterpret_cast<float4 *>(sh.red + lane8 * kHeadDim)[c4] = acc;
+    __syncthreads();
+    if (threadIdx.x < kHeadDim) {
+        float o = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kLanes; ++i) o += sh.red[i * kHeadDim + threadIdx.x];
+        const float r = lsum > 0.0f ? o / lsum : 0.0f;
+        p.out[(int64_t)bh * kHeadDim + threadIdx.x] = f32_to_bf16_rne(r);
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------ S1 and S2
+__device__ __forceinline__ int slice_len_of(int L)
+{
+    const int per = (L + kSlices - 1) / kSlices;
+    return (per + kSliceQuantum - 1) / kSliceQuantum * kSliceQuantum;
+}
+
+// In the histogram of `n_bins` digits, finds the highest digit d whose suffix count
+// (keys with digit >= d) reaches `need`; returns d and need minus the count above d.
+template <int kBins>
+__device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t need, uint32_t *found,
+                                           uint32_t *scan_scratch, uint32_t &digit, uint32_t &rest)
+{
+    constexpr int per = kBins / kThreads;
+    uint32_t mine[per];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        mine[j] = hist[kBins - 1 - (threadIdx.x * per + j)];  // bins taken from the top
+        sum += mine[j];
+    }
+    uint32_t total;
+    uint32_t above = block_scan(sum, scan_scratch, total) - sum;
+    if (threadIdx.x == 0) {
+        found[0] = 0;      // need > total: every key qualifies
+        found[1] = need;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        if (above < need && need <= above + mine[j]) {
+            found[0] = (uint32_t)(kBins - 1 - (threadIdx.x * per + j));
+            found[1] = need - above;
+        }
+        above += mine[j];
+    }
+    __syncthreads();
+    digit = found[0];
+    rest = found[1];
+    __syncthreads();
+}
+
+// Phase 1 of the selection for slice `slice` of score row (b, rgi): a threshold T0 that keeps
+// somewhat more than n = min(k, L) scores is read off a histogram of a fixed sample of the
+// row (every slice derives the same T0); the slice's scores >= T0 are written, in position
+// order, as (ordered key, position) pairs.
+__device__ __forceinline__ void select1_unit(const Common &c, const S1Part &p, int b, int rgi, int slice,
+                                             SharedSelect &sh, SharedPool &pool)
+{
+    const int L = clamp_len(c.lengths[b], c.max_len);
+    const int n = c.k < L ? c.k : L;
+    const int64_t row = (int64_t)b * p.n_rgroups + rgi;
+    int32_t *count_out = p.list_count + row * kSlices + slice;
+    const int slen = slice_len_of(L);
+    const int s0 = slice * slen;
+    if (n == L || s0 >= L) {  // everything is selected, or the slice is empty
+        if (threadIdx.x == 0) *count_out = 0;
+        return;
+    }
+    const float *sel = p.sel + row * c.sel_stride;
+    // ---- threshold from the sample
+    for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
+    __syncthreads();
+    const int n_sample = L <= kSample ? L : kSample;
+    {
+        float sv[kSample / kThreads];
+#pragma unroll
+        for (int u = 0; u < kSample / kThreads; ++u) {
+            const int i = threadIdx.x + u * kThreads;
+            int pos = i;
+            if (L > kSample) pos = (int)(((int64_t)(i >> 6) * L / kSampleBlocks) & ~3ll) + (i & 63);
+            sv[u] = i < n_sample ? sel[pos] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kSample / kThreads; ++u)
+            if (threadIdx.x + u * kThreads < n_sample) atomicAdd(&sh.hist[ordered_key(sv[u]) >> 20], 1u);
+    }
+    __syncthreads();
+    uint32_t target;
+    if (L <= kSample) {
+        target = (uint32_t)n;
+    } else {
+        const float f = (float)n_sample * (float)n / (float)L;
+        target = (uint32_t)(f + 4.0f * sqrtf(f) + 8.0f);
+    }
+    uint32_t digit = 0, rest;
+    if (target < (uint32_t)n_sample) find_digit<4096>(sh.hist, target, sh.found, pool.scan, digit, rest);
+    const uint32_t t0 = digit << 20;
+    // ---- ordered filter of the slice
+    uint2 *dst = p.list + (row * kSlices + slice) * (int64_t)c.list_cap;
+    const int s1 = s0 + slen < L ? s0 + slen : L;
+    uint32_t base = 0;
+    const int n_it = (s1 - s0 + kThreads * 4 - 1) / (kThreads * 4);
+    for (int it0 = 0; it0 < n_it; it0 += 4) {
+        float4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
+            x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 < s1) x[u] = *reinterpret_cast<const float4 *>(sel + i0);  // rows are padded to 64
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (it0 + u < n_it) {
+                const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
+                const float xs[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+                uint32_t keys[4];
+                uint32_t pass = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    keys[j] = ordered_key(xs[j]);
+                    pass |= (uint32_t)(i0 + j < s1 && keys[j] >= t0) << j;
+                }
+                const uint32_t cnt = (uint32_t)__builtin_popcount(pass);
+                uint32_t total;
+                uint32_t at = base + block_scan(cnt, pool.scan, total) - cnt;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((pass >> j) & 1u) dst[at++] = make_uint2(keys[j], (uint32_t)(i0 + j));
+                base += total;
+            }
+        }
+    }
+    if (threadIdx.x == 0) *count_out = (int32_t)base;
+}
+
+constexpr int kS2Regs = 32;  // candidates one thread keeps in registers in the fast path
+
+// Radix select + ordered compaction straight from memory (any number of candidates).
+template <typename Fetch>
+__device__ __forceinline__ void select2_slow(const Common &c, int n, int total, Fetch &fetch, int32_t *dst,
+                                             SharedSelect &sh, SharedPool &pool)
+{
+    // ---- radix select: the n-th largest key
+    uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)n;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+        const int n_bins = pass == 0 ? 4096 : 1024;
+        const uint32_t digit_mask = (uint32_t)n_bins - 1u;
+        for (int i = threadIdx.x; i < n_bins; i += kThreads) sh.hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < total; i += kThreads) {
+            uint32_t key, pos;
+            fetch(i, key, pos);
+            if ((key & prefix_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+        }
+        __syncthreads();
+        uint32_t digit, rest;
+        if (pass == 0)
+            find_digit<4096>(sh.hist, need, sh.found, pool.scan, digit, rest);
+        else
+            find_digit<1024>(sh.hist, need, sh.found, pool.scan, digit, rest);
+        prefix |= digit << shift;
+        prefix_mask |= digit_mask << shift;
+        need = rest;
+    }
+    const uint32_t T = prefix;   // the n-th largest key
+    const uint32_t r_eq = need;  // how many keys == T are kept: those at the lowest positions
+
+    // ---- ordered compaction: keys > T, and the first r_eq keys == T, in position order
+    uint32_t base_gt = 0, base_eq = 0;
+    for (int t0 = 0; t0 < total; t0 += kThreads * 4) {
+        const int i0 = t0 + threadIdx.x * 4;
+        uint32_t gt = 0, eq = 0, poss[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i0 + j < total) {
+                uint32_t key;
+                fetch(i0 + j, key, poss[j]);
+                gt |= (uint32_t)(key > T) << j;
+                eq |= (uint32_t)(key == T) << j;
+            }
+        }
+        const uint32_t packed = (uint32_t)__builtin_popcount(gt) | ((uint32_t)__builtin_popcount(eq) << 16);
+        uint32_t tot;
+        const uint32_t excl = block_scan(packed, pool.scan, tot) - packed;
+        uint32_t n_gt = base_gt + (excl & 0xFFFFu);
+        uint32_t n_eq = base_eq + (excl >> 16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if ((gt >> j) & 1u) {
+                dst[n_gt + (n_eq < r_eq ? n_eq : r_eq)] = (int32_t)poss[j];
+                ++n_gt;
+            } else if ((eq >> j) & 1u) {
+                if (n_eq < r_eq) dst[n_gt + n_eq] = (int32_t)poss[j];
+                ++n_eq;
+            }
+        }
+        base_gt += tot & 0xFFFFu;
+        base_eq += tot >> 16;
+    }
+}
+
+// Phase 2 for KV head (b, g): exact top-n of the row from the filtered list (or from the raw
+// scores when the list is too short), ties to the lower position, written ascending.
+__device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, int b, int g,
+                                             SharedSelect &sh, SharedPool &pool)
+{
+    const int64_t bg = (int64_t)b * c.n_kv_heads + g;
+    int32_t *dst = p.idx_out + bg * c.k;
+    const int rgi = p.rindex[g];
+    if (rgi == 0xFF) {  // no retrieval head in the group: the set is handed on unchanged
+        const int32_t *src = p.idx_in + bg * c.k;
+        for (int i = threadIdx.x; i < c.k; i += kThreads) dst[i] = src[i];
+        return;
+    }
+    const int L = clamp_len(c.lengths[b], c.max_len);
+    const int n = c.k < L ? c.k : L;
+    if (n == L) {  // everything is selected
+        for (int i = threadIdx.x; i < c.k; i += kThreads) dst[i] = i < L ? i : -1;
+        return;
+    }
+    const int64_t row = (int64_t)b * p.n_rgroups + rgi;
+    const float *sel = p.sel + row * c.sel_stride;
+    const uint2 *list = p.list + row * kSlices * (int64_t)c.list_cap;
+    __syncthreads();
+    if (threadIdx.x < 64) {  // one slice count per lane, prefix sum inside the wavefront
+        int cnt = 0;
+        if (threadIdx.x < kSlices) {
+            cnt = p.list_count[row * kSlices + threadIdx.x];
+            cnt = cnt < 0 ? 0 : (cnt > c.list_cap ? c.list_cap : cnt);
+        }
+        int incl = cnt;
+#pragma unroll
+        for (int d = 1; d < kSlices; d <<= 1) {
+            const int y = __shfl_up(incl, d);
+            if ((int)threadIdx.x >= d) incl += y;
+        }
+        if (threadIdx.x < kSlices) sh.slice_pre[threadIdx.x + 1] = incl;
+        if (threadIdx.x == 0) sh.slice_pre[0] = 0;
+    }
+    __syncthreads();
+    int total = sh.slice_pre[kSlices];
+    const bool raw = total < n;  // the sampled threshold kept too few: rank the raw row
+    if (raw) total = L;
+    // element i of the candidate sequence (ascending by position in both cases)
+    auto fetch = [&](int i, uint32_t &key, uint32_t &pos) {
+        if (raw) {
+            key = ordered_key(sel[i]);
+            pos = (uint32_t)i;
+        } else {
+            int lo = 0;
+#pragma unroll
+            for (int step = kSlices / 2; step >= 1; step >>= 1)
+                if (sh.slice_pre[lo + step] <= i) lo += step;
+            const uint2 e = list[(int64_t)lo * c.list_cap + (i - sh.slice_pre[lo])];
+            key = e.x;
+            pos = e.y;
+        }
+    };
+
+    if (!raw && total <= kThreads * kS2Regs) {
+        // Fast path: thread t keeps candidates [t*per, (t+1)*per) in registers, loaded with
+        // all loads in flight at once; the passes then never touch global memory again.
+        const int per = (total + kThreads - 1) / kThreads;
+        uint32_t keys[kS2Regs], poss[kS2Regs];
+#pragma unroll
+        for (int e = 0; e < kS2Regs; ++e) {
+            const int i = threadIdx.x * per + e;
+            keys[e] = 0;
+            poss[e] = 0xFFFFFFFFu;  // marks "no candidate"
+            if (e < per && i < total) fetch(i, keys[e], poss[e]);
+        }
+        uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)n;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int n_bins = pass == 0 ? 4096 : 1024;
+            const uint32_t digit_mask = (uint32_t)n_bins - 1u;
+            for (int i = threadIdx.x; i < n_bins; i += kThreads) sh.hist[i] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < kS2Regs; ++e)
+                if (poss[e] != 0xFFFFFFFFu && (keys[e] & prefix_mask) == prefix)
+                    atomicAdd(&sh.hist[(keys[e] >> shift) & digit_mask], 1u);
+            __syncthreads();
+            uint32_t digit, rest;
+            if (pass == 0)
+                find_digit<4096>(sh.hist, need, sh.found, pool.scan, digit, rest);
+            else
+                find_digit<1024>(sh.hist, need, sh.found, pool.scan, digit, rest);
+            prefix |= digit << shift;
+            prefix_mask |= digit_mask << shift;
+            need = rest;
+        }
+        const uint32_t T = prefix, r_eq = need;
+        uint32_t cnt_gt = 0, cnt_eq = 0;
+#pragma unroll
+        for (int e = 0; e < kS2Regs; ++e) {
+            const bool have = poss[e] != 0xFFFFFFFFu;
+            cnt_gt += (uint32_t)(have && keys[e] > T);
+            cnt_eq += (uint32_t)(have && keys[e] == T);
+        }
+        const uint32_t packed = cnt_gt | (cnt_eq << 16);
+        uint32_t tot;
+        const uint32_t excl = block_scan(packed, pool.scan, tot) - packed;
+        uint32_t n_gt = excl & 0xFFFFu, n_eq = excl >> 16;
+#pragma unroll
+        for (int e = 0; e < kS2Regs; ++e) {
+            if (poss[e] == 0xFFFFFFFFu) continue;
+            if (keys[e] > T) {
+                dst[n_gt + (n_eq < r_eq ? n_eq : r_eq)] = (int32_t)poss[e];
+                ++n_gt;
+            } else if (keys[e] == T) {
+                if (n_eq < r_eq) dst[n_gt + n_eq] = (int32_t)poss[e];
+                ++n_eq;
+            }
+        }
+    } else {
+        select2_slow(c, n, total, fetch, dst, sh, pool);
+    }
+    for (int i = n + threadIdx.x; i < c.k; i += kThreads) dst[i] = -1;
+}
+
+// ------------------------------------------------------------------------------ the kernel
+__global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan P)
+{
+    __shared__ SharedUnit su;
+    __shared__ SharedPool pool;
+    const Common &c = P.c;
+    const int w = blockIdx.x;
+    const int W = c.n_wg;
+    TRACE(0);
+
+    // ---- small units: kinds in order of decreasing cost, unit j runs on workgroup j mod W
+    const int n_s2r = P.s2.enabled ? c.batch * P.s2.n_rgroups : 0;
+    const int n_c = P.comb.enabled ? c.batch * c.n_q_heads : 0;
+    const int n_s1 = P.s1.enabled ? c.batch * P.s1.n_rgroups * kSlices : 0;
+    const int n_s2c = P.s2.enabled ? c.batch * (c.n_kv_heads - P.s2.n_rgroups) : 0;
+    const int n_small = n_s2r + n_c + n_s1 + n_s2c;
+    for (int j = w; j < n_small; j += W) {
+        int u = j;
+        if (u < n_s2r) {  // u-th (sequence, retrieval group)
+            const int b = u / P.s2.n_rgroups;
+            int want = u % P.s2.n_rgroups, g = 0;
+            for (int gg = 0; gg < c.n_kv_heads; ++gg)
+                if (P.s2.rindex[gg] == want) g = gg;
+            select2_unit(c, P.s2, b, g, su.sel, pool);
+        } else if ((u -= n_s2r) < n_c) {
+            combine_unit(c, P.comb, u, su.comb, pool);
+        } else if ((u -= n_c) < n_s1) {
+            const int slice = u % kSlices;
+            const int rgi = (u / kSlices) % P.s1.n_rgroups;
+            const int b = u / (kSlices * P.s1.n_rgroups);
+            select1_unit(c, P.s1, b, rgi, slice, su.sel, pool);
+        } else {  // (u - n_s1)-th (sequence, group that keeps its set)
+            u -= n_s1;
+            const int n_keep = c.n_kv_heads - P.s2.n_rgroups;
+            const int b = u / n_keep;
+            int want = u % n_keep, g = 0;
+            for (int gg = 0; gg < c.n_kv_heads; ++gg)
+                if (P.s2.rindex[gg] == 0xFF && want-- == 0) g = gg;
+            select2_unit(c, P.s2, b, g, su.sel, pool);
+        }
+        __syncthreads();
+    }
+    TRACE(1);
+    if (!P.r.enabled && !P.g.enabled) return;
+
+    // ---- the pooled row space: per sequence, n_rgroups R segments then n_sgroups G segments
+    const int n_rg = P.r.enabled ? P.r.n_rgroups : 0;
+    const int n_sg = P.g.enabled ? P.g.n_sgroups : 0;
+    {
+        uint32_t blocks = 0;
+        if (threadIdx.x < c.batch) {
+            const int L = clamp_len(c.lengths[threadIdx.x], c.max_len);
+            pool.len[threadIdx.x] = L;
+            const int kk = c.k < L ? c.k : L;
+            blocks = (uint32_t)(n_rg * ((L + kBlockRows - 1) / kBlockRows) +
+                                n_sg * ((kk + c.g_block_rows - 1) / c.g_block_rows));
+        }
+        uint32_t total;
+        const uint32_t incl = block_scan(blocks, pool.scan, total);
+        if (threadIdx.x < c.batch) pool.bpre[threadIdx.x + 1] = (int32_t)incl;
+        if (threadIdx.x == 0) pool.bpre[0] = 0;
+    }
+    __syncthreads();
+    const int T = pool.bpre[c.batch];
+    {
+        // cost of the small units of this thread's kPer consecutive workgroups
+        // (non-increasing in the workgroup index)
+        constexpr int kPer = kMaxWg / kThreads;
+        uint32_t comp[kPer], comp_sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int ww = threadIdx.x * kPer + i;
+            comp[i] = 0;
+            if (ww < W)
+                for (int j = ww; j < n_small; j += W)
+                    comp[i] += j < n_s2r ? c.cost_s2 : (j < n_s2r + n_c ? c.cost_c : (j < n_s2r + n_c + n_s1 ? c.cost_s1 : 0));
+            comp_sum += comp[i];
+        }
+        uint32_t all_comp;
+        block_scan(comp_sum, pool.scan, all_comp);
+        const uint32_t base_share = ((uint32_t)T + all_comp + (uint32_t)W - 1u) / (uint32_t)W;
+        uint32_t share[kPer], share_sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int ww = threadIdx.x * kPer + i;
+            share[i] = (ww < W && base_share > comp[i]) ? base_share - comp[i] : 0u;
+            share_sum += share[i];
+        }
+        uint32_t dummy;
+        uint32_t at = block_scan(share_sum, pool.scan, dummy) - share_sum;
+        if (threadIdx.x == 0) pool.a[0] = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            at += share[i];
+            const int ww = threadIdx.x * kPer + i;
+            if (ww < kMaxWg) pool.a[ww + 1] = (int32_t)at;
+        }
+    }
+    __syncthreads();
+    int x = pool.a[w];
+    int x1 = pool.a[w + 1];
+    x1 = x1 < T ? x1 : T;
+    TRACE(2);
+
+    while (x < x1) {
+        int b = 0;
+        while (pool.bpre[b + 1] <= x) ++b;
+        const int L = pool.len[b];
+        const int kk = c.k < L ? c.k : L;
+        const int nb_r = (L + kBlockRows - 1) / kBlockRows;
+        const int nb_g = (kk + c.g_block_rows - 1) / c.g_block_rows;
+        int xo = x - pool.bpre[b];
+        const bool gather = xo >= n_rg * nb_r;
+        int gi, blk, nb, seg_rows, seg_start;
+        if (!gather) {
+            gi = xo / nb_r;
+            blk = xo % nb_r;
+            nb = nb_r;
+            seg_rows = L;
+            seg_start = pool.bpre[b] + gi * nb_r;
+        } else {
+            xo -= n_rg * nb_r;
+            gi = xo / nb_g;
+            blk = xo % nb_g;
+            nb = nb_g;
+            seg_rows = kk;
+            seg_start = pool.bpre[b] + n_rg * nb_r + gi * nb_g;
+        }
+        int len = x1 - x;
+        len = len < nb - blk ? len : nb - blk;
+        const int brows = gather ? c.g_block_rows : kBlockRows;
+        const int r0 = blk * brows;
+        int r1 = (blk + len) * brows;
+        r1 = r1 < seg_rows ? r1 : seg_rows;
+        // slot = distance to the first workgroup whose share reaches into this segment
+        int lo = 0, hi = W - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (pool.a[mid + 1] > seg_start) hi = mid; else lo = mid + 1;
+        }
+        const int slot = w - lo;
+        const bool ends = blk + len == nb;
+        const uint32_t gmask = (1u << c.group) - 1u;
+        if (!gather) {
+            const int g = P.r.rgroup[gi];
+            const uint32_t hmask = P.r.rmask[g] & gmask;
+            float *sel_row = P.r.emit_sel ? P.r.sel + ((int64_t)b * P.r.n_rgroups + gi) * c.sel_stride : nullptr;
+            dispatch_piece<false>(__builtin_popcount(hmask), c, P.r.q, P.r.k_cache, P.r.v_cache, nullptr,
+                                  sel_row, P.r.part_o, P.r.part_ml, P.r.part_count, b, g, hmask, L, r0, r1,
+                                  slot, ends, su.attn);
+        } else {
+            const int g = P.g.sgroup[gi];
+            const uint32_t hmask = ~(uint32_t)P.g.rmask[g] & gmask;
+            const int32_t *idx_src = P.g.idx + ((int64_t)b * c.n_kv_heads + g) * c.k;
+            dispatch_piece<true>(__builtin_popcount(hmask), c, P.g.q, P.g.k_cache, P.g.v_cache, idx_src,
+                                 nullptr, P.g.part_o, P.g.part_ml, P.g.part_count, b, g, hmask, L, r0, r1,
+                                 slot, ends, su.attn);
+        }
+        x += len;
+        TRACE(3);
+    }
+    TRACE(4);
+}
+
+// ------------------------------------------------------------------------------ helpers
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4_t *src, size_t n_vec, uint32_t *sink)
+{
+    // every workgroup streams one contiguous share with 8 nontemporal 16-byte loads in flight
+    const size_t share = (n_vec / gridDim.x) / (256 * 8) * (256 * 8);
+    const u32x4_t *p = src + (size_t)blockIdx.x * share + threadIdx.x;
+    uint32_t acc = 0;
+    for (size_t r = 0; r < share; r += 256 * 8) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + r + (size_t)u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x9E3779B9u) *sink = acc;  // practically never: keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(uint4 *dst, const uint4 *src, size_t n_vec)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+__global__ void validate_idx_kernel(const int32_t *idx, const int32_t *lengths, int32_t n_kv_heads,
+                                    int32_t k, int32_t max_len, unsigned long long *n_bad)
+{
+    // one workgroup per (sequence, KV head); quadratic duplicate check, debug use only
+    const int bg = blockIdx.x;
+    const int b = bg / n_kv_heads;
+    const int L = clamp_len(lengths[b], max_len);
+    const int32_t *row = idx + (int64_t)bg * k;
+    unsigned long long bad = 0;
+    for (int i = threadIdx.x; i < k; i += blockDim.x) {
+        const int32_t t = row[i];
+        if (t < 0) {
+            if (t != -1) ++bad;
+            continue;
+        }
+        if (t >= L) ++bad;
+        if (i > 0 && row[i - 1] < 0) ++bad;  // a valid entry after padding
+        for (int j = 0; j < i; ++j)
+            if (row[j] == t) {
+                ++bad;
+                break;
+            }
+    }
+    if (bad) atomicAdd(n_bad, bad);
+}
+
+}  // namespace
+
+#ifdef LYCHEE_TRACE
+extern "C" int lychee_trace_read(unsigned long long *host, int n_wg)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * n_wg) == hipSuccess ? 0 : -4;
+}
+#endif
+
+hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
+{
+    if (plan.c.n_wg < 1 || plan.c.n_wg > kMaxWg) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(lychee_units_kernel, dim3(plan.c.n_wg), dim3(kThreads), 0, stream, plan);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_idx(const int32_t *idx, const int32_t *lengths, int32_t batch,
+                               int32_t n_kv_heads, int32_t k, int32_t max_len,
+                               unsigned long long *n_bad, hipStream_t stream)
+{
+    hipLaunchKernelGGL(validate_idx_kernel, dim3(batch * n_kv_heads), dim3(256), 0, stream, idx,
+                       lengths, n_kv_heads, k, max_len, n_bad);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t stream)
+{
+    const size_t n_vec = bytes / 16;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(512), dim3(256), 0, stream,
+                       static_cast<const u32x4_t *>(src), n_vec, static_cast<uint32_t *>(sink));
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t stream)
+{
+    const size_t n_vec = bytes / 16;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(256), 0, stream,
+                       static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), n_vec);
+    return hipGetLastError();
+}
+
+}  // namespace lychee

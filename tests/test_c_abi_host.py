@@ -39,6 +39,7 @@ def test_shape_validation(lb):
     assert lb.check_shape(lb.make_shape(1, 64, 8, 1024, 16)) == lb.EUNSUPPORTED     # 8 q heads per KV head
     assert lb.check_shape(lb.make_shape(1, 30, 8, 1024, 16)) == lb.EINVAL           # not a multiple
     assert lb.check_shape(lb.make_shape(0, 32, 8, 1024, 16)) == lb.EINVAL
+    assert lb.check_shape(lb.make_shape(257, 32, 8, 1024, 16)) == lb.EUNSUPPORTED
     assert lb.check_shape(lb.make_shape(1, 32, 8, 1024, 0)) == lb.EINVAL            # k < 1
     assert lb.check_shape(lb.make_shape(1, 32, 8, 0, 16)) == lb.EINVAL
     assert lb.check_shape(lb.make_shape(1, 32, 8, 1024, 16, strides=(8 * 1024 * 128, 1024 * 128, 64))) == lb.EINVAL
@@ -66,7 +67,7 @@ def test_workspace_size(lb):
     assert small % 256 == 0 and big % 256 == 0
     # selection scores alone need B * H_kv * L * 4 bytes
     assert big >= 8 * 131072 * 4
-    assert big < 64 * 2 ** 20
+    assert big < 256 * 2 ** 20
 
 
 def test_error_strings(lb):
@@ -79,8 +80,8 @@ def test_error_strings(lb):
 def test_calls_reject_null_context_without_touching_a_gpu(lb):
     lib = ctypes.CDLL(lb.LIB_PATH)
     s = lb.make_shape(1, 8, 2, 4096, 256)
-    lib.lychee_set_unit_rows.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32]
-    assert lib.lychee_set_unit_rows(None, 0, 0) == lb.EINVAL
+    lib.lychee_set_option.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32]
+    assert lib.lychee_set_option(None, lb.OPT_WG_PER_CU, 2) == lb.EINVAL
     lib.lychee_dense_decode_attn.argtypes = lb._lib.lychee_dense_decode_attn.argtypes
     assert lib.lychee_dense_decode_attn(None, ctypes.byref(s), None, None, None, None, None, None, 0, None) == lb.EINVAL
 

@@ -176,7 +176,8 @@ def test_sparse_with_full_set_equals_dense_kernel(ctx):
 
 
 # ------------------------------------------------------------------ splits and determinism
-def test_result_does_not_depend_on_the_split_size_and_is_deterministic(ctx):
+def test_result_does_not_depend_on_the_grid_size_and_is_deterministic(ctx):
+    lb = H.binding()
     w = wl.scaled(wl.WORKLOADS["c1"], max_len=5000, k=700, planted=16)
     inp = wl.make_layer(w, l_cap=5000)
     idx_in = H.previous_layer_sets(inp, w.k)
@@ -184,14 +185,19 @@ def test_result_does_not_depend_on_the_split_size_and_is_deterministic(ctx):
     dl = H.DeviceLayer(inp, w.k, idx_in)
     results = []
     try:
-        for rows in [(0, 0), (128, 128), (320, 192), (8192, 2048), (0, 0)]:
-            ctx.set_unit_rows(*rows)
+        for wg_per_cu, costs in [(2, (3, 1, 1)), (1, (3, 1, 1)), (3, (0, 0, 0)), (2, (40, 20, 9)), (2, (3, 1, 1))]:
+            ctx.set_option(lb.OPT_WG_PER_CU, wg_per_cu)
+            for opt, v in zip((lb.OPT_COST_S2, lb.OPT_COST_C, lb.OPT_COST_S1), costs):
+                ctx.set_option(opt, v)
             out, idx = H.run_hybrid(ctx, dl, inp.mask)
-            H.assert_outputs_close(out, out_ref, "units%s" % (rows,))
-            H.assert_sets_match(idx, idx_ref, sel_ref, inp.mask, inp, w.k, idx_in, "units%s" % (rows,))
+            what = "wg_per_cu=%d costs=%s" % (wg_per_cu, costs)
+            H.assert_outputs_close(out, out_ref, what)
+            H.assert_sets_match(idx, idx_ref, sel_ref, inp.mask, inp, w.k, idx_in, what)
             results.append((out, idx))
     finally:
-        ctx.set_unit_rows(0, 0)
+        ctx.set_option(lb.OPT_WG_PER_CU, 2)
+        for opt, v in zip((lb.OPT_COST_S2, lb.OPT_COST_C, lb.OPT_COST_S1), (3, 1, 1)):
+            ctx.set_option(opt, v)
     for out, idx in results[1:]:
         assert (idx == results[0][1]).all()              # scores do not depend on the split
         assert np.abs(out - results[0][0]).max() <= 2 ** -6
@@ -221,9 +227,10 @@ def test_c4_batched_ragged(ctx):
 
 
 # ------------------------------------------------------------------ decode step (chaining)
-def test_decode_step_chains_sets_through_layers(ctx):
+@pytest.mark.parametrize("pipeline", [1, 0])
+def test_decode_step_chains_sets_through_layers(ctx, pipeline):
     lb = H.binding()
-    n_layers = 4
+    n_layers = 6
     w = wl.scaled(wl.WORKLOADS["c3"], max_len=4096, k=256, n_layers=n_layers, planted=64)
     layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=4096) for l in range(n_layers)]
     masks = np.stack([ly.mask for ly in layers])
@@ -236,12 +243,18 @@ def test_decode_step_chains_sets_through_layers(ctx):
         refs.append((out_ref, idx, sel_ref))
     shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 4096, w.k, kv=layers[0].k_cache)
     ws = lb.alloc_workspace(shape)
+    ws.fill_(0xFF)
     outs = [torch.zeros_like(ly.q) for ly in layers]
     idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
     lens = torch.from_numpy(layers[0].lengths).cuda()
-    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
-                    [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
-    torch.cuda.synchronize()
+    ctx.set_option(lb.OPT_PIPELINE, pipeline)
+    try:
+        for rep in range(2):    # the second step reuses a workspace full of the first one's data
+            ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                            [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
+            torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_PIPELINE, 1)
     for l in range(n_layers):
         H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "step layer %d" % l)
     # the final sets: groups that selected in the last layer are checked against its scores,
@@ -256,6 +269,34 @@ def test_decode_step_chains_sets_through_layers(ctx):
             assert ok, msg
         else:
             assert (got[0, g] == refs[-1][1][0, g]).all()
+
+
+def test_decode_step_with_given_sets_and_ragged_batch(ctx):
+    """Layer 0 is a hybrid layer fed by caller-supplied sets; batch of 3 ragged sequences."""
+    lb = H.binding()
+    n_layers = 5
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=3, max_len=3000, k=200, n_layers=n_layers, planted=32,
+                  len_lo=700, len_hi=3000)
+    lens_h = wl.lengths(w)
+    layers = [wl.make_layer(w, layer=l, device="cuda", lens=lens_h, l_cap=3000) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    idx0 = H.previous_layer_sets(layers[0], w.k)
+    idx = idx0
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, w.k, idx)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 3000, w.k, kv=layers[0].k_cache)
+    ws = lb.alloc_workspace(shape)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    lens = torch.from_numpy(lens_h).cuda()
+    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                    [ly.v_cache for ly in layers], masks, torch.from_numpy(idx0).cuda(), outs, None,
+                    lens, ws)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "ragged step layer %d" % l)
 
 
 # ------------------------------------------------------------------ boundary behaviour
