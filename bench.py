@@ -29,7 +29,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
-    ap.add_argument("--no-pipeline", action="store_true")
+    ap.add_argument("--layerwise", action="store_true", help="decode step layer after layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -49,7 +49,7 @@ def main() -> int:
     ctx = lb.Context(0)
     if args.wg_per_cu:
         ctx.set_option(lb.OPT_WG_PER_CU, args.wg_per_cu)
-    ctx.set_option(lb.OPT_PIPELINE, 0 if args.no_pipeline else 1)
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_LAYERWISE if args.layerwise else lb.STEP_PHASED)
 
     t_gen = time.perf_counter()
     layers = [wl.make_layer(w, layer=l, device=dev) for l in range(n_layers)]
@@ -59,7 +59,7 @@ def main() -> int:
     lens_h = layers[0].lengths
     lens = torch.from_numpy(lens_h).to(dev)
     shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, w.k, kv=layers[0].k_cache)
-    ws = lb.alloc_workspace(shape, dev)
+    ws = lb.alloc_workspace(shape, dev, n_layers=n_layers)
     outs = [torch.zeros_like(ly.q) for ly in layers]
     idx_final = torch.zeros((w.batch, w.n_kv_heads, w.k), dtype=torch.int32, device=dev)
     idx0 = None
@@ -145,7 +145,7 @@ def main() -> int:
                                "layer 0 all-retrieval then %d retrieval heads per layer" % (
                                    w.name, n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.max_len,
                                    w.k, w.n_retrieval),
-                   "pipeline": not args.no_pipeline},
+                   "step_mode": "layerwise" if args.layerwise else "phased"},
         "step_algorithmic_bytes": step_bytes,
         "step_achieved_gbps": round(step_bytes / sec / 1e9, 1),
         "step_hbm_frac": round(step_bytes / sec / 1e9 / HBM_PEAK_GBPS, 4),

@@ -12,9 +12,13 @@
  * Conventions shared by every call
  *   - Pointers are DEVICE pointers unless a parameter says HOST.  The caller owns every
  *     buffer; the library neither frees nor keeps them after the call's stream-ordered
- *     work has finished.  Nothing is allocated inside a call.
- *   - Calls only enqueue work on `hip_stream` (a hipStream_t; NULL = the default stream)
- *     and return without waiting for it.  They never read device memory from the host.
+ *     work has finished.  Nothing is allocated inside a call (a context allocates a 4 MiB
+ *     device arena and its pinned mirror once, in lychee_create).
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t; NULL = the default stream):
+ *     kernel launches, preceded by one small asynchronous host-to-device copy when the
+ *     call's pointers differ from those of earlier calls.  They never read device memory
+ *     from the host and normally return without waiting (the exception: once the arena has
+ *     seen about 4 MiB of distinct descriptor tables, a call waits for the stream once).
  *   - bf16 means the upper 16 bits of an IEEE fp32.  Scores and accumulation are fp32;
  *     `out` is rounded to nearest-even bf16.
  *   - KV-cache element (b, g, t, i), g a KV head, t a position, i < 128, lives at
@@ -51,7 +55,9 @@ extern "C" {
 #define LYCHEE_MAX_GROUP       4  /* query heads per KV head served (1..4)                     */
 #define LYCHEE_MAX_BATCH     256
 
-typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id and tuning, no buffers */
+typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id, tuning and a small device
+                                         arena for per-call descriptor tables; use one context
+                                         per stream */
 
 /* Problem shape of one layer call (the inputs of Alg. 1 that are not tensors). */
 typedef struct lychee_shape {
@@ -74,10 +80,12 @@ int lychee_destroy(lychee_ctx *ctx);
  * lychee_check_shape: validates `shape`; if `head_type_mask` (HOST, [H_q]) is given it also
  *   checks that sparse heads come with an inherited set (`has_idx_in` != 0).
  * lychee_workspace_bytes: bytes of scratch any call below needs for `shape` (selection
- *   scores, split partials, the step driver's set buffers); 0 if the shape is invalid.
+ *   scores, split partials, select lists); 0 if the shape is invalid.  lychee_decode_step
+ *   needs lychee_step_workspace_bytes (the same per layer).
  *   The workspace must be 256-byte aligned; its contents are don't-care on entry. */
 int    lychee_check_shape(const lychee_shape *shape, const uint8_t *head_type_mask, int has_idx_in);
 size_t lychee_workspace_bytes(const lychee_shape *shape);
+size_t lychee_step_workspace_bytes(const lychee_shape *shape, int32_t n_layers); /* for lychee_decode_step */
 
 /*
  * One layer of Alg. 1's per-head loop (retrieval branch: Eq. 1, Eq. 2, o = A V; sparse
@@ -118,6 +126,17 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
  *   idx_in                     sets entering layer 0, or NULL when layer 0 is all-retrieval
  *                              (Sec. 3.1: every head of the first layer is a retrieval head)
  *   idx_out                    the sets leaving the last layer; may be NULL
+ *   workspace                  at least lychee_step_workspace_bytes(shape, n_layers) bytes
+ * Because every layer's query is an input of the call, only the sparse heads of layer l+1
+ * depend on layer l (through its sets).  STEP_MODE chooses how that is used:
+ *   LYCHEE_STEP_PHASED (default)  five launches for the whole step: the retrieval streaming
+ *     of all layers pooled in one launch, then select phase 1, select phase 2, the sparse
+ *     gathers of all layers, and the combines.  out[l] of every layer is complete only
+ *     when the call's work has finished.
+ *   LYCHEE_STEP_LAYERWISE  layer after layer, each as lychee_decode_attn (three dependent
+ *     launches); out[l] is complete before layer l+1 starts, as a model that computes
+ *     q[l+1] from out[l] needs.
+ * Fewer than 128 layers; PHASED falls back to LAYERWISE when n_layers * batch > 2048.
  */
 int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
                        const void *const *q, const void *const *k_cache,
@@ -133,22 +152,17 @@ int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_
 
 /* Options of a context.  Results never depend on them beyond fp32 rounding order of the
  * split merge (index sets do not depend on them at all).
- *   WG_PER_CU  workgroups per compute unit in every launch (1..3, default 2)
- *   PIPELINE   lychee_decode_step: 1 (default) = one launch per layer, in which the streaming
- *              of layer t runs beside the select / gather / combine work of layers t-1..t-3
- *              (outputs of layer l are complete three launches after its streaming);
- *              0 = layer after layer, three dependent launches each, as lychee_decode_attn
- *   COST_*     balancing weights of the small work units, in 64-row blocks of streaming
- *   N_WG       workgroups per launch, overriding WG_PER_CU (0 = CUs x WG_PER_CU; at most 768)
+ *   WG_PER_CU     workgroups per compute unit in every launch (1..3, default 2)
+ *   N_WG          workgroups per launch, overriding WG_PER_CU (0 = CUs x WG_PER_CU; at most 768)
+ *   STEP_MODE     how lychee_decode_step orders its work (see there)
  *   GATHER_BLOCK  set entries whose gather is balanced against 64 streamed rows (a multiple
- *              of 16 in [16, 128], default 48: a gathered row costs more than a streamed one) */
-#define LYCHEE_OPT_WG_PER_CU 1
-#define LYCHEE_OPT_PIPELINE  2
-#define LYCHEE_OPT_COST_S2   3
-#define LYCHEE_OPT_COST_C    4
-#define LYCHEE_OPT_COST_S1   5
+ *                 of 16 in [16, 128], default 48: a gathered row costs more than a streamed one) */
+#define LYCHEE_OPT_WG_PER_CU    1
+#define LYCHEE_OPT_STEP_MODE    2
 #define LYCHEE_OPT_GATHER_BLOCK 6
-#define LYCHEE_OPT_N_WG       7
+#define LYCHEE_OPT_N_WG         7
+#define LYCHEE_STEP_PHASED      1
+#define LYCHEE_STEP_LAYERWISE   0
 int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
 
 /* Per-kernel timing with HIP events on the caller's stream.  While enabled, every launch of

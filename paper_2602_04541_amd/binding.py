@@ -19,10 +19,12 @@ LIB_PATH = os.path.join(_HERE, "liblychee.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 KERNEL_ATTN, KERNEL_COMBINE, KERNEL_SELECT = 0, 1, 2
-OPT_WG_PER_CU, OPT_PIPELINE, OPT_COST_S2, OPT_COST_C, OPT_COST_S1, OPT_GATHER_BLOCK, OPT_N_WG = 1, 2, 3, 4, 5, 6, 7
+OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG = 1, 2, 6, 7
+STEP_PHASED, STEP_LAYERWISE = 1, 0
 
 EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
+    "lychee_step_workspace_bytes",
     "lychee_decode_attn", "lychee_dense_decode_attn", "lychee_decode_step",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
@@ -56,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.lychee_check_shape.argtypes = [shp, vp, ctypes.c_int]
     lib.lychee_workspace_bytes.argtypes = [shp]
     lib.lychee_workspace_bytes.restype = sz
+    lib.lychee_step_workspace_bytes.argtypes = [shp, i32]
+    lib.lychee_step_workspace_bytes.restype = sz
     lib.lychee_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_dense_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -68,7 +72,7 @@ def _load() -> ctypes.CDLL:
     lib.lychee_strerror.argtypes = [ctypes.c_int]
     lib.lychee_strerror.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("lychee_workspace_bytes", "lychee_strerror"):
+        if name not in ("lychee_workspace_bytes", "lychee_step_workspace_bytes", "lychee_strerror"):
             getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -125,6 +129,10 @@ def check_shape(shape: Shape, head_type_mask: Optional[np.ndarray] = None,
 
 def workspace_bytes(shape: Shape) -> int:
     return int(_lib.lychee_workspace_bytes(ctypes.byref(shape)))
+
+
+def step_workspace_bytes(shape: Shape, n_layers: int) -> int:
+    return int(_lib.lychee_step_workspace_bytes(ctypes.byref(shape), n_layers))
 
 
 class Context:
@@ -208,9 +216,10 @@ class Context:
                "lychee_probe_copy")
 
 
-def alloc_workspace(shape: Shape, device="cuda") -> torch.Tensor:
-    """A device buffer of lychee_workspace_bytes(shape) bytes (torch only allocates it)."""
-    n = workspace_bytes(shape)
+def alloc_workspace(shape: Shape, device="cuda", n_layers: int = 1) -> torch.Tensor:
+    """A device buffer of lychee_step_workspace_bytes(shape, n_layers) bytes (torch only
+    allocates it); n_layers = 1 is what the single-layer calls need."""
+    n = step_workspace_bytes(shape, n_layers)
     if n == 0:
         raise LycheeError(_lib.lychee_check_shape(ctypes.byref(shape), None, 1), "lychee_workspace_bytes")
     return torch.empty(n, dtype=torch.uint8, device=device)

@@ -1,10 +1,11 @@
-// Host side of liblychee: argument checks, the split plan, workspace carving and the
-// stream-ordered launch sequence of one layer call (attention units -> combine -> select)
-// and of a whole decode step (Alg. 1's layer loop restricted to its per-head loop).
+// Host side of liblychee: argument checks, workspace carving, the table of layer
+// descriptors and the stream-ordered launch sequences of a layer call and of a decode step
+// (Alg. 1's layer loop restricted to its per-head loop).
 #include "../../include/lychee.h"
 #include "lychee_internal.h"
 
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -12,14 +13,17 @@
 
 using namespace lychee;
 
+namespace {
+constexpr size_t kArenaBytes = 4u << 20;  // device memory for descriptor tables, per context
+}
+
 struct lychee_ctx {
     int device = 0;
     int n_cu = 256;
     int32_t wg_per_cu = 2;
-    int32_t pipeline = 1;
-    int32_t cost_s2 = 3, cost_c = 1, cost_s1 = 1;
+    int32_t n_wg = 0;          // 0 = n_cu * wg_per_cu
+    int32_t step_mode = LYCHEE_STEP_PHASED;
     int32_t g_block_rows = 48;
-    int32_t n_wg = 0;  // 0 = n_cu * wg_per_cu
     bool timing = false;
     struct Rec {
         int cls;
@@ -27,35 +31,45 @@ struct lychee_ctx {
     };
     std::vector<Rec> recs;         // events recorded since the last read
     std::vector<hipEvent_t> pool;  // events free for reuse
+    // Descriptor tables: built on the host, staged in pinned memory, copied to the arena
+    // with an asynchronous copy on the caller's stream, and cached by content so that a
+    // serving loop that passes the same buffers every step uploads nothing.
+    char *arena_dev = nullptr;
+    char *arena_host = nullptr;  // pinned, same layout as the device arena
+    size_t arena_used = 0;
+    struct Cached {
+        uint64_t hash;
+        size_t offset, bytes;
+    };
+    std::vector<Cached> cache;
 };
 
 namespace {
 
-constexpr int kWsWg = 768;      // partial slots per head the workspace provides
-constexpr int kSelRing = 3;     // layers whose selection scores are alive at once (pipelined step)
-constexpr int kPartRing = 4;
-constexpr int kListRing = 2;
+constexpr int kWsWg = 768;  // largest grid a launch uses = partial slots per head in the workspace
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-int32_t slice_cap(int32_t max_len)
+// Entries of one score row's filtered list: every slice can keep all of its scores, and
+// slices are rounded up to the filter's quantum.
+int32_t list_row_entries(int32_t max_len)
 {
-    const int64_t per = (max_len + kSlices - 1) / kSlices;
-    return (int32_t)round_up(per, kSliceQuantum);
+    return (int32_t)(round_up(max_len, kSliceQuantum) + (int64_t)kSlices * kSliceQuantum);
 }
 
+// Per-layer scratch, laid out layer after layer.
 struct Workspace {
-    size_t sel_off[kSelRing], part_o_off[kPartRing], part_ml_off[kPartRing], part_count_off[kPartRing];
-    size_t list_off[kListRing], list_count_off[kListRing], idx_off[2], total;
-    int32_t sel_stride, list_cap;
+    size_t sel, part_o, part_ml, part_count, list, list_count, idx_set;  // offsets inside a layer
+    size_t layer_bytes, total;
+    int32_t sel_stride, list_row;
 };
 
-Workspace carve(const lychee_shape &s)
+Workspace carve(const lychee_shape &s, int n_layers)
 {
     Workspace w;
     w.sel_stride = (int32_t)round_up(s.max_len, 64);
-    w.list_cap = slice_cap(s.max_len);
+    w.list_row = list_row_entries(s.max_len);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -64,18 +78,15 @@ Workspace carve(const lychee_shape &s)
     };
     const size_t heads = (size_t)s.batch * s.n_q_heads;
     const size_t groups = (size_t)s.batch * s.n_kv_heads;
-    for (int i = 0; i < kSelRing; ++i) w.sel_off[i] = take(groups * w.sel_stride * sizeof(float));
-    for (int i = 0; i < kPartRing; ++i) {
-        w.part_o_off[i] = take(heads * kWsWg * kHeadDim * sizeof(float));
-        w.part_ml_off[i] = take(heads * kWsWg * 2 * sizeof(float));
-        w.part_count_off[i] = take(heads * sizeof(int32_t));
-    }
-    for (int i = 0; i < kListRing; ++i) {
-        w.list_off[i] = take(groups * kSlices * (size_t)w.list_cap * sizeof(uint2));
-        w.list_count_off[i] = take(groups * kSlices * sizeof(int32_t));
-    }
-    for (int i = 0; i < 2; ++i) w.idx_off[i] = take(groups * s.k * sizeof(int32_t));
-    w.total = off;
+    w.sel = take(groups * w.sel_stride * sizeof(float));
+    w.part_o = take(heads * kWsWg * kHeadDim * sizeof(float));
+    w.part_ml = take(heads * kWsWg * 2 * sizeof(float));
+    w.part_count = take(heads * sizeof(int32_t));
+    w.list = take(groups * (size_t)w.list_row * sizeof(uint2));
+    w.list_count = take(groups * kSlices * sizeof(int32_t));
+    w.idx_set = take(groups * s.k * sizeof(int32_t));
+    w.layer_bytes = off;
+    w.total = off * (size_t)n_layers;
     return w;
 }
 
@@ -97,212 +108,14 @@ int check_shape(const lychee_shape *s)
     return LYCHEE_OK;
 }
 
-// The head-type structure of one layer, as the kernels want it.
-struct Groups {
-    int n_rgroups = 0, n_sgroups = 0;
-    uint8_t rgroup[kMaxKvHeads], sgroup[kMaxKvHeads], rmask[kMaxKvHeads], rindex[kMaxKvHeads];
-};
-
-Groups make_groups(const lychee_shape &s, const uint8_t *mask)  // mask == nullptr: all retrieval
-{
-    Groups gr;
-    memset(&gr, 0, sizeof gr);
-    const int G = s.n_q_heads / s.n_kv_heads;
-    for (int g = 0; g < s.n_kv_heads; ++g) {
-        uint32_t bits = 0;
-        for (int i = 0; i < G; ++i)
-            if (mask == nullptr || mask[g * G + i]) bits |= 1u << i;
-        gr.rmask[g] = (uint8_t)bits;
-        gr.rindex[g] = 0xFF;
-        if (bits != 0) {
-            gr.rindex[g] = (uint8_t)gr.n_rgroups;
-            gr.rgroup[gr.n_rgroups++] = (uint8_t)g;
-        }
-        if (bits != (1u << G) - 1u) gr.sgroup[gr.n_sgroups++] = (uint8_t)g;
-    }
-    return gr;
-}
-
-// One layer's tensors and where its intermediate results live.
-struct LayerIo {
-    const void *q, *k_cache, *v_cache;
-    void *out;
-    const int32_t *idx_in;
-    int32_t *idx_out;
-    Groups gr;
-    bool emit_sel, want_select;
-    int sel_slot, part_slot, list_slot;
-};
-
-struct Planner {
-    const lychee_ctx *ctx;
-    const lychee_shape &s;
-    const Workspace &w;
-    char *ws;
-    const int32_t *lengths;
-
-    LaunchPlan blank() const
-    {
-        LaunchPlan p;
-        memset(&p, 0, sizeof p);
-        Common &c = p.c;
-        c.lengths = lengths;
-        c.stride_b = s.kv_stride_batch;
-        c.stride_h = s.kv_stride_head;
-        c.stride_t = s.kv_stride_tok;
-        c.batch = s.batch;
-        c.n_q_heads = s.n_q_heads;
-        c.n_kv_heads = s.n_kv_heads;
-        c.group = s.n_q_heads / s.n_kv_heads;
-        c.k = s.k;
-        c.max_len = s.max_len;
-        c.sel_stride = w.sel_stride;
-        c.list_cap = w.list_cap;
-        int n_wg = ctx->n_wg > 0 ? ctx->n_wg : ctx->n_cu * ctx->wg_per_cu;
-        c.n_wg = n_wg > kWsWg ? kWsWg : n_wg;
-        c.part_stride = kWsWg;
-        c.g_block_rows = ctx->g_block_rows;
-        c.cost_s2 = ctx->cost_s2;
-        c.cost_c = ctx->cost_c;
-        c.cost_s1 = ctx->cost_s1;
-        c.scale = (float)(1.0 / sqrt((double)kHeadDim));
-        c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
-        return p;
-    }
-    float *part_o(int slot) const { return reinterpret_cast<float *>(ws + w.part_o_off[slot]); }
-    float *part_ml(int slot) const { return reinterpret_cast<float *>(ws + w.part_ml_off[slot]); }
-    int32_t *part_count(int slot) const { return reinterpret_cast<int32_t *>(ws + w.part_count_off[slot]); }
-    float *sel(int slot) const { return reinterpret_cast<float *>(ws + w.sel_off[slot]); }
-
-    void add_r(LaunchPlan &p, const LayerIo &io) const
-    {
-        if (io.gr.n_rgroups == 0) return;
-        RPart &r = p.r;
-        r.enabled = 1;
-        r.q = static_cast<const uint16_t *>(io.q);
-        r.k_cache = static_cast<const uint16_t *>(io.k_cache);
-        r.v_cache = static_cast<const uint16_t *>(io.v_cache);
-        r.sel = sel(io.sel_slot);
-        r.part_o = part_o(io.part_slot);
-        r.part_ml = part_ml(io.part_slot);
-        r.part_count = part_count(io.part_slot);
-        r.n_rgroups = io.gr.n_rgroups;
-        r.emit_sel = io.emit_sel ? 1 : 0;
-        memcpy(r.rgroup, io.gr.rgroup, sizeof r.rgroup);
-        memcpy(r.rmask, io.gr.rmask, sizeof r.rmask);
-    }
-    void add_g(LaunchPlan &p, const LayerIo &io) const
-    {
-        if (io.gr.n_sgroups == 0) return;
-        GPart &g = p.g;
-        g.enabled = 1;
-        g.q = static_cast<const uint16_t *>(io.q);
-        g.k_cache = static_cast<const uint16_t *>(io.k_cache);
-        g.v_cache = static_cast<const uint16_t *>(io.v_cache);
-        g.idx = io.idx_in;
-        g.part_o = part_o(io.part_slot);
-        g.part_ml = part_ml(io.part_slot);
-        g.part_count = part_count(io.part_slot);
-        g.n_sgroups = io.gr.n_sgroups;
-        memcpy(g.sgroup, io.gr.sgroup, sizeof g.sgroup);
-        memcpy(g.rmask, io.gr.rmask, sizeof g.rmask);
-    }
-    void add_c(LaunchPlan &p, const LayerIo &io) const
-    {
-        CPart &c = p.comb;
-        c.enabled = 1;
-        c.part_o = part_o(io.part_slot);
-        c.part_ml = part_ml(io.part_slot);
-        c.part_count = part_count(io.part_slot);
-        c.out = static_cast<uint16_t *>(io.out);
-    }
-    void add_s1(LaunchPlan &p, const LayerIo &io) const
-    {
-        if (!io.want_select || io.gr.n_rgroups == 0) return;
-        S1Part &a = p.s1;
-        a.enabled = 1;
-        a.sel = sel(io.sel_slot);
-        a.list = reinterpret_cast<uint2 *>(ws + w.list_off[io.list_slot]);
-        a.list_count = reinterpret_cast<int32_t *>(ws + w.list_count_off[io.list_slot]);
-        a.n_rgroups = io.gr.n_rgroups;
-    }
-    void add_s2(LaunchPlan &p, const LayerIo &io) const
-    {
-        if (!io.want_select) return;
-        S2Part &a = p.s2;
-        a.enabled = 1;
-        a.sel = sel(io.sel_slot);
-        a.list = reinterpret_cast<const uint2 *>(ws + w.list_off[io.list_slot]);
-        a.list_count = reinterpret_cast<const int32_t *>(ws + w.list_count_off[io.list_slot]);
-        a.idx_in = io.idx_in;
-        a.idx_out = io.idx_out;
-        a.n_rgroups = io.gr.n_rgroups;
-        memcpy(a.rindex, io.gr.rindex, sizeof a.rindex);
-    }
-};
-
-bool is_empty(const LaunchPlan &p)
-{
-    return !p.r.enabled && !p.g.enabled && !p.comb.enabled && !p.s1.enabled && !p.s2.enabled;
-}
-
-int launch_class(const LaunchPlan &p)
-{
-    if (p.r.enabled || p.g.enabled) return LYCHEE_KERNEL_ATTN;
-    if (p.comb.enabled || p.s1.enabled) return LYCHEE_KERNEL_COMBINE;
-    return LYCHEE_KERNEL_SELECT;
-}
-
-hipEvent_t take_event(lychee_ctx *ctx)
-{
-    if (!ctx->pool.empty()) {
-        hipEvent_t e = ctx->pool.back();
-        ctx->pool.pop_back();
-        return e;
-    }
-    hipEvent_t e = nullptr;
-    if (hipEventCreate(&e) != hipSuccess) return nullptr;
-    return e;
-}
-
-int submit(lychee_ctx *ctx, const LaunchPlan &p, hipStream_t stream)
-{
-    if (is_empty(p)) return LYCHEE_OK;
-    if (!ctx->timing) return launch_units(p, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
-    lychee_ctx::Rec r{launch_class(p), take_event(ctx), take_event(ctx)};
-    if (r.start == nullptr || r.stop == nullptr) return LYCHEE_EHIP;
-    if (hipEventRecord(r.start, stream) != hipSuccess) return LYCHEE_EHIP;
-    if (launch_units(p, stream) != hipSuccess) return LYCHEE_EHIP;
-    if (hipEventRecord(r.stop, stream) != hipSuccess) return LYCHEE_EHIP;
-    ctx->recs.push_back(r);
-    return LYCHEE_OK;
-}
-
-// One layer, three dependent launches: R+G, then S1+C, then S2.
-int run_layer(lychee_ctx *ctx, const Planner &pl, const LayerIo &io, hipStream_t stream)
-{
-    LaunchPlan a = pl.blank();
-    pl.add_r(a, io);
-    pl.add_g(a, io);
-    int rc = submit(ctx, a, stream);
-    if (rc != LYCHEE_OK) return rc;
-    LaunchPlan b = pl.blank();
-    pl.add_s1(b, io);
-    pl.add_c(b, io);
-    if ((rc = submit(ctx, b, stream)) != LYCHEE_OK) return rc;
-    LaunchPlan c = pl.blank();
-    pl.add_s2(c, io);
-    return submit(ctx, c, stream);
-}
-
 int check_common(lychee_ctx *ctx, const lychee_shape *shape, const void *workspace,
-                 size_t workspace_bytes)
+                 size_t workspace_bytes, int n_layers)
 {
     if (ctx == nullptr) return LYCHEE_EINVAL;
     const int rc = check_shape(shape);
     if (rc != LYCHEE_OK) return rc;
     if (workspace == nullptr || !aligned(workspace, 256)) return LYCHEE_EWORKSPACE;
-    if (workspace_bytes < carve(*shape).total) return LYCHEE_EWORKSPACE;
+    if (workspace_bytes < carve(*shape, n_layers).total) return LYCHEE_EWORKSPACE;
     return LYCHEE_OK;
 }
 
@@ -326,6 +139,182 @@ int make_current(lychee_ctx *ctx)
     return LYCHEE_OK;
 }
 
+// Fills the head-type tables of a descriptor.  mask == nullptr: every head is a retrieval head.
+void set_groups(LayerDesc &d, const lychee_shape &s, const uint8_t *mask)
+{
+    const int G = s.n_q_heads / s.n_kv_heads;
+    d.n_rgroups = d.n_sgroups = 0;
+    for (int g = 0; g < s.n_kv_heads; ++g) {
+        uint32_t bits = 0;
+        for (int i = 0; i < G; ++i)
+            if (mask == nullptr || mask[g * G + i]) bits |= 1u << i;
+        d.rmask[g] = (uint8_t)bits;
+        d.rindex[g] = 0xFF;
+        if (bits != 0) {
+            d.rindex[g] = (uint8_t)d.n_rgroups;
+            d.rgroup[d.n_rgroups++] = (uint8_t)g;
+        }
+        if (bits != (1u << G) - 1u) d.sgroup[d.n_sgroups++] = (uint8_t)g;
+    }
+}
+
+void set_scratch(LayerDesc &d, const Workspace &w, char *ws, int layer_slot)
+{
+    char *base = ws + (size_t)layer_slot * w.layer_bytes;
+    d.sel = reinterpret_cast<float *>(base + w.sel);
+    d.part_o = reinterpret_cast<float *>(base + w.part_o);
+    d.part_ml = reinterpret_cast<float *>(base + w.part_ml);
+    d.part_count = reinterpret_cast<int32_t *>(base + w.part_count);
+    d.list = reinterpret_cast<uint2 *>(base + w.list);
+    d.list_count = reinterpret_cast<int32_t *>(base + w.list_count);
+}
+
+int32_t *idx_set_of(const Workspace &w, char *ws, int layer_slot)
+{
+    return reinterpret_cast<int32_t *>(ws + (size_t)layer_slot * w.layer_bytes + w.idx_set);
+}
+
+uint64_t hash_bytes(const void *p, size_t n)
+{
+    const unsigned char *b = static_cast<const unsigned char *>(p);
+    uint64_t h = 1469598103934665603ull;  // FNV-1a
+    for (size_t i = 0; i < n; ++i) h = (h ^ b[i]) * 1099511628211ull;
+    return h;
+}
+
+// Returns the device address of a table with exactly these descriptors, uploading it (one
+// asynchronous copy on `stream`) unless an identical table is already resident.
+const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &descs, hipStream_t stream)
+{
+    const size_t bytes = descs.size() * sizeof(LayerDesc);
+    if (bytes > kArenaBytes) return nullptr;
+    const uint64_t h = hash_bytes(descs.data(), bytes);
+    for (const auto &e : ctx->cache)
+        if (e.hash == h && e.bytes == bytes && memcmp(ctx->arena_host + e.offset, descs.data(), bytes) == 0)
+            return reinterpret_cast<const LayerDesc *>(ctx->arena_dev + e.offset);
+    if (ctx->arena_used + bytes > kArenaBytes) {
+        // Arena full: start over.  Tables still in use by enqueued launches, and staging
+        // bytes of copies still in flight, must not be overwritten, so wait for the stream.
+        if (hipStreamSynchronize(stream) != hipSuccess) return nullptr;
+        ctx->arena_used = 0;
+        ctx->cache.clear();
+    }
+    const size_t off = ctx->arena_used;
+    memcpy(ctx->arena_host + off, descs.data(), bytes);
+    if (hipMemcpyAsync(ctx->arena_dev + off, ctx->arena_host + off, bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
+        return nullptr;
+    ctx->arena_used = (size_t)round_up((int64_t)(off + bytes), 256);
+    ctx->cache.push_back({h, off, bytes});
+    return reinterpret_cast<const LayerDesc *>(ctx->arena_dev + off);
+}
+
+struct Ranges {
+    int r_first = 0, r_count = 0, g_first = 0, g_count = 0, c_first = 0, c_count = 0;
+    int s1_first = 0, s1_count = 0, s2_first = 0, s2_count = 0;
+};
+
+hipEvent_t take_event(lychee_ctx *ctx)
+{
+    if (!ctx->pool.empty()) {
+        hipEvent_t e = ctx->pool.back();
+        ctx->pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct Launcher {
+    lychee_ctx *ctx;
+    const lychee_shape &s;
+    const Workspace &w;
+    const int32_t *lengths;
+    const LayerDesc *table;
+    hipStream_t stream;
+    int n_slices;  // slices per score row, the same in the S1 and S2 launches of a call
+
+    int grid() const
+    {
+        const int n_wg = ctx->n_wg > 0 ? ctx->n_wg : ctx->n_cu * ctx->wg_per_cu;
+        return n_wg > kWsWg ? kWsWg : n_wg;
+    }
+    // Enough slices to give every workgroup a filter unit, for `rows` score rows.
+    void choose_slices(int64_t rows)
+    {
+        n_slices = 1;
+        while (n_slices < kSlices && rows * n_slices * 2 <= grid()) n_slices *= 2;
+    }
+
+    int go(const Ranges &r) const
+    {
+        if (r.r_count + r.g_count + r.c_count + r.s1_count + r.s2_count == 0) return LYCHEE_OK;
+#ifdef LYCHEE_TRACE
+        {   // trace builds: LYCHEE_TRACE_STOP=n drops every launch after the n-th of a call
+            static int budget = -1, left = 0;
+            if (budget < 0) budget = getenv("LYCHEE_TRACE_STOP") ? atoi(getenv("LYCHEE_TRACE_STOP")) : 0;
+            if (budget > 0) {
+                if (r.r_count > 1 || (r.r_count == 1 && r.r_first == 0)) left = budget;
+                if (left-- <= 0) return LYCHEE_OK;
+            }
+        }
+#endif
+        LaunchPlan p;
+        memset(&p, 0, sizeof p);
+        Common &c = p.c;
+        c.lengths = lengths;
+        c.stride_b = s.kv_stride_batch;
+        c.stride_h = s.kv_stride_head;
+        c.stride_t = s.kv_stride_tok;
+        c.batch = s.batch;
+        c.n_q_heads = s.n_q_heads;
+        c.n_kv_heads = s.n_kv_heads;
+        c.group = s.n_q_heads / s.n_kv_heads;
+        c.k = s.k;
+        c.max_len = s.max_len;
+        c.sel_stride = w.sel_stride;
+        c.list_row = w.list_row;
+        c.n_slices = n_slices;
+        c.n_wg = grid();
+        c.part_stride = kWsWg;
+        c.g_block_rows = ctx->g_block_rows;
+        c.scale = (float)(1.0 / sqrt((double)kHeadDim));
+        c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
+        p.layers = table;
+        p.r_first = r.r_first, p.r_count = r.r_count;
+        p.g_first = r.g_first, p.g_count = r.g_count;
+        p.c_first = r.c_first, p.c_count = r.c_count;
+        p.s1_first = r.s1_first, p.s1_count = r.s1_count;
+        p.s2_first = r.s2_first, p.s2_count = r.s2_count;
+        const int cls = (r.r_count || r.g_count) ? LYCHEE_KERNEL_ATTN
+                        : (r.c_count || r.s1_count) ? LYCHEE_KERNEL_COMBINE : LYCHEE_KERNEL_SELECT;
+        if (!ctx->timing) return launch_units(p, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
+        lychee_ctx::Rec rec{cls, take_event(ctx), take_event(ctx)};
+        if (rec.start == nullptr || rec.stop == nullptr) return LYCHEE_EHIP;
+        if (hipEventRecord(rec.start, stream) != hipSuccess) return LYCHEE_EHIP;
+        if (launch_units(p, stream) != hipSuccess) return LYCHEE_EHIP;
+        if (hipEventRecord(rec.stop, stream) != hipSuccess) return LYCHEE_EHIP;
+        ctx->recs.push_back(rec);
+        return LYCHEE_OK;
+    }
+};
+
+// Layer `l` of the table, three dependent launches: R+G, then S1+C, then S2.
+int run_layer(const Launcher &L, int l, bool select)
+{
+    Ranges a;
+    a.r_first = a.g_first = l, a.r_count = a.g_count = 1;
+    int rc = L.go(a);
+    if (rc != LYCHEE_OK) return rc;
+    Ranges b;
+    b.c_first = l, b.c_count = 1;
+    if (select) b.s1_first = l, b.s1_count = 1;
+    if ((rc = L.go(b)) != LYCHEE_OK) return rc;
+    Ranges c;
+    if (select) c.s2_first = l, c.s2_count = 1;
+    return L.go(c);
+}
+
 }  // namespace
 
 extern "C" {
@@ -342,6 +331,17 @@ int lychee_create(lychee_ctx **out, int device)
     if (ctx == nullptr) return LYCHEE_EHIP;
     ctx->device = device;
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    int cur = -1;
+    bool ok = hipGetDevice(&cur) == hipSuccess && hipSetDevice(device) == hipSuccess;
+    ok = ok && hipMalloc(reinterpret_cast<void **>(&ctx->arena_dev), kArenaBytes) == hipSuccess;
+    ok = ok && hipHostMalloc(reinterpret_cast<void **>(&ctx->arena_host), kArenaBytes, hipHostMallocDefault) == hipSuccess;
+    if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+    if (!ok) {
+        if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
+        if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
+        delete ctx;
+        return LYCHEE_EHIP;
+    }
     *out = ctx;
     return LYCHEE_OK;
 }
@@ -354,6 +354,8 @@ int lychee_destroy(lychee_ctx *ctx)
         (void)hipEventDestroy(r.stop);
     }
     for (auto e : ctx->pool) (void)hipEventDestroy(e);
+    if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
+    if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
     delete ctx;
     return LYCHEE_OK;
 }
@@ -368,7 +370,13 @@ int lychee_check_shape(const lychee_shape *shape, const uint8_t *head_type_mask,
 size_t lychee_workspace_bytes(const lychee_shape *shape)
 {
     if (check_shape(shape) != LYCHEE_OK) return 0;
-    return carve(*shape).total;
+    return carve(*shape, 1).total;
+}
+
+size_t lychee_step_workspace_bytes(const lychee_shape *shape, int32_t n_layers)
+{
+    if (check_shape(shape) != LYCHEE_OK || n_layers < 1 || n_layers > kMaxLayers) return 0;
+    return carve(*shape, n_layers).total;
 }
 
 int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
@@ -376,7 +384,7 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
                        const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
                        void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_common(ctx, shape, workspace, workspace_bytes);
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, 1);
     if (rc != LYCHEE_OK) return rc;
     rc = check_mask(shape, head_type_mask, idx_in != nullptr);
     if (rc != LYCHEE_OK) return rc;
@@ -388,11 +396,26 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
         return LYCHEE_EINVAL;
     if (idx_in == idx_out) return LYCHEE_EINVAL;
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
-    const Workspace w = carve(*shape);
-    const Planner pl{ctx, *shape, w, static_cast<char *>(workspace), lengths};
-    LayerIo io{q, k_cache, v_cache, out, idx_in, idx_out, make_groups(*shape, head_type_mask),
-               true, true, 0, 0, 0};
-    return run_layer(ctx, pl, io, static_cast<hipStream_t>(hip_stream));
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, 1);
+    std::vector<LayerDesc> descs(1);
+    LayerDesc &d = descs[0];
+    memset(&d, 0, sizeof d);
+    d.q = static_cast<const uint16_t *>(q);
+    d.k_cache = static_cast<const uint16_t *>(k_cache);
+    d.v_cache = static_cast<const uint16_t *>(v_cache);
+    d.out = static_cast<uint16_t *>(out);
+    set_groups(d, *shape, head_type_mask);
+    set_scratch(d, w, static_cast<char *>(workspace), 0);
+    d.idx_out = idx_out;
+    for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = idx_in;
+    d.emit_sel = 1;
+    d.copy_keep = 1;
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+    L.choose_slices((int64_t)shape->batch * d.n_rgroups);
+    return run_layer(L, 0, true);
 }
 
 int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
@@ -400,7 +423,7 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
                              const int32_t *lengths, void *workspace, size_t workspace_bytes,
                              void *hip_stream)
 {
-    int rc = check_common(ctx, shape, workspace, workspace_bytes);
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, 1);
     if (rc != LYCHEE_OK) return rc;
     if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr || lengths == nullptr)
         return LYCHEE_EINVAL;
@@ -408,11 +431,21 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
         !aligned(lengths, 4))
         return LYCHEE_EINVAL;
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
-    const Workspace w = carve(*shape);
-    const Planner pl{ctx, *shape, w, static_cast<char *>(workspace), lengths};
-    LayerIo io{q, k_cache, v_cache, out, nullptr, nullptr, make_groups(*shape, nullptr),
-               false, false, 0, 0, 0};
-    return run_layer(ctx, pl, io, static_cast<hipStream_t>(hip_stream));
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, 1);
+    std::vector<LayerDesc> descs(1);
+    LayerDesc &d = descs[0];
+    memset(&d, 0, sizeof d);
+    d.q = static_cast<const uint16_t *>(q);
+    d.k_cache = static_cast<const uint16_t *>(k_cache);
+    d.v_cache = static_cast<const uint16_t *>(v_cache);
+    d.out = static_cast<uint16_t *>(out);
+    set_groups(d, *shape, nullptr);
+    set_scratch(d, w, static_cast<char *>(workspace), 0);
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    const Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+    return run_layer(L, 0, false);
 }
 
 int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
@@ -422,10 +455,11 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
                        const int32_t *lengths, void *workspace, size_t workspace_bytes,
                        void *hip_stream)
 {
-    int rc = check_common(ctx, shape, workspace, workspace_bytes);
+    if (n_layers < 1 || n_layers >= kMaxLayers) return n_layers < 1 ? LYCHEE_EINVAL : LYCHEE_EUNSUPPORTED;
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, n_layers);
     if (rc != LYCHEE_OK) return rc;
-    if (n_layers < 1 || q == nullptr || k_cache == nullptr || v_cache == nullptr ||
-        out == nullptr || head_type_masks == nullptr || lengths == nullptr)
+    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr ||
+        head_type_masks == nullptr || lengths == nullptr)
         return LYCHEE_EINVAL;
     if (!aligned(idx_in, 4) || !aligned(idx_out, 4) || !aligned(lengths, 4)) return LYCHEE_EINVAL;
     if (idx_in != nullptr && idx_in == idx_out) return LYCHEE_EINVAL;
@@ -440,45 +474,82 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
         if (rc != LYCHEE_OK) return rc;
     }
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
-    const Workspace w = carve(*shape);
-    char *ws = static_cast<char *>(workspace);
-    const Planner pl{ctx, *shape, w, ws, lengths};
-    int32_t *buf[2] = {reinterpret_cast<int32_t *>(ws + w.idx_off[0]),
-                       reinterpret_cast<int32_t *>(ws + w.idx_off[1])};
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, n_layers);
+    char *ws = static_cast<char *>(workspace);
 
-    // layer l reads the sets idx(l) and writes idx(l+1); idx(0) = idx_in, idx(n) = idx_out
-    auto sets_of = [&](int l) -> int32_t * {
-        if (l == n_layers && idx_out != nullptr) return idx_out;
-        return buf[l & 1];
-    };
-    auto io_of = [&](int l) {
-        const bool want = l < n_layers - 1 || idx_out != nullptr;
-        return LayerIo{q[l], k_cache[l], v_cache[l], out[l],
-                       l == 0 ? idx_in : sets_of(l), sets_of(l + 1),
-                       make_groups(*shape, head_type_masks + (size_t)l * shape->n_q_heads),
-                       want, want, l % kSelRing, l % kPartRing, l % kListRing};
-    };
-    if (!ctx->pipeline) {
-        for (int l = 0; l < n_layers; ++l)
-            if ((rc = run_layer(ctx, pl, io_of(l), stream)) != LYCHEE_OK) return rc;
-        return LYCHEE_OK;
+    // Layer l writes the sets of its retrieval groups into its own array; a KV head whose
+    // group holds no retrieval head keeps reading the array of the last layer that selected
+    // for it (Sec. 3.1: the set is propagated unchanged), so nothing is copied between layers.
+    // Entry n_layers of the table only assembles the caller's idx_out from those arrays.
+    std::vector<LayerDesc> descs((size_t)n_layers + 1);
+    const int32_t *cur[kMaxKvHeads];
+    for (int g = 0; g < shape->n_kv_heads; ++g) cur[g] = idx_in;
+    for (int l = 0; l < n_layers; ++l) {
+        LayerDesc &d = descs[l];
+        memset(&d, 0, sizeof d);
+        d.q = static_cast<const uint16_t *>(q[l]);
+        d.k_cache = static_cast<const uint16_t *>(k_cache[l]);
+        d.v_cache = static_cast<const uint16_t *>(v_cache[l]);
+        d.out = static_cast<uint16_t *>(out[l]);
+        set_groups(d, *shape, head_type_masks + (size_t)l * shape->n_q_heads);
+        set_scratch(d, w, ws, l);
+        d.idx_out = idx_set_of(w, ws, l);
+        for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = cur[g];
+        d.emit_sel = 1;
+        d.copy_keep = 0;
+        for (int i = 0; i < d.n_rgroups; ++i) cur[d.rgroup[i]] = d.idx_out;
     }
-    // Software pipeline over launches t: the streaming of layer t shares a launch with the
-    // select phases, the gather and the combine of earlier layers, whose inputs were all
-    // written by earlier launches:
-    //   R(t)  |  S1(t-1)  |  S2(t-2), G(t-2)  |  C(t-3)
-    // G(l) needs the sets S2(l-1) wrote one launch before; C(l) needs R(l) and G(l).
-    for (int t = 0; t < n_layers + 3; ++t) {
-        LaunchPlan p = pl.blank();
-        if (t < n_layers) pl.add_r(p, io_of(t));
-        if (t - 1 >= 0 && t - 1 < n_layers) pl.add_s1(p, io_of(t - 1));
-        if (t - 2 >= 0 && t - 2 < n_layers) {
-            pl.add_s2(p, io_of(t - 2));
-            pl.add_g(p, io_of(t - 2));
-        }
-        if (t - 3 >= 0 && t - 3 < n_layers) pl.add_c(p, io_of(t - 3));
-        if ((rc = submit(ctx, p, stream)) != LYCHEE_OK) return rc;
+    LayerDesc &fin = descs[n_layers];
+    memset(&fin, 0, sizeof fin);
+    for (int g = 0; g < shape->n_kv_heads; ++g) {
+        fin.rindex[g] = 0xFF;
+        fin.idx_src[g] = cur[g];
+    }
+    fin.idx_out = idx_out;
+    fin.copy_keep = 1;
+    const bool assemble = idx_out != nullptr;
+    // the last layer's selection is only needed if the caller wants the final sets
+    const int n_select = assemble ? n_layers : n_layers - 1;
+
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+
+    const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && (int64_t)n_layers * shape->batch <= kMaxItems;
+    if (!phased) {
+        int max_rg = 1;
+        for (int l = 0; l < n_layers; ++l) max_rg = descs[l].n_rgroups > max_rg ? descs[l].n_rgroups : max_rg;
+        L.choose_slices((int64_t)shape->batch * max_rg);
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = run_layer(L, l, l < n_select)) != LYCHEE_OK) return rc;
+    } else {
+        int64_t rows = 0;
+        for (int l = 0; l < n_select; ++l) rows += (int64_t)shape->batch * descs[l].n_rgroups;
+        L.choose_slices(rows);
+        // All layers at once, one launch per phase; each phase needs only earlier phases:
+        //   R (streaming, every layer)  ->  S1  ->  S2  ->  G (gather)  ->  C (combine)
+        Ranges r;
+        r.r_first = 0, r.r_count = n_layers;
+        if ((rc = L.go(r)) != LYCHEE_OK) return rc;
+        Ranges s1;
+        s1.s1_first = 0, s1.s1_count = n_select;
+        if ((rc = L.go(s1)) != LYCHEE_OK) return rc;
+        Ranges s2;
+        s2.s2_first = 0, s2.s2_count = n_select;
+        if ((rc = L.go(s2)) != LYCHEE_OK) return rc;
+        Ranges g;
+        g.g_first = 0, g.g_count = n_layers;
+        if ((rc = L.go(g)) != LYCHEE_OK) return rc;
+        Ranges c;
+        c.c_first = 0, c.c_count = n_layers;
+        if (assemble) c.s2_first = n_layers, c.s2_count = 1;  // the set copies ride along
+        if ((rc = L.go(c)) != LYCHEE_OK) return rc;
+    }
+    if (assemble && !phased) {
+        Ranges f;
+        f.s2_first = n_layers, f.s2_count = 1;
+        if ((rc = L.go(f)) != LYCHEE_OK) return rc;
     }
     return LYCHEE_OK;
 }
@@ -513,8 +584,9 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
         if (value < 1 || value > 3) return LYCHEE_EINVAL;
         ctx->wg_per_cu = value;
         return LYCHEE_OK;
-    case LYCHEE_OPT_PIPELINE:
-        ctx->pipeline = value != 0;
+    case LYCHEE_OPT_STEP_MODE:
+        if (value != LYCHEE_STEP_PHASED && value != LYCHEE_STEP_LAYERWISE) return LYCHEE_EINVAL;
+        ctx->step_mode = value;
         return LYCHEE_OK;
     case LYCHEE_OPT_N_WG:
         if (value < 0 || value > kWsWg) return LYCHEE_EINVAL;
@@ -523,15 +595,6 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
     case LYCHEE_OPT_GATHER_BLOCK:
         if (value < 16 || value > 128 || value % 16) return LYCHEE_EINVAL;
         ctx->g_block_rows = value;
-        return LYCHEE_OK;
-    case LYCHEE_OPT_COST_S2:
-    case LYCHEE_OPT_COST_C:
-    case LYCHEE_OPT_COST_S1:
-        if (value < 0 || value > 4096) return LYCHEE_EINVAL;
-        (option == LYCHEE_OPT_COST_S2 ? ctx->cost_s2 : option == LYCHEE_OPT_COST_C ? ctx->cost_c : ctx->cost_s1) = value;
-        // the kernel's balancing needs costs that do not increase from S2 to C to S1
-        if (ctx->cost_c > ctx->cost_s2) ctx->cost_c = ctx->cost_s2;
-        if (ctx->cost_s1 > ctx->cost_c) ctx->cost_s1 = ctx->cost_c;
         return LYCHEE_OK;
     default:
         return LYCHEE_EINVAL;
@@ -593,7 +656,7 @@ const char *lychee_strerror(int code)
     switch (code) {
     case LYCHEE_OK: return "ok";
     case LYCHEE_EINVAL: return "invalid argument";
-    case LYCHEE_EUNSUPPORTED: return "unsupported shape (head_dim must be 128, at most 4 query heads per KV head, at most 64 KV heads, batch at most 256)";
+    case LYCHEE_EUNSUPPORTED: return "unsupported shape (head_dim must be 128, at most 4 query heads per KV head, at most 64 KV heads, batch at most 256, fewer than 128 layers per step)";
     case LYCHEE_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LYCHEE_EHIP: return "HIP runtime error";
     default: return "unknown error";

@@ -20,83 +20,62 @@ constexpr int kBlockRows = kWaves * kTileRows;  // cache rows per block of the p
 constexpr int kSliceQuantum = kThreads * 4;     // select-filter slices are multiples of this
 constexpr int kMaxWg = 1024;             // upper bound of the grid of one launch
 constexpr int kIdxChunk = 2048;          // set entries staged in LDS at a time
-constexpr int kSlices = 32;              // slices of one score row in the select filter
+constexpr int kSlices = 32;              // most slices of one score row in the select filter
 constexpr int kSampleBlocks = 64;        // the threshold sample: 64 blocks of 64 scores
 constexpr int kSample = 4096;
 constexpr float kMinusBig = -1.0e30f;    // "no score yet" sentinel of the running maximum
+
+constexpr int kMaxLayers = 128;          // layers one launch can cover
+constexpr int kMaxItems = 2048;          // (layer, sequence) pairs of one launch's pooled rows
 
 // What every part of a launch shares.
 struct Common {
     const int32_t *lengths;
     int64_t stride_b, stride_h, stride_t;
     int32_t batch, n_q_heads, n_kv_heads, group;
-    int32_t k, max_len, sel_stride, list_cap;  // list_cap: capacity of one filter slice
-    int32_t n_wg;        // grid size of this launch
-    int32_t part_stride; // partial slots per head
+    int32_t k, max_len, sel_stride;
+    int32_t list_row;     // entries of one score row's filtered list
+    int32_t n_slices;     // slices one score row is filtered in (a power of two <= kSlices)
+    int32_t n_wg;         // grid size of this launch
+    int32_t part_stride;  // partial slots per head
     int32_t g_block_rows; // set entries per pooled block of gather work (fewer than kBlockRows:
                           // a gathered row costs more than a streamed one)
-    int32_t cost_s2, cost_c, cost_s1;  // small-unit costs, in blocks of pooled work
-    float scale;         // 1 / sqrt(head_dim)
-    float scale_log2e;   // log2(e) / sqrt(head_dim)
+    float scale;          // 1 / sqrt(head_dim)
+    float scale_log2e;    // log2(e) / sqrt(head_dim)
 };
 
-// Retrieval streaming (Eq. 1, o = A V, selection scores) of one layer.
-struct RPart {
+// Everything about one layer that any unit kind needs.  A table of these lives in device
+// memory; a launch names the layer ranges its unit kinds cover.
+struct LayerDesc {
     const uint16_t *q, *k_cache, *v_cache;
-    float *sel;           // [B][n_rgroups][sel_stride]
-    float *part_o;        // [B*H_q][part_stride][128]
-    float *part_ml;       // [B*H_q][part_stride][2]
-    int32_t *part_count;  // [B*H_q]
-    int32_t enabled, n_rgroups, emit_sel;
+    uint16_t *out;         // bf16 [B][H_q][128]
+    float *sel;            // [B][n_rgroups][sel_stride] pooled selection scores (scaled logits)
+    float *part_o;         // [B*H_q][part_stride][128] un-normalised partial outputs
+    float *part_ml;        // [B*H_q][part_stride][2]   running maximum (raw dot units) and sum
+    int32_t *part_count;   // [B*H_q] partial slots in use
+    uint2 *list;           // [B*n_rgroups][list_row] filtered (ordered key, position), slice by slice
+    int32_t *list_count;   // [B*n_rgroups][kSlices]
+    int32_t *idx_out;      // [B][H_kv][k] where this layer's sets are written
+    const int32_t *idx_src[kMaxKvHeads];  // per KV head: base of the [B][H_kv][k] array that
+                                          // holds the set this layer inherits for that head
+    int32_t n_rgroups, n_sgroups;
+    int32_t emit_sel;      // R units write selection scores
+    int32_t copy_keep;     // S2 also copies the inherited sets of heads that keep theirs
     uint8_t rgroup[kMaxKvHeads];  // KV heads whose group holds a retrieval head
-    uint8_t rmask[kMaxKvHeads];   // per KV head: bit i = query head g*G+i is a retrieval head
-};
-
-// Sparse gather attention (Eq. 3) of one layer.
-struct GPart {
-    const uint16_t *q, *k_cache, *v_cache;
-    const int32_t *idx;   // [B][H_kv][k] inherited sets
-    float *part_o, *part_ml;
-    int32_t *part_count;
-    int32_t enabled, n_sgroups;
     uint8_t sgroup[kMaxKvHeads];  // KV heads whose group holds a sparse head
-    uint8_t rmask[kMaxKvHeads];
-};
-
-// Merge of the partials of one layer into its bf16 output.
-struct CPart {
-    const float *part_o, *part_ml;
-    const int32_t *part_count;
-    uint16_t *out;  // bf16 [B][H_q][128]
-    int32_t enabled;
-};
-
-// Select, phase 1: threshold from a sample, ordered filter of every slice into a list.
-struct S1Part {
-    const float *sel;
-    uint2 *list;          // [B*n_rgroups][kSlices][list_cap] (ordered key, position)
-    int32_t *list_count;  // [B*n_rgroups][kSlices]
-    int32_t enabled, n_rgroups;
-};
-
-// Select, phase 2: exact radix select over the filtered list, ordered write of the set.
-struct S2Part {
-    const float *sel;
-    const uint2 *list;
-    const int32_t *list_count;
-    const int32_t *idx_in;
-    int32_t *idx_out;
-    int32_t enabled, n_rgroups;
+    uint8_t rmask[kMaxKvHeads];   // per KV head: bit i = query head g*G+i is a retrieval head
     uint8_t rindex[kMaxKvHeads];  // position of KV head g among the retrieval groups, 0xFF = none
 };
 
+// Kernel argument: the layer ranges [first, first + count) of each unit kind.
 struct LaunchPlan {
     Common c;
-    RPart r;
-    GPart g;
-    CPart comb;
-    S1Part s1;
-    S2Part s2;
+    const LayerDesc *layers;
+    int32_t r_first, r_count;    // retrieval streaming
+    int32_t g_first, g_count;    // sparse gather
+    int32_t c_first, c_count;    // combine
+    int32_t s1_first, s1_count;  // select phase 1
+    int32_t s2_first, s2_count;  // select phase 2 (and set copies)
 };
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream);

@@ -7,17 +7,18 @@
 //   S1 select, phase 1       threshold from a sample of the scores, ordered filter into a list
 //   S2 select, phase 2       exact radix select over the list (ties to the lower position),
 //                            ordered write of the set; verbatim copy for groups that keep theirs
-// The parts of one launch are mutually independent (they may belong to different layers of a
-// decode step); everything that depends on another part's result runs in a later launch, so
-// there are no device-side waits, fences or atomics on global memory.
+// A launch names, for each kind, the range of layers it covers in a table of layer
+// descriptors in device memory.  The units of one launch are mutually independent;
+// everything that depends on another unit's result runs in a later launch, so there are no
+// device-side waits, fences or atomics on global memory.
 //
 // Pooling (App. C describes pooling full and sparse block work into uniform splits).  The R
-// and G rows of a launch form one row space cut into 64-row blocks.  Every workgroup first
-// runs its few small units (C, S1, S2: distributed round-robin, most expensive first), then
-// an equal share of the pooled blocks, reduced by the cost of its small units, so that all
-// workgroups finish together.  A share is a contiguous run of blocks and may cross from one
-// (sequence, KV head) segment into the next; each (workgroup, segment) piece leaves one
-// partial per head in a slot that depends only on the shapes, never on timing.
+// and G rows of a launch, over all its layers, sequences and KV heads, form one row space
+// cut into blocks of 64 rows (fewer for gathered rows, which cost more); every workgroup
+// takes an equal, contiguous run of blocks.  A run may cross from one (layer, sequence, KV
+// head) segment into the next; each (workgroup, segment) piece leaves one partial per head in
+// a slot that depends only on the shapes, never on timing.  Small units (C, S1, S2) are
+// dealt round-robin.
 //
 // Data path of R and G.  Cache rows go from HBM to registers with 16-byte nontemporal loads:
 // a 64-lane wavefront covers 4 rows per load instruction (16 lanes x 16 bytes = one 256-byte
@@ -54,8 +55,8 @@ union SharedUnit {
     SharedCombine comb;
 };
 struct SharedPool {
-    int32_t a[kMaxWg + 1];        // first pooled block of every workgroup
-    int32_t bpre[kMaxBatch + 1];  // first pooled block of every sequence
+    int32_t ipre[kMaxItems + 1];         // first pooled block of every (layer, sequence) item
+    int32_t upre[4][kMaxLayers + 1];     // first small unit of every layer, per unit kind
     int32_t len[kMaxBatch];
     uint32_t scan[kWaves + 1];
     float fred[kWaves + 1];
@@ -481,7 +482,7 @@ __device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const ui
 // ------------------------------------------------------------------------------ C
 // out = (sum_s w_s o_s) / (sum_s w_s l_s),  w_s = 2^((m_s - M) log2(e)/sqrt(d)),  M = max_s m_s,
 // over the head's partial slots in ascending order (a fixed summation tree).
-__device__ __forceinline__ void combine_unit(const Common &c, const CPart &p, int bh, SharedCombine &sh,
+__device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p, int bh, SharedCombine &sh,
                                              SharedPool &pool)
 {
     int count = p.part_count[bh];
@@ -536,9 +537,9 @@ __device__ __forceinline__ void combine_unit(const Common &c, const CPart &p, in
 }
 
 // ------------------------------------------------------------------------------ S1 and S2
-__device__ __forceinline__ int slice_len_of(int L)
+__device__ __forceinline__ int slice_len_of(int L, int n_slices)
 {
-    const int per = (L + kSlices - 1) / kSlices;
+    const int per = (L + n_slices - 1) / n_slices;
     return (per + kSliceQuantum - 1) / kSliceQuantum * kSliceQuantum;
 }
 
@@ -581,14 +582,14 @@ __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t need, 
 // somewhat more than n = min(k, L) scores is read off a histogram of a fixed sample of the
 // row (every slice derives the same T0); the slice's scores >= T0 are written, in position
 // order, as (ordered key, position) pairs.
-__device__ __forceinline__ void select1_unit(const Common &c, const S1Part &p, int b, int rgi, int slice,
+__device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p, int b, int rgi, int slice,
                                              SharedSelect &sh, SharedPool &pool)
 {
     const int L = clamp_len(c.lengths[b], c.max_len);
     const int n = c.k < L ? c.k : L;
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     int32_t *count_out = p.list_count + row * kSlices + slice;
-    const int slen = slice_len_of(L);
+    const int slen = slice_len_of(L, c.n_slices);
     const int s0 = slice * slen;
     if (n == L || s0 >= L) {  // everything is selected, or the slice is empty
         if (threadIdx.x == 0) *count_out = 0;
@@ -599,8 +600,8 @@ __device__ __forceinline__ void select1_unit(const Common &c, const S1Part &p, i
     for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
     __syncthreads();
     const int n_sample = L <= kSample ? L : kSample;
+    float sv[kSample / kThreads];
     {
-        float sv[kSample / kThreads];
 #pragma unroll
         for (int u = 0; u < kSample / kThreads; ++u) {
             const int i = threadIdx.x + u * kThreads;
@@ -620,11 +621,25 @@ __device__ __forceinline__ void select1_unit(const Common &c, const S1Part &p, i
         const float f = (float)n_sample * (float)n / (float)L;
         target = (uint32_t)(f + 4.0f * sqrtf(f) + 8.0f);
     }
-    uint32_t digit = 0, rest;
-    if (target < (uint32_t)n_sample) find_digit<4096>(sh.hist, target, sh.found, pool.scan, digit, rest);
-    const uint32_t t0 = digit << 20;
+    uint32_t t0 = 0;
+    if (target < (uint32_t)n_sample) {
+        // the sample's target-th largest key, to 22 bits: top 12 bits, then the next 10
+        uint32_t d1, rest1, d2, rest2;
+        find_digit<4096>(sh.hist, target, sh.found, pool.scan, d1, rest1);
+        for (int i = threadIdx.x; i < 1024; i += kThreads) sh.hist[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kSample / kThreads; ++u) {
+            const uint32_t key = ordered_key(sv[u]);
+            if (threadIdx.x + u * kThreads < n_sample && (key >> 20) == d1)
+                atomicAdd(&sh.hist[(key >> 10) & 1023u], 1u);
+        }
+        __syncthreads();
+        find_digit<1024>(sh.hist, rest1, sh.found, pool.scan, d2, rest2);
+        t0 = (d1 << 20) | (d2 << 10);
+    }
     // ---- ordered filter of the slice
-    uint2 *dst = p.list + (row * kSlices + slice) * (int64_t)c.list_cap;
+    uint2 *dst = p.list + row * (int64_t)c.list_row + (int64_t)slice * slen;
     const int s1 = s0 + slen < L ? s0 + slen : L;
     uint32_t base = 0;
     const int n_it = (s1 - s0 + kThreads * 4 - 1) / (kThreads * 4);
@@ -661,7 +676,7 @@ __device__ __forceinline__ void select1_unit(const Common &c, const S1Part &p, i
     if (threadIdx.x == 0) *count_out = (int32_t)base;
 }
 
-constexpr int kS2Regs = 32;  // candidates one thread keeps in registers in the fast path
+constexpr int kS2Regs = 40;  // candidates one thread keeps in registers in the fast path
 
 // Radix select + ordered compaction straight from memory (any number of candidates).
 template <typename Fetch>
@@ -677,10 +692,17 @@ __device__ __forceinline__ void select2_slow(const Common &c, int n, int total, 
         const uint32_t digit_mask = (uint32_t)n_bins - 1u;
         for (int i = threadIdx.x; i < n_bins; i += kThreads) sh.hist[i] = 0;
         __syncthreads();
-        for (int i = threadIdx.x; i < total; i += kThreads) {
-            uint32_t key, pos;
-            fetch(i, key, pos);
-            if ((key & prefix_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kThreads) {
+            uint32_t key[8], pos[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                fetch(i < total ? i : total - 1, key[u], pos[u]);  // unconditional: loads overlap
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (i0 + u * kThreads < total && (key[u] & prefix_mask) == prefix)
+                    atomicAdd(&sh.hist[(key[u] >> shift) & digit_mask], 1u);
         }
         __syncthreads();
         uint32_t digit, rest;
@@ -731,14 +753,14 @@ __device__ __forceinline__ void select2_slow(const Common &c, int n, int total, 
 
 // Phase 2 for KV head (b, g): exact top-n of the row from the filtered list (or from the raw
 // scores when the list is too short), ties to the lower position, written ascending.
-__device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, int b, int g,
+__device__ __forceinline__ void select2_unit(const Common &c, const LayerDesc &p, int b, int g,
                                              SharedSelect &sh, SharedPool &pool)
 {
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
     const int rgi = p.rindex[g];
     if (rgi == 0xFF) {  // no retrieval head in the group: the set is handed on unchanged
-        const int32_t *src = p.idx_in + bg * c.k;
+        const int32_t *src = p.idx_src[g] + bg * c.k;
         for (int i = threadIdx.x; i < c.k; i += kThreads) dst[i] = src[i];
         return;
     }
@@ -750,13 +772,14 @@ __device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, i
     }
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     const float *sel = p.sel + row * c.sel_stride;
-    const uint2 *list = p.list + row * kSlices * (int64_t)c.list_cap;
+    const uint2 *list = p.list + row * (int64_t)c.list_row;
+    const int slen = slice_len_of(L, c.n_slices);
     __syncthreads();
     if (threadIdx.x < 64) {  // one slice count per lane, prefix sum inside the wavefront
         int cnt = 0;
-        if (threadIdx.x < kSlices) {
+        if (threadIdx.x < c.n_slices) {
             cnt = p.list_count[row * kSlices + threadIdx.x];
-            cnt = cnt < 0 ? 0 : (cnt > c.list_cap ? c.list_cap : cnt);
+            cnt = cnt < 0 ? 0 : (cnt > slen ? slen : cnt);
         }
         int incl = cnt;
 #pragma unroll
@@ -769,6 +792,7 @@ __device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, i
     }
     __syncthreads();
     int total = sh.slice_pre[kSlices];
+    TRACE(5);
     const bool raw = total < n;  // the sampled threshold kept too few: rank the raw row
     if (raw) total = L;
     // element i of the candidate sequence (ascending by position in both cases)
@@ -781,7 +805,7 @@ __device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, i
 #pragma unroll
             for (int step = kSlices / 2; step >= 1; step >>= 1)
                 if (sh.slice_pre[lo + step] <= i) lo += step;
-            const uint2 e = list[(int64_t)lo * c.list_cap + (i - sh.slice_pre[lo])];
+            const uint2 e = list[(int64_t)lo * slen + (i - sh.slice_pre[lo])];
             key = e.x;
             pos = e.y;
         }
@@ -800,6 +824,8 @@ __device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, i
             if (e < per && i < total) fetch(i, keys[e], poss[e]);
         }
         uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)n;
+        if (keys[0] == 0xDEADBEEFu) prefix = 1;  // (trace builds: forces the loads to land here)
+        TRACE(6);
 #pragma unroll
         for (int pass = 0; pass < 3; ++pass) {
             const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
@@ -822,6 +848,7 @@ __device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, i
             need = rest;
         }
         const uint32_t T = prefix, r_eq = need;
+        TRACE(7);
         uint32_t cnt_gt = 0, cnt_eq = 0;
 #pragma unroll
         for (int e = 0; e < kS2Regs; ++e) {
@@ -851,162 +878,163 @@ __device__ __forceinline__ void select2_unit(const Common &c, const S2Part &p, i
 }
 
 // ------------------------------------------------------------------------------ the kernel
+// Largest i in [0, n) with pre[i] <= x, for a non-decreasing pre[0..n] with pre[0] <= x < pre[n].
+__device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pre[mid] <= x) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
 __global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan P)
 {
     __shared__ SharedUnit su;
     __shared__ SharedPool pool;
     const Common &c = P.c;
+    const LayerDesc *layers = P.layers;
     const int w = blockIdx.x;
     const int W = c.n_wg;
     TRACE(0);
 
-    // ---- small units: kinds in order of decreasing cost, unit j runs on workgroup j mod W
-    const int n_s2r = P.s2.enabled ? c.batch * P.s2.n_rgroups : 0;
-    const int n_c = P.comb.enabled ? c.batch * c.n_q_heads : 0;
-    const int n_s1 = P.s1.enabled ? c.batch * P.s1.n_rgroups * kSlices : 0;
-    const int n_s2c = P.s2.enabled ? c.batch * (c.n_kv_heads - P.s2.n_rgroups) : 0;
-    const int n_small = n_s2r + n_c + n_s1 + n_s2c;
-    for (int j = w; j < n_small; j += W) {
-        int u = j;
-        if (u < n_s2r) {  // u-th (sequence, retrieval group)
-            const int b = u / P.s2.n_rgroups;
-            int want = u % P.s2.n_rgroups, g = 0;
-            for (int gg = 0; gg < c.n_kv_heads; ++gg)
-                if (P.s2.rindex[gg] == want) g = gg;
-            select2_unit(c, P.s2, b, g, su.sel, pool);
-        } else if ((u -= n_s2r) < n_c) {
-            combine_unit(c, P.comb, u, su.comb, pool);
-        } else if ((u -= n_c) < n_s1) {
-            const int slice = u % kSlices;
-            const int rgi = (u / kSlices) % P.s1.n_rgroups;
-            const int b = u / (kSlices * P.s1.n_rgroups);
-            select1_unit(c, P.s1, b, rgi, slice, su.sel, pool);
-        } else {  // (u - n_s1)-th (sequence, group that keeps its set)
-            u -= n_s1;
-            const int n_keep = c.n_kv_heads - P.s2.n_rgroups;
-            const int b = u / n_keep;
-            int want = u % n_keep, g = 0;
-            for (int gg = 0; gg < c.n_kv_heads; ++gg)
-                if (P.s2.rindex[gg] == 0xFF && want-- == 0) g = gg;
-            select2_unit(c, P.s2, b, g, su.sel, pool);
+    // ---- small units.  Kinds in a fixed order (S2 on retrieval groups, C, S1, S2 set
+    // copies); within a kind layer by layer; unit j runs on workgroup j mod W.
+    if (P.s2_count + P.c_count + P.s1_count > 0) {
+        uint32_t cnt[4] = {0, 0, 0, 0};
+        const int t = threadIdx.x;
+        if (t < P.s2_count) {
+            const LayerDesc &L = layers[P.s2_first + t];
+            cnt[0] = (uint32_t)(c.batch * L.n_rgroups);
+            cnt[3] = L.copy_keep ? (uint32_t)(c.batch * (c.n_kv_heads - L.n_rgroups)) : 0u;
+        }
+        if (t < P.c_count) cnt[1] = (uint32_t)(c.batch * c.n_q_heads);
+        if (t < P.s1_count) cnt[2] = (uint32_t)(c.batch * layers[P.s1_first + t].n_rgroups * c.n_slices);
+        uint32_t tot[4];
+#pragma unroll
+        for (int kd = 0; kd < 4; ++kd) {
+            const uint32_t incl = block_scan(cnt[kd], pool.scan, tot[kd]);
+            if (t < kMaxLayers) pool.upre[kd][t + 1] = (int32_t)incl;
+            if (t == 0) pool.upre[kd][0] = 0;
         }
         __syncthreads();
+        const int n_small = (int)(tot[0] + tot[1] + tot[2] + tot[3]);
+        for (int j = w; j < n_small; j += W) {
+            int u = j;
+            if (u < (int)tot[0]) {
+                const int li = find_item(pool.upre[0], P.s2_count, u);
+                const LayerDesc &L = layers[P.s2_first + li];
+                u -= pool.upre[0][li];
+                const int b = u / L.n_rgroups;
+                select2_unit(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
+            } else if ((u -= (int)tot[0]) < (int)tot[1]) {
+                const int li = u / (c.batch * c.n_q_heads);
+                combine_unit(c, layers[P.c_first + li], u % (c.batch * c.n_q_heads), su.comb, pool);
+            } else if ((u -= (int)tot[1]) < (int)tot[2]) {
+                const int li = find_item(pool.upre[2], P.s1_count, u);
+                const LayerDesc &L = layers[P.s1_first + li];
+                u -= pool.upre[2][li];
+                const int slice = u % c.n_slices;
+                const int rgi = (u / c.n_slices) % L.n_rgroups;
+                const int b = u / (c.n_slices * L.n_rgroups);
+                select1_unit(c, L, b, rgi, slice, su.sel, pool);
+            } else {  // copy of the set of a KV head whose group holds no retrieval head
+                u -= (int)tot[2];
+                const int li = find_item(pool.upre[3], P.s2_count, u);
+                const LayerDesc &L = layers[P.s2_first + li];
+                u -= pool.upre[3][li];
+                const int n_keep = c.n_kv_heads - L.n_rgroups;
+                const int b = u / n_keep;
+                int want = u % n_keep, g = 0;
+                for (int gg = 0; gg < c.n_kv_heads; ++gg)
+                    if (L.rindex[gg] == 0xFF && want-- == 0) g = gg;
+                select2_unit(c, L, b, g, su.sel, pool);
+            }
+            __syncthreads();
+        }
     }
     TRACE(1);
-    if (!P.r.enabled && !P.g.enabled) return;
+    const int n_items = (P.r_count + P.g_count) * c.batch;
+    if (n_items == 0) return;
 
-    // ---- the pooled row space: per sequence, n_rgroups R segments then n_sgroups G segments
-    const int n_rg = P.r.enabled ? P.r.n_rgroups : 0;
-    const int n_sg = P.g.enabled ? P.g.n_sgroups : 0;
+    // ---- the pooled row space: R items (layer, sequence) then G items, each item holding
+    // one segment per retrieval (sparse) KV head of the layer
+    if (threadIdx.x < c.batch) pool.len[threadIdx.x] = clamp_len(c.lengths[threadIdx.x], c.max_len);
+    __syncthreads();
     {
-        uint32_t blocks = 0;
-        if (threadIdx.x < c.batch) {
-            const int L = clamp_len(c.lengths[threadIdx.x], c.max_len);
-            pool.len[threadIdx.x] = L;
-            const int kk = c.k < L ? c.k : L;
-            blocks = (uint32_t)(n_rg * ((L + kBlockRows - 1) / kBlockRows) +
-                                n_sg * ((kk + c.g_block_rows - 1) / c.g_block_rows));
+        constexpr int kPer = kMaxItems / kThreads;
+        uint32_t blocks[kPer], sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int it = threadIdx.x * kPer + i;
+            blocks[i] = 0;
+            if (it < n_items) {
+                const int li = it / c.batch;
+                const int L = pool.len[it % c.batch];
+                if (li < P.r_count) {
+                    blocks[i] = (uint32_t)(layers[P.r_first + li].n_rgroups * ((L + kBlockRows - 1) / kBlockRows));
+                } else {
+                    const int kk = c.k < L ? c.k : L;
+                    blocks[i] = (uint32_t)(layers[P.g_first + li - P.r_count].n_sgroups *
+                                           ((kk + c.g_block_rows - 1) / c.g_block_rows));
+                }
+            }
+            sum += blocks[i];
         }
         uint32_t total;
-        const uint32_t incl = block_scan(blocks, pool.scan, total);
-        if (threadIdx.x < c.batch) pool.bpre[threadIdx.x + 1] = (int32_t)incl;
-        if (threadIdx.x == 0) pool.bpre[0] = 0;
-    }
-    __syncthreads();
-    const int T = pool.bpre[c.batch];
-    {
-        // cost of the small units of this thread's kPer consecutive workgroups
-        // (non-increasing in the workgroup index)
-        constexpr int kPer = kMaxWg / kThreads;
-        uint32_t comp[kPer], comp_sum = 0;
+        uint32_t at = block_scan(sum, pool.scan, total) - sum;
+        if (threadIdx.x == 0) pool.ipre[0] = 0;
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int ww = threadIdx.x * kPer + i;
-            comp[i] = 0;
-            if (ww < W)
-                for (int j = ww; j < n_small; j += W)
-                    comp[i] += j < n_s2r ? c.cost_s2 : (j < n_s2r + n_c ? c.cost_c : (j < n_s2r + n_c + n_s1 ? c.cost_s1 : 0));
-            comp_sum += comp[i];
-        }
-        uint32_t all_comp;
-        block_scan(comp_sum, pool.scan, all_comp);
-        const uint32_t base_share = ((uint32_t)T + all_comp + (uint32_t)W - 1u) / (uint32_t)W;
-        uint32_t share[kPer], share_sum = 0;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            const int ww = threadIdx.x * kPer + i;
-            share[i] = (ww < W && base_share > comp[i]) ? base_share - comp[i] : 0u;
-            share_sum += share[i];
-        }
-        uint32_t dummy;
-        uint32_t at = block_scan(share_sum, pool.scan, dummy) - share_sum;
-        if (threadIdx.x == 0) pool.a[0] = 0;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            at += share[i];
-            const int ww = threadIdx.x * kPer + i;
-            if (ww < kMaxWg) pool.a[ww + 1] = (int32_t)at;
+            at += blocks[i];
+            pool.ipre[threadIdx.x * kPer + i + 1] = (int32_t)at;
         }
     }
     __syncthreads();
-    int x = pool.a[w];
-    int x1 = pool.a[w + 1];
+    const int T = pool.ipre[n_items];
+    const int share = (T + W - 1) / W;  // every workgroup takes `share` consecutive blocks
+    int x = w * share;
+    int x1 = x + share;
     x1 = x1 < T ? x1 : T;
     TRACE(2);
 
     while (x < x1) {
-        int b = 0;
-        while (pool.bpre[b + 1] <= x) ++b;
-        const int L = pool.len[b];
-        const int kk = c.k < L ? c.k : L;
-        const int nb_r = (L + kBlockRows - 1) / kBlockRows;
-        const int nb_g = (kk + c.g_block_rows - 1) / c.g_block_rows;
-        int xo = x - pool.bpre[b];
-        const bool gather = xo >= n_rg * nb_r;
-        int gi, blk, nb, seg_rows, seg_start;
-        if (!gather) {
-            gi = xo / nb_r;
-            blk = xo % nb_r;
-            nb = nb_r;
-            seg_rows = L;
-            seg_start = pool.bpre[b] + gi * nb_r;
-        } else {
-            xo -= n_rg * nb_r;
-            gi = xo / nb_g;
-            blk = xo % nb_g;
-            nb = nb_g;
-            seg_rows = kk;
-            seg_start = pool.bpre[b] + n_rg * nb_r + gi * nb_g;
-        }
+        const int it = find_item(pool.ipre, n_items, x);
+        const int li = it / c.batch;
+        const int b = it % c.batch;
+        const bool gather = li >= P.r_count;
+        const LayerDesc &L = gather ? layers[P.g_first + li - P.r_count] : layers[P.r_first + li];
+        const int len_b = pool.len[b];
+        const int seg_rows = gather ? (c.k < len_b ? c.k : len_b) : len_b;
+        const int brows = gather ? c.g_block_rows : kBlockRows;
+        const int nb = (seg_rows + brows - 1) / brows;  // blocks per segment of this item
+        const int xo = x - pool.ipre[it];
+        const int gi = xo / nb;
+        const int blk = xo % nb;
+        const int seg_start = pool.ipre[it] + gi * nb;
         int len = x1 - x;
         len = len < nb - blk ? len : nb - blk;
-        const int brows = gather ? c.g_block_rows : kBlockRows;
         const int r0 = blk * brows;
         int r1 = (blk + len) * brows;
         r1 = r1 < seg_rows ? r1 : seg_rows;
-        // slot = distance to the first workgroup whose share reaches into this segment
-        int lo = 0, hi = W - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (pool.a[mid + 1] > seg_start) hi = mid; else lo = mid + 1;
-        }
-        const int slot = w - lo;
+        const int slot = w - seg_start / share;  // pieces of a segment sit on consecutive workgroups
         const bool ends = blk + len == nb;
         const uint32_t gmask = (1u << c.group) - 1u;
         if (!gather) {
-            const int g = P.r.rgroup[gi];
-            const uint32_t hmask = P.r.rmask[g] & gmask;
-            float *sel_row = P.r.emit_sel ? P.r.sel + ((int64_t)b * P.r.n_rgroups + gi) * c.sel_stride : nullptr;
-            dispatch_piece<false>(__builtin_popcount(hmask), c, P.r.q, P.r.k_cache, P.r.v_cache, nullptr,
-                                  sel_row, P.r.part_o, P.r.part_ml, P.r.part_count, b, g, hmask, L, r0, r1,
-                                  slot, ends, su.attn);
+            const int g = L.rgroup[gi];
+            const uint32_t hmask = L.rmask[g] & gmask;
+            float *sel_row = L.emit_sel ? L.sel + ((int64_t)b * L.n_rgroups + gi) * c.sel_stride : nullptr;
+            dispatch_piece<false>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, nullptr, sel_row,
+                                  L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
+                                  su.attn);
         } else {
-            const int g = P.g.sgroup[gi];
-            const uint32_t hmask = ~(uint32_t)P.g.rmask[g] & gmask;
-            const int32_t *idx_src = P.g.idx + ((int64_t)b * c.n_kv_heads + g) * c.k;
-            dispatch_piece<true>(__builtin_popcount(hmask), c, P.g.q, P.g.k_cache, P.g.v_cache, idx_src,
-                                 nullptr, P.g.part_o, P.g.part_ml, P.g.part_count, b, g, hmask, L, r0, r1,
-                                 slot, ends, su.attn);
+            const int g = L.sgroup[gi];
+            const uint32_t hmask = ~(uint32_t)L.rmask[g] & gmask;
+            const int32_t *idx_src = L.idx_src[g] + ((int64_t)b * c.n_kv_heads + g) * c.k;
+            dispatch_piece<true>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, idx_src, nullptr,
+                                 L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
+                                 su.attn);
         }
         x += len;
         TRACE(3);

@@ -68,6 +68,9 @@ def test_workspace_size(lb):
     # selection scores alone need B * H_kv * L * 4 bytes
     assert big >= 8 * 131072 * 4
     assert big < 256 * 2 ** 20
+    s = lb.make_shape(1, 32, 8, 131072, 4096)
+    assert lb.step_workspace_bytes(s, 36) == 36 * big
+    assert lb.step_workspace_bytes(s, 0) == 0 and lb.step_workspace_bytes(s, 1000) == 0
 
 
 def test_error_strings(lb):

@@ -185,19 +185,19 @@ def test_result_does_not_depend_on_the_grid_size_and_is_deterministic(ctx):
     dl = H.DeviceLayer(inp, w.k, idx_in)
     results = []
     try:
-        for wg_per_cu, costs in [(2, (3, 1, 1)), (1, (3, 1, 1)), (3, (0, 0, 0)), (2, (40, 20, 9)), (2, (3, 1, 1))]:
+        for wg_per_cu, n_wg, gb in [(2, 0, 48), (1, 0, 48), (3, 0, 16), (2, 37, 128), (2, 1, 64), (2, 0, 48)]:
             ctx.set_option(lb.OPT_WG_PER_CU, wg_per_cu)
-            for opt, v in zip((lb.OPT_COST_S2, lb.OPT_COST_C, lb.OPT_COST_S1), costs):
-                ctx.set_option(opt, v)
+            ctx.set_option(lb.OPT_N_WG, n_wg)
+            ctx.set_option(lb.OPT_GATHER_BLOCK, gb)
             out, idx = H.run_hybrid(ctx, dl, inp.mask)
-            what = "wg_per_cu=%d costs=%s" % (wg_per_cu, costs)
+            what = "wg_per_cu=%d n_wg=%d gather_block=%d" % (wg_per_cu, n_wg, gb)
             H.assert_outputs_close(out, out_ref, what)
             H.assert_sets_match(idx, idx_ref, sel_ref, inp.mask, inp, w.k, idx_in, what)
             results.append((out, idx))
     finally:
         ctx.set_option(lb.OPT_WG_PER_CU, 2)
-        for opt, v in zip((lb.OPT_COST_S2, lb.OPT_COST_C, lb.OPT_COST_S1), (3, 1, 1)):
-            ctx.set_option(opt, v)
+        ctx.set_option(lb.OPT_N_WG, 0)
+        ctx.set_option(lb.OPT_GATHER_BLOCK, 48)
     for out, idx in results[1:]:
         assert (idx == results[0][1]).all()              # scores do not depend on the split
         assert np.abs(out - results[0][0]).max() <= 2 ** -6
@@ -227,8 +227,8 @@ def test_c4_batched_ragged(ctx):
 
 
 # ------------------------------------------------------------------ decode step (chaining)
-@pytest.mark.parametrize("pipeline", [1, 0])
-def test_decode_step_chains_sets_through_layers(ctx, pipeline):
+@pytest.mark.parametrize("mode", ["phased", "layerwise"])
+def test_decode_step_chains_sets_through_layers(ctx, mode):
     lb = H.binding()
     n_layers = 6
     w = wl.scaled(wl.WORKLOADS["c3"], max_len=4096, k=256, n_layers=n_layers, planted=64)
@@ -242,19 +242,19 @@ def test_decode_step_chains_sets_through_layers(ctx, pipeline):
         out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, w.k, idx)
         refs.append((out_ref, idx, sel_ref))
     shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 4096, w.k, kv=layers[0].k_cache)
-    ws = lb.alloc_workspace(shape)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
     ws.fill_(0xFF)
     outs = [torch.zeros_like(ly.q) for ly in layers]
     idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
     lens = torch.from_numpy(layers[0].lengths).cuda()
-    ctx.set_option(lb.OPT_PIPELINE, pipeline)
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED if mode == "phased" else lb.STEP_LAYERWISE)
     try:
         for rep in range(2):    # the second step reuses a workspace full of the first one's data
             ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
                             [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
             torch.cuda.synchronize()
     finally:
-        ctx.set_option(lb.OPT_PIPELINE, 1)
+        ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
     for l in range(n_layers):
         H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "step layer %d" % l)
     # the final sets: groups that selected in the last layer are checked against its scores,
@@ -287,7 +287,7 @@ def test_decode_step_with_given_sets_and_ragged_batch(ctx):
         out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, w.k, idx)
         refs.append((out_ref, idx, sel_ref))
     shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 3000, w.k, kv=layers[0].k_cache)
-    ws = lb.alloc_workspace(shape)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
     ws.fill_(0xFF)
     outs = [torch.zeros_like(ly.q) for ly in layers]
     lens = torch.from_numpy(lens_h).cuda()
