@@ -3,8 +3,14 @@
 
 A *step* is the attention of one whole decode step on the Qwen3-8B-shaped 128K workload
 (36 layers, 32 query / 8 KV heads, head dim 128, batch 1, k = 4096; layer 0 all-retrieval,
-layers 1..35 with 3 retrieval heads): one call of lychee_decode_step with all inputs
+layers 1..35 with 3 retrieval heads): one call of lychee_decode_step with every input
 already resident in HBM.  Prints ONE JSON line.
+
+  value      microseconds per step (whole job, one GPU)
+  roofline   the streaming launch of the work-unit kernel (it moves > 90 % of the bytes):
+             algorithmic bytes of that launch / its duration measured with HIP events on the
+             launch stream, against the 8 TB/s HBM peak
+  cpu_baseline  the fp64 CPU oracle timed on one whole step of the same workload
 """
 from __future__ import annotations
 
@@ -19,6 +25,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "lychee_units_kernel_c3_stream_pmc.txt")
+
+
+def measured_traffic():
+    """HBM bytes per streaming launch from the committed rocprofv3 --pmc summary, if any."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -29,8 +47,11 @@ def main() -> int:
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
-    ap.add_argument("--layerwise", action="store_true", help="decode step layer after layer")
+    ap.add_argument("--tail", type=int, default=-1)
+    ap.add_argument("--gather-block", type=int, default=0)
+    ap.add_argument("--layerwise", action="store_true", help="time the layer-after-layer step as `value`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="skip the dense and layerwise legs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not served (the path has no "
@@ -49,7 +70,10 @@ def main() -> int:
     ctx = lb.Context(0)
     if args.wg_per_cu:
         ctx.set_option(lb.OPT_WG_PER_CU, args.wg_per_cu)
-    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_LAYERWISE if args.layerwise else lb.STEP_PHASED)
+    if args.tail >= 0:
+        ctx.set_option(lb.OPT_TAIL_PERMILLE, args.tail)
+    if args.gather_block:
+        ctx.set_option(lb.OPT_GATHER_BLOCK, args.gather_block)
 
     t_gen = time.perf_counter()
     layers = [wl.make_layer(w, layer=l, device=dev) for l in range(n_layers)]
@@ -63,7 +87,7 @@ def main() -> int:
     outs = [torch.zeros_like(ly.q) for ly in layers]
     idx_final = torch.zeros((w.batch, w.n_kv_heads, w.k), dtype=torch.int32, device=dev)
     idx0 = None
-    if not masks[0].all():      # single-layer workloads: inherited sets = planted + leading rows
+    if not masks[0].all():      # single-layer workloads: some inherited sets to gather from
         idx0_h = np.tile(np.arange(w.k, dtype=np.int32), (w.batch, w.n_kv_heads, 1))
         for b in range(w.batch):
             idx0_h[b] = np.minimum(idx0_h[b], int(lens_h[b]) - 1)
@@ -89,44 +113,62 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    def set_mode(layerwise):
+        ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_LAYERWISE if layerwise else lb.STEP_PHASED)
+
     # ---- the timed region: exactly `steps` hybrid decode steps -------------------------
+    set_mode(args.layerwise)
     sec = timed(hybrid_step, args.steps, args.warmup)
 
-    # ---- per-kernel durations with HIP events on the launch stream (same steps again) ---
+    # ---- per-launch durations with HIP events on the launch stream (same steps again) ---
     ctx.timing_enable(True)
     for _ in range(args.steps):
         hybrid_step()
     ms_cls, n_cls = ctx.timing_read()
     ctx.timing_enable(False)
-    attn_us = 1e3 * ms_cls[lb.KERNEL_ATTN] / max(1, n_cls[lb.KERNEL_ATTN])
+    stream_us = 1e3 * ms_cls[lb.KERNEL_STREAM] / max(1, n_cls[lb.KERNEL_STREAM])
+    launches_per_step = {name: n_cls[i] // args.steps for i, name in
+                         enumerate(["stream", "gather", "select1", "select2", "combine"])}
 
-    # ---- the dense kernel on identical buffers ------------------------------------------
-    dense_sec = timed(dense_step, max(3, args.steps // 3), 1)
-
-    # ---- streaming-read ceiling of this machine ---------------------------------------------
+    # ---- the other step order, the dense kernel, the streaming-read ceiling ---------------
+    other_sec = dense_sec = None
+    if not args.quick:
+        set_mode(not args.layerwise)
+        other_sec = timed(hybrid_step, max(3, args.steps // 3), 1)
+        set_mode(args.layerwise)
+        dense_sec = timed(dense_step, max(3, args.steps // 3), 1)
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
     probe_bytes = ks[0].numel() * 2
+    n_probe = min(n_layers, 8)
+
     def probe():
-        for l in range(min(n_layers, 8)):
+        for l in range(n_probe):
             ctx.probe_read(ks[l], probe_bytes, sink)
     probe_sec = timed(probe, 5, 1)
-    read_ceiling = probe_bytes * min(n_layers, 8) / probe_sec / 1e9
+    read_ceiling = probe_bytes * n_probe / probe_sec / 1e9
 
     # ---- algorithmic bytes ---------------------------------------------------------------
+    # per step: every K+V row streamed or gathered (512 B), the fp32 selection score written
+    # and read once per streamed row, the index sets, q and out
     step_bytes = sum(wl.algorithmic_bytes(w, masks[l], lens_h) for l in range(n_layers))
     dense_bytes = n_layers * wl.dense_bytes(w, lens_h)
-    # the attention-units kernel alone: K+V rows streamed and gathered, the fp32 selection
-    # score written per streamed row, the inherited sets and q read
+    # per streaming launch: 512 B of K+V and 4 B of score per streamed row, plus q
     G = w.group
-    attn_bytes = 0
+    rows_streamed = 0
+    rows_gathered = 0
     for l in range(n_layers):
         n_r = sum(1 for g in range(w.n_kv_heads) if masks[l][g * G:(g + 1) * G].any())
         n_s = sum(1 for g in range(w.n_kv_heads) if (masks[l][g * G:(g + 1) * G] == 0).any())
-        for L in lens_h:
-            attn_bytes += n_r * int(L) * (512 + 4) + n_s * min(w.k, int(L)) * (512 + 4)
-        attn_bytes += w.batch * w.n_q_heads * 256
-    attn_bytes_per_launch = attn_bytes / n_layers
-    achieved = attn_bytes_per_launch / (attn_us * 1e-6) / 1e9 if attn_us > 0 else 0.0
+        rows_streamed += sum(n_r * int(L) for L in lens_h)
+        rows_gathered += sum(n_s * min(w.k, int(L)) for L in lens_h)
+    n_stream_launches = max(1, launches_per_step["stream"])
+    if args.layerwise:          # the streaming launch of a layer also carries its gathers
+        stream_bytes = (rows_streamed + rows_gathered) * 512 + rows_streamed * 4
+    else:
+        stream_bytes = rows_streamed * (512 + 4)
+    stream_bytes = (stream_bytes + n_layers * w.batch * w.n_q_heads * 256) / n_stream_launches
+    achieved = stream_bytes / (stream_us * 1e-6) / 1e9 if stream_us > 0 else 0.0
+    traffic = measured_traffic() if (args.workload == "c3" and not args.layerwise and not args.layers) else None
 
     result = {
         "metric": "us per decode-step attention (all layers) at 128K",
@@ -149,46 +191,43 @@ def main() -> int:
         "step_algorithmic_bytes": step_bytes,
         "step_achieved_gbps": round(step_bytes / sec / 1e9, 1),
         "step_hbm_frac": round(step_bytes / sec / 1e9 / HBM_PEAK_GBPS, 4),
-        "dense_us": round(dense_sec * 1e6, 2),
-        "dense_achieved_gbps": round(dense_bytes / dense_sec / 1e9, 1),
-        "speedup_vs_dense": round(dense_sec / sec, 3),
         "read_ceiling_gbps": round(read_ceiling, 1),
-        "kernel_us_per_step": {"attn": round(1e3 * ms_cls[0] / args.steps, 2),
-                               "combine": round(1e3 * ms_cls[1] / args.steps, 2),
-                               "select": round(1e3 * ms_cls[2] / args.steps, 2)},
+        "launches_per_step": launches_per_step,
+        "launch_us_per_step": {name: round(1e3 * ms_cls[i] / args.steps, 2) for i, name in
+                               enumerate(["stream", "gather", "select1", "select2", "combine"])},
         "paper_context": "paper reports up to 2.7x end-to-end TPOT speed-up over full attention at "
                          "128K, batch 1, budget 4096 (Sec. 4.3.1; GPU of that run not stated, kernel "
                          "study on one NVIDIA A800)",
-        "roofline": {"bound": "hbm", "kernel": "attn_units_kernel",
+        "roofline": {"bound": "hbm", "kernel": "lychee_units_kernel (streaming launch)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "avg_launch_us": round(attn_us, 2),
-                     "algorithmic_bytes_per_launch": int(attn_bytes_per_launch)},
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "avg_launch_us": round(stream_us, 2),
+                     "algorithmic_bytes_per_launch": int(stream_bytes)},
         "gen_seconds": round(t_gen, 1),
     }
+    if other_sec is not None:
+        result["layerwise_us" if not args.layerwise else "phased_us"] = round(other_sec * 1e6, 2)
+        result["dense_us"] = round(dense_sec * 1e6, 2)
+        result["dense_achieved_gbps"] = round(dense_bytes / dense_sec / 1e9, 1)
+        result["speedup_vs_dense"] = round(dense_sec / sec, 3)
 
     # ---- the CPU oracle on a bounded sample of the same workload --------------------------
     if not args.no_cpu_baseline:
         from oracle import lychee_oracle as lo
-        sample = [0, 1] if n_layers > 1 else [0]
-        t_layers = []
-        idx = None
-        for l in sample:
+        # every layer of the step, chained through its sets exactly like the GPU step; the
+        # device-to-host copies of the cache are outside the timed regions
+        t_cpu = 0.0
+        idx = None if masks[0].all() else idx0.cpu().numpy()
+        for l in range(n_layers):
             ly = layers[l]
             qb, kb, vb = (wl.bf16_bits(t) for t in (ly.q, ly.k_cache, ly.v_cache))
-            if idx is None and not masks[l].all():
-                idx = idx0.cpu().numpy()
             t0 = time.perf_counter()
             _, idx, _ = lo.decode_attn(qb, kb, vb, masks[l], w.k, idx, lens_h)
-            t_layers.append(time.perf_counter() - t0)
-        if n_layers > 1:
-            est = t_layers[0] + (n_layers - 1) * t_layers[1]
-            what = ("layers 0 (all-retrieval) and 1 (3 retrieval heads) of the same workload timed "
-                    "(%.2f s, %.2f s); step = layer0 + %d x layer1" % (t_layers[0], t_layers[1], n_layers - 1))
-        else:
-            est, what = t_layers[0], "the single layer of the workload"
-        result["cpu_baseline"] = {"value": round(est * 1e6, 0), "unit": "us", "cores": lo.num_threads(),
-                                  "kind": "oracle", "sample": what}
+            t_cpu += time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(t_cpu * 1e6, 0), "unit": "us", "cores": lo.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": "one whole step: all %d layers of the same workload, sets "
+                                            "chained layer to layer (%.2f s of oracle time)" % (n_layers, t_cpu)}
     print(json.dumps(result), flush=True)
     ctx.close()
     return 0

@@ -155,26 +155,31 @@ int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_
  *   WG_PER_CU     workgroups per compute unit in every launch (1..3, default 2)
  *   N_WG          workgroups per launch, overriding WG_PER_CU (0 = CUs x WG_PER_CU; at most 768)
  *   STEP_MODE     how lychee_decode_step orders its work (see there)
+ *   TAIL_PERMILLE permille of a launch's streaming / gather rows that workgroups claim
+ *                 dynamically, in small chunks, after their fixed share (0..1000, default 250; launches too short to hold several chunks per workgroup use none);
+ *                 it levels out compute units that stream at different speeds
  *   GATHER_BLOCK  set entries whose gather is balanced against 64 streamed rows (a multiple
  *                 of 16 in [16, 128], default 48: a gathered row costs more than a streamed one) */
 #define LYCHEE_OPT_WG_PER_CU    1
 #define LYCHEE_OPT_STEP_MODE    2
 #define LYCHEE_OPT_GATHER_BLOCK 6
 #define LYCHEE_OPT_N_WG         7
+#define LYCHEE_OPT_TAIL_PERMILLE 8
 #define LYCHEE_STEP_PHASED      1
 #define LYCHEE_STEP_LAYERWISE   0
 int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
 
-/* Per-kernel timing with HIP events on the caller's stream.  While enabled, every launch of
- * the library's kernels is bracketed by an event pair.  lychee_timing_read waits for the
- * recorded events, adds up the milliseconds and launches per launch class since the last
- * read and clears the record.  Every launch runs the same work-unit kernel; its class says
- * what it carried: 0 = streaming / gather work (plus whatever else shared the launch),
- * 1 = select phase 1 and combine only, 2 = select phase 2 only. */
-#define LYCHEE_KERNEL_ATTN    0
-#define LYCHEE_KERNEL_COMBINE 1
-#define LYCHEE_KERNEL_SELECT  2
-#define LYCHEE_N_KERNEL_CLASSES 3
+/* Per-launch timing with HIP events on the caller's stream.  While enabled, every launch of
+ * the library's work-unit kernel is bracketed by an event pair.  lychee_timing_read waits for
+ * the recorded events, adds up the milliseconds and launches per launch class since the last
+ * read and clears the record.  Every launch runs the same kernel; its class says what it
+ * carried (arrays of LYCHEE_N_KERNEL_CLASSES entries). */
+#define LYCHEE_KERNEL_STREAM  0   /* retrieval streaming (alone or with gather work)       */
+#define LYCHEE_KERNEL_GATHER  1   /* sparse gather only                                     */
+#define LYCHEE_KERNEL_SELECT1 2   /* select phase 1 (alone or with combine)                 */
+#define LYCHEE_KERNEL_SELECT2 3   /* select phase 2 / set copies only                       */
+#define LYCHEE_KERNEL_COMBINE 4   /* combine (alone or with set copies)                     */
+#define LYCHEE_N_KERNEL_CLASSES 5
 int lychee_timing_enable(lychee_ctx *ctx, int on);
 int lychee_timing_read(lychee_ctx *ctx, float *ms_per_class, int32_t *launches_per_class);
 

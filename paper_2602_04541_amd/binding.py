@@ -18,8 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblychee.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
-KERNEL_ATTN, KERNEL_COMBINE, KERNEL_SELECT = 0, 1, 2
-OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG = 1, 2, 6, 7
+KERNEL_STREAM, KERNEL_GATHER, KERNEL_SELECT1, KERNEL_SELECT2, KERNEL_COMBINE = 0, 1, 2, 3, 4
+N_KERNEL_CLASSES = 5
+OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE = 1, 2, 6, 7, 8
 STEP_PHASED, STEP_LAYERWISE = 1, 0
 
 EXPORTS = [
@@ -202,8 +203,8 @@ class Context:
         _check(_lib.lychee_timing_enable(self._h, int(on)), "lychee_timing_enable")
 
     def timing_read(self):
-        ms = (ctypes.c_float * 3)()
-        n = (ctypes.c_int32 * 3)()
+        ms = (ctypes.c_float * N_KERNEL_CLASSES)()
+        n = (ctypes.c_int32 * N_KERNEL_CLASSES)()
         _check(_lib.lychee_timing_read(self._h, ms, n), "lychee_timing_read")
         return list(ms), list(n)
 

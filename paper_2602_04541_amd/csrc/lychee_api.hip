@@ -15,6 +15,7 @@ using namespace lychee;
 
 namespace {
 constexpr size_t kArenaBytes = 4u << 20;  // device memory for descriptor tables, per context
+constexpr size_t kArenaReserved = 256;    // its first bytes hold the ring of chunk counters
 }
 
 struct lychee_ctx {
@@ -24,6 +25,8 @@ struct lychee_ctx {
     int32_t n_wg = 0;          // 0 = n_cu * wg_per_cu
     int32_t step_mode = LYCHEE_STEP_PHASED;
     int32_t g_block_rows = 48;
+    int32_t tail_permille = 250;
+    uint32_t launch_seq = 0;   // pooled launches so far: picks the chunk counter
     bool timing = false;
     struct Rec {
         int cls;
@@ -46,7 +49,8 @@ struct lychee_ctx {
 
 namespace {
 
-constexpr int kWsWg = 768;  // largest grid a launch uses = partial slots per head in the workspace
+constexpr int kWsWg = 768;        // largest grid a launch uses
+constexpr int kPartSlots = 1024;  // partial slots per head in the workspace: static runs + chunks
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -79,8 +83,8 @@ Workspace carve(const lychee_shape &s, int n_layers)
     const size_t heads = (size_t)s.batch * s.n_q_heads;
     const size_t groups = (size_t)s.batch * s.n_kv_heads;
     w.sel = take(groups * w.sel_stride * sizeof(float));
-    w.part_o = take(heads * kWsWg * kHeadDim * sizeof(float));
-    w.part_ml = take(heads * kWsWg * 2 * sizeof(float));
+    w.part_o = take(heads * kPartSlots * kHeadDim * sizeof(float));
+    w.part_ml = take(heads * kPartSlots * 2 * sizeof(float));
     w.part_count = take(heads * sizeof(int32_t));
     w.list = take(groups * (size_t)w.list_row * sizeof(uint2));
     w.list_count = take(groups * kSlices * sizeof(int32_t));
@@ -187,7 +191,7 @@ uint64_t hash_bytes(const void *p, size_t n)
 const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &descs, hipStream_t stream)
 {
     const size_t bytes = descs.size() * sizeof(LayerDesc);
-    if (bytes > kArenaBytes) return nullptr;
+    if (bytes > kArenaBytes - kArenaReserved) return nullptr;
     const uint64_t h = hash_bytes(descs.data(), bytes);
     for (const auto &e : ctx->cache)
         if (e.hash == h && e.bytes == bytes && memcmp(ctx->arena_host + e.offset, descs.data(), bytes) == 0)
@@ -196,7 +200,7 @@ const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &d
         // Arena full: start over.  Tables still in use by enqueued launches, and staging
         // bytes of copies still in flight, must not be overwritten, so wait for the stream.
         if (hipStreamSynchronize(stream) != hipSuccess) return nullptr;
-        ctx->arena_used = 0;
+        ctx->arena_used = kArenaReserved;
         ctx->cache.clear();
     }
     const size_t off = ctx->arena_used;
@@ -276,8 +280,16 @@ struct Launcher {
         c.list_row = w.list_row;
         c.n_slices = n_slices;
         c.n_wg = grid();
-        c.part_stride = kWsWg;
+        c.part_stride = kPartSlots;
         c.g_block_rows = ctx->g_block_rows;
+        c.tickets = reinterpret_cast<uint32_t *>(ctx->arena_dev);
+        c.tail_permille = ctx->tail_permille;
+        // chunks small enough to level the finish times, large enough that a segment
+        // never has more than ~192 of them (partial slots per head are limited)
+        const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
+        c.chunk_blocks = (int32_t)((seg_blocks + 191) / 192);
+        if (c.chunk_blocks < 2) c.chunk_blocks = 2;
+        if (r.r_count || r.g_count) c.ticket_slot = (int32_t)(ctx->launch_seq++ % kTicketRing);
         c.scale = (float)(1.0 / sqrt((double)kHeadDim));
         c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
         p.layers = table;
@@ -286,8 +298,9 @@ struct Launcher {
         p.c_first = r.c_first, p.c_count = r.c_count;
         p.s1_first = r.s1_first, p.s1_count = r.s1_count;
         p.s2_first = r.s2_first, p.s2_count = r.s2_count;
-        const int cls = (r.r_count || r.g_count) ? LYCHEE_KERNEL_ATTN
-                        : (r.c_count || r.s1_count) ? LYCHEE_KERNEL_COMBINE : LYCHEE_KERNEL_SELECT;
+        const int cls = r.r_count ? LYCHEE_KERNEL_STREAM : r.g_count ? LYCHEE_KERNEL_GATHER
+                        : r.s1_count ? LYCHEE_KERNEL_SELECT1 : r.c_count ? LYCHEE_KERNEL_COMBINE
+                        : LYCHEE_KERNEL_SELECT2;
         if (!ctx->timing) return launch_units(p, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
         lychee_ctx::Rec rec{cls, take_event(ctx), take_event(ctx)};
         if (rec.start == nullptr || rec.stop == nullptr) return LYCHEE_EHIP;
@@ -335,6 +348,8 @@ int lychee_create(lychee_ctx **out, int device)
     bool ok = hipGetDevice(&cur) == hipSuccess && hipSetDevice(device) == hipSuccess;
     ok = ok && hipMalloc(reinterpret_cast<void **>(&ctx->arena_dev), kArenaBytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void **>(&ctx->arena_host), kArenaBytes, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMemset(ctx->arena_dev, 0, kArenaReserved) == hipSuccess;
+    ctx->arena_used = kArenaReserved;
     if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     if (!ok) {
         if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
@@ -591,6 +606,10 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
     case LYCHEE_OPT_N_WG:
         if (value < 0 || value > kWsWg) return LYCHEE_EINVAL;
         ctx->n_wg = value;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_TAIL_PERMILLE:
+        if (value < 0 || value > 1000) return LYCHEE_EINVAL;
+        ctx->tail_permille = value;
         return LYCHEE_OK;
     case LYCHEE_OPT_GATHER_BLOCK:
         if (value < 16 || value > 128 || value % 16) return LYCHEE_EINVAL;

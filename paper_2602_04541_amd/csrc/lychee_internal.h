@@ -26,7 +26,8 @@ constexpr int kSample = 4096;
 constexpr float kMinusBig = -1.0e30f;    // "no score yet" sentinel of the running maximum
 
 constexpr int kMaxLayers = 128;          // layers one launch can cover
-constexpr int kMaxItems = 2048;          // (layer, sequence) pairs of one launch's pooled rows
+constexpr int kMaxItems = 2048;
+constexpr int kTicketRing = 64;          // chunk counters; one is cleared 32 launches before its use          // (layer, sequence) pairs of one launch's pooled rows
 
 // What every part of a launch shares.
 struct Common {
@@ -38,6 +39,10 @@ struct Common {
     int32_t n_slices;     // slices one score row is filtered in (a power of two <= kSlices)
     int32_t n_wg;         // grid size of this launch
     int32_t part_stride;  // partial slots per head
+    uint32_t *tickets;    // ring of kTicketRing chunk counters, zero except the ones in use
+    int32_t ticket_slot;  // the counter of this launch; the launch also clears the opposite one
+    int32_t tail_permille;// share of the pooled blocks handed out dynamically, in chunks of
+    int32_t chunk_blocks; //   chunk_blocks blocks, to whichever workgroup asks next
     int32_t g_block_rows; // set entries per pooled block of gather work (fewer than kBlockRows:
                           // a gathered row costs more than a streamed one)
     float scale;          // 1 / sqrt(head_dim)

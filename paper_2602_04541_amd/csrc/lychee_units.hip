@@ -59,6 +59,7 @@ struct SharedPool {
     int32_t upre[4][kMaxLayers + 1];     // first small unit of every layer, per unit kind
     int32_t len[kMaxBatch];
     uint32_t scan[kWaves + 1];
+    unsigned long long scan64[kWaves + 1];
     float fred[kWaves + 1];
 };
 
@@ -134,6 +135,32 @@ __device__ __forceinline__ uint32_t block_scan(uint32_t v, uint32_t *wave_tot, u
     for (int w = 0; w < kWaves; ++w) {
         const uint32_t t = wave_tot[w];
         before += (w < wave) ? t : 0u;
+        all += t;
+    }
+    total = all;
+    return x + before;
+}
+
+// The same for four 16-bit counts packed in 64 bits (no field may overflow).
+__device__ __forceinline__ unsigned long long block_scan64(unsigned long long v, unsigned long long *wave_tot,
+                                                           unsigned long long &total)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    unsigned long long x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    unsigned long long before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const unsigned long long t = wave_tot[w];
+        before += (w < wave) ? t : 0ull;
         all += t;
     }
     total = all;
@@ -638,40 +665,52 @@ __device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p
         find_digit<1024>(sh.hist, rest1, sh.found, pool.scan, d2, rest2);
         t0 = (d1 << 20) | (d2 << 10);
     }
-    // ---- ordered filter of the slice
+    // ---- ordered filter of the slice: rounds of kThreads*4 scores, four rounds per batch;
+    // the next batch's loads are in flight while this one is scanned and written, and one
+    // scan of four packed 16-bit counts places all four rounds
     uint2 *dst = p.list + row * (int64_t)c.list_row + (int64_t)slice * slen;
     const int s1 = s0 + slen < L ? s0 + slen : L;
     uint32_t base = 0;
     const int n_it = (s1 - s0 + kThreads * 4 - 1) / (kThreads * 4);
-    for (int it0 = 0; it0 < n_it; it0 += 4) {
-        float4 x[4];
+    auto load_batch = [&](float4 (&x)[4], int it0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
             x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i0 < s1) x[u] = *reinterpret_cast<const float4 *>(sel + i0);  // rows are padded to 64
         }
+    };
+    float4 cur[4], nxt[4];
+    load_batch(cur, 0);
+    for (int it0 = 0; it0 < n_it; it0 += 4) {
+        load_batch(nxt, it0 + 4);  // past the end: nothing is loaded
+        uint32_t keys[4][4], pass[4];
+        unsigned long long packed = 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (it0 + u < n_it) {
-                const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
-                const float xs[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-                uint32_t keys[4];
-                uint32_t pass = 0;
+            const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
+            const float xs[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
+            pass[u] = 0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    keys[j] = ordered_key(xs[j]);
-                    pass |= (uint32_t)(i0 + j < s1 && keys[j] >= t0) << j;
-                }
-                const uint32_t cnt = (uint32_t)__builtin_popcount(pass);
-                uint32_t total;
-                uint32_t at = base + block_scan(cnt, pool.scan, total) - cnt;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if ((pass >> j) & 1u) dst[at++] = make_uint2(keys[j], (uint32_t)(i0 + j));
-                base += total;
+            for (int j = 0; j < 4; ++j) {
+                keys[u][j] = ordered_key(xs[j]);
+                pass[u] |= (uint32_t)(i0 + j < s1 && keys[u][j] >= t0) << j;
             }
+            packed |= (unsigned long long)__builtin_popcount(pass[u]) << (16 * u);
         }
+        unsigned long long total;
+        const unsigned long long excl = block_scan64(packed, pool.scan64, total) - packed;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
+            uint32_t at = base + (uint32_t)((excl >> (16 * u)) & 0xFFFFull);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((pass[u] >> j) & 1u) dst[at++] = make_uint2(keys[u][j], (uint32_t)(i0 + j));
+            base += (uint32_t)((total >> (16 * u)) & 0xFFFFull);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
     }
     if (threadIdx.x == 0) *count_out = (int32_t)base;
 }
@@ -993,51 +1032,85 @@ __global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan
     }
     __syncthreads();
     const int T = pool.ipre[n_items];
-    const int share = (T + W - 1) / W;  // every workgroup takes `share` consecutive blocks
-    int x = w * share;
-    int x1 = x + share;
-    x1 = x1 < T ? x1 : T;
+    // Most of the pooled blocks are dealt statically, an equal contiguous run per workgroup;
+    // the last tail_permille/1000 of them are cut into chunks that workgroups claim through
+    // a counter as they finish, which evens out CUs that stream at different speeds.  Runs
+    // and chunks in ascending block order are the launch's *work items*; the pieces of a
+    // segment sit in consecutive items, and a piece's partial slot is its item's distance to
+    // the first item of the segment, whoever ran it.
+    // (a launch too short to hold several chunks per workgroup is dealt statically: the
+    // chunks' start-up cost would outweigh what they level out)
+    const int tail = (int64_t)T >= 8ll * c.chunk_blocks * W ? c.tail_permille : 0;
+    const int share = (int)((int64_t)T * (1000 - tail) / (1000ll * W));
+    const int T_static = share * W;
+    const int n_static = share > 0 ? W : 0;
+    const int chunk = c.chunk_blocks;
+    const int n_chunks = (T - T_static + chunk - 1) / chunk;
+    auto item_of = [&](int blk) { return blk < T_static ? blk / share : n_static + (blk - T_static) / chunk; };
+    uint32_t *counter = c.tickets + c.ticket_slot;
+    uint32_t next_ticket = 0;
+    if (threadIdx.x == 0) {
+        next_ticket = atomicAdd(counter, 1u);  // asked for early, looked at after the static run
+        if (w == 0) c.tickets[(c.ticket_slot + kTicketRing / 2) % kTicketRing] = 0u;
+    }
     TRACE(2);
 
-    while (x < x1) {
-        const int it = find_item(pool.ipre, n_items, x);
-        const int li = it / c.batch;
-        const int b = it % c.batch;
-        const bool gather = li >= P.r_count;
-        const LayerDesc &L = gather ? layers[P.g_first + li - P.r_count] : layers[P.r_first + li];
-        const int len_b = pool.len[b];
-        const int seg_rows = gather ? (c.k < len_b ? c.k : len_b) : len_b;
-        const int brows = gather ? c.g_block_rows : kBlockRows;
-        const int nb = (seg_rows + brows - 1) / brows;  // blocks per segment of this item
-        const int xo = x - pool.ipre[it];
-        const int gi = xo / nb;
-        const int blk = xo % nb;
-        const int seg_start = pool.ipre[it] + gi * nb;
-        int len = x1 - x;
-        len = len < nb - blk ? len : nb - blk;
-        const int r0 = blk * brows;
-        int r1 = (blk + len) * brows;
-        r1 = r1 < seg_rows ? r1 : seg_rows;
-        const int slot = w - seg_start / share;  // pieces of a segment sit on consecutive workgroups
-        const bool ends = blk + len == nb;
-        const uint32_t gmask = (1u << c.group) - 1u;
-        if (!gather) {
-            const int g = L.rgroup[gi];
-            const uint32_t hmask = L.rmask[g] & gmask;
-            float *sel_row = L.emit_sel ? L.sel + ((int64_t)b * L.n_rgroups + gi) * c.sel_stride : nullptr;
-            dispatch_piece<false>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, nullptr, sel_row,
-                                  L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
-                                  su.attn);
-        } else {
-            const int g = L.sgroup[gi];
-            const uint32_t hmask = ~(uint32_t)L.rmask[g] & gmask;
-            const int32_t *idx_src = L.idx_src[g] + ((int64_t)b * c.n_kv_heads + g) * c.k;
-            dispatch_piece<true>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, idx_src, nullptr,
-                                 L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
-                                 su.attn);
+    int item = w;
+    int x = w * share;
+    int x1 = x + share;
+    for (;;) {
+        while (x < x1) {
+            const int it = find_item(pool.ipre, n_items, x);
+            const int li = it / c.batch;
+            const int b = it % c.batch;
+            const bool gather = li >= P.r_count;
+            const LayerDesc &L = gather ? layers[P.g_first + li - P.r_count] : layers[P.r_first + li];
+            const int len_b = pool.len[b];
+            const int seg_rows = gather ? (c.k < len_b ? c.k : len_b) : len_b;
+            const int brows = gather ? c.g_block_rows : kBlockRows;
+            const int nb = (seg_rows + brows - 1) / brows;  // blocks per segment of this item
+            const int xo = x - pool.ipre[it];
+            const int gi = xo / nb;
+            const int blk = xo % nb;
+            const int seg_start = pool.ipre[it] + gi * nb;
+            int len = x1 - x;
+            len = len < nb - blk ? len : nb - blk;
+            const int r0 = blk * brows;
+            int r1 = (blk + len) * brows;
+            r1 = r1 < seg_rows ? r1 : seg_rows;
+            const int slot = item - item_of(seg_start);
+            const bool ends = blk + len == nb;
+            const uint32_t gmask = (1u << c.group) - 1u;
+            if (!gather) {
+                const int g = L.rgroup[gi];
+                const uint32_t hmask = L.rmask[g] & gmask;
+                float *sel_row = L.emit_sel ? L.sel + ((int64_t)b * L.n_rgroups + gi) * c.sel_stride : nullptr;
+                dispatch_piece<false>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, nullptr, sel_row,
+                                      L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
+                                      su.attn);
+            } else {
+                const int g = L.sgroup[gi];
+                const uint32_t hmask = ~(uint32_t)L.rmask[g] & gmask;
+                const int32_t *idx_src = L.idx_src[g] + ((int64_t)b * c.n_kv_heads + g) * c.k;
+                dispatch_piece<true>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, idx_src, nullptr,
+                                     L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
+                                     su.attn);
+            }
+            x += len;
+            TRACE(3);
         }
-        x += len;
-        TRACE(3);
+        // next chunk: every workgroup asks until it is told that none is left
+        __syncthreads();
+        if (threadIdx.x == 0) pool.scan[0] = next_ticket;
+        __syncthreads();
+        const int ticket = (int)pool.scan[0];
+        __syncthreads();
+        if (ticket >= n_chunks) break;
+        if (threadIdx.x == 0) next_ticket = atomicAdd(counter, 1u);
+        item = n_static + ticket;
+        x = T_static + ticket * chunk;
+        x1 = x + chunk;
+        x1 = x1 < T ? x1 : T;
     }
     TRACE(4);
 }

@@ -185,12 +185,14 @@ def test_result_does_not_depend_on_the_grid_size_and_is_deterministic(ctx):
     dl = H.DeviceLayer(inp, w.k, idx_in)
     results = []
     try:
-        for wg_per_cu, n_wg, gb in [(2, 0, 48), (1, 0, 48), (3, 0, 16), (2, 37, 128), (2, 1, 64), (2, 0, 48)]:
+        for wg_per_cu, n_wg, gb, tail in [(2, 0, 48, 150), (1, 0, 48, 0), (3, 0, 16, 1000), (2, 37, 128, 500),
+                                          (2, 1, 64, 150), (2, 0, 48, 150)]:
             ctx.set_option(lb.OPT_WG_PER_CU, wg_per_cu)
             ctx.set_option(lb.OPT_N_WG, n_wg)
             ctx.set_option(lb.OPT_GATHER_BLOCK, gb)
+            ctx.set_option(lb.OPT_TAIL_PERMILLE, tail)
             out, idx = H.run_hybrid(ctx, dl, inp.mask)
-            what = "wg_per_cu=%d n_wg=%d gather_block=%d" % (wg_per_cu, n_wg, gb)
+            what = "wg_per_cu=%d n_wg=%d gather_block=%d tail=%d" % (wg_per_cu, n_wg, gb, tail)
             H.assert_outputs_close(out, out_ref, what)
             H.assert_sets_match(idx, idx_ref, sel_ref, inp.mask, inp, w.k, idx_in, what)
             results.append((out, idx))
@@ -198,6 +200,7 @@ def test_result_does_not_depend_on_the_grid_size_and_is_deterministic(ctx):
         ctx.set_option(lb.OPT_WG_PER_CU, 2)
         ctx.set_option(lb.OPT_N_WG, 0)
         ctx.set_option(lb.OPT_GATHER_BLOCK, 48)
+        ctx.set_option(lb.OPT_TAIL_PERMILLE, 150)
     for out, idx in results[1:]:
         assert (idx == results[0][1]).all()              # scores do not depend on the split
         assert np.abs(out - results[0][0]).max() <= 2 ** -6
