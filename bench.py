@@ -146,6 +146,12 @@ def main() -> int:
             ctx.probe_read(ks[l], probe_bytes, sink)
     probe_sec = timed(probe, 5, 1)
     read_ceiling = probe_bytes * n_probe / probe_sec / 1e9
+    # one plain copy of known size (reads and writes probe_bytes): the yardstick that the
+    # FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled by
+    copy_dst = torch.empty_like(ks[0])
+    ctx.probe_copy(copy_dst, ks[0], probe_bytes)
+    torch.cuda.synchronize()
+    del copy_dst
 
     # ---- algorithmic bytes ---------------------------------------------------------------
     # per step: every K+V row streamed or gathered (512 B), the fp32 selection score written
