@@ -335,3 +335,92 @@ def test_error_codes_and_index_validator(ctx):
     broken[0, 0, 3] = broken[0, 0, 2]      # a duplicate
     broken[0, 1, 0] = 512                  # out of range
     assert ctx.validate_idx(dl.shape, broken, dl.lengths) == 2
+
+
+# ------------------------------------------------------------------ configuration 3, full size
+@pytest.mark.parametrize("layer", [0, 1, 17, 35])
+def test_c3_full_size_single_layers(ctx, layer):
+    """Teacher-forced: a 128K Qwen3-8B-shaped layer with the oracle's sets as idx_in."""
+    w = wl.WORKLOADS["c3"]
+    inp = wl.make_layer(w, layer=layer, device="cuda")
+    idx_in = None if inp.mask.all() else H.previous_layer_sets(inp, w.k)
+    _say("c3 layer %d: retrieval heads %s" % (layer, np.flatnonzero(inp.mask).tolist()))
+    _, _, idx_gpu, _, _, _ = H.check_layer(ctx, inp, inp.mask, w.k, idx_in, "c3 layer %d" % layer)
+    G = w.group
+    for g in range(w.n_kv_heads):
+        if inp.mask[g * G:(g + 1) * G].any():       # k = 4096 holds all 1024 planted rows
+            assert np.isin(inp.planted_pos[0, g], idx_gpu[0, g]).all()
+
+
+def test_c3_full_decode_step_in_the_benchmarked_configuration(ctx):
+    """The whole 36-layer 128K step exactly as bench.py launches it (phased mode), every
+    layer's output and the final sets against the oracle chain."""
+    lb = H.binding()
+    w = wl.WORKLOADS["c3"]
+    n_layers = w.n_layers
+    layers = [wl.make_layer(w, layer=l, device="cuda") for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    lens_h = layers[0].lengths
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, w.k, kv=layers[0].k_cache)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
+    lens = torch.from_numpy(lens_h).cuda()
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                    [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
+    torch.cuda.synchronize()
+    got_final = idx_final.cpu().numpy()
+    # oracle chain, one layer on the host at a time; remember which scores produced each set
+    G = w.group
+    idx = None
+    last_sel = [None] * w.n_kv_heads
+    worst = 0.0
+    for l, ly in enumerate(layers):
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, w.k, idx)
+        worst = max(worst, H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), out_ref, "c3 step layer %d" % l))
+        for g in range(w.n_kv_heads):
+            if ly.mask[g * G:(g + 1) * G].any():
+                last_sel[g] = sel_ref[0, g, :w.max_len].copy()
+    _say("c3 step: worst abs output error %.4g" % worst)
+    for g in range(w.n_kv_heads):
+        ok, n_diff, msg = H.index_sets_match(got_final[0, g], idx[0, g], last_sel[g], w.k, H.TIE_REL)
+        assert ok, "final set of KV head %d: %s" % (g, msg)
+        assert (np.diff(got_final[0, g]) > 0).all()
+
+
+# ------------------------------------------------------------------ configuration 5: sweep
+@pytest.mark.parametrize("n_retrieval", [1, 4, 32])
+@pytest.mark.parametrize("k", [64, 1024, 8192, 131072])
+def test_c5_budget_and_retrieval_fraction_sweep_with_ties(ctx, k, n_retrieval):
+    w = wl.scaled(wl.WORKLOADS["c5"], k=k, n_retrieval=n_retrieval)
+    rng = np.random.default_rng(k + n_retrieval)
+    if n_retrieval == 32:
+        mask = np.ones(32, np.uint8)
+    elif n_retrieval == 4:
+        mask = wl.head_type_mask(w, 0)
+    else:
+        mask = np.zeros(32, np.uint8)
+        mask[int(rng.integers(0, 32))] = 1
+    inp = wl.make_layer(w, device="cuda", mask=mask)
+    # mass ties: 4096 key rows per KV head become copies of a few source rows (planted rows
+    # and rows spread over the score range), V untouched
+    src = np.stack([np.concatenate([inp.planted_pos[0, g, :8],
+                                    rng.choice(w.max_len, size=24, replace=False)])
+                    for g in range(w.n_kv_heads)])[None]
+    wl.plant_ties(inp, 4096, src)
+    if k >= w.max_len:
+        idx_in = np.tile(np.arange(w.max_len, dtype=np.int32), (1, w.n_kv_heads, 1))
+    else:
+        idx_in = H.previous_layer_sets(inp, k)
+    if n_retrieval == 32:
+        idx_in = None
+    _say("c5 k=%d retrieval heads %s" % (k, np.flatnonzero(mask).tolist()))
+    dl, out_gpu, idx_gpu, out_ref, idx_ref, _ = H.check_layer(ctx, inp, mask, k, idx_in, "c5 k=%d r=%d" % (k, n_retrieval))
+    if k >= w.max_len:
+        # the full set: sparse heads must equal the dense kernel's result for those heads
+        dense = H.run_dense(ctx, dl)
+        assert np.abs(dense - out_gpu).max() <= 2 ** -6
+        for g in range(w.n_kv_heads):
+            if mask[g * 4:(g + 1) * 4].any():
+                assert (idx_gpu[0, g] == np.arange(w.max_len)).all()
