@@ -100,8 +100,7 @@ def main() -> int:
         ctx.decode_step(shape, qs, ks, vs, masks, idx0, outs, idx_final, lens, ws)
 
     def dense_step():
-        for l in range(n_layers):
-            ctx.dense_decode_attn(shape, qs[l], ks[l], vs[l], outs[l], lens, ws)
+        ctx.dense_decode_step(shape, qs, ks, vs, outs, lens, ws)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -131,10 +130,11 @@ def main() -> int:
                          enumerate(["stream", "gather", "select1", "select2", "combine"])}
 
     # ---- the other step order, the dense kernel, the streaming-read ceiling ---------------
-    other_sec = dense_sec = None
+    other_sec = dense_sec = dense_other_sec = None
     if not args.quick:
         set_mode(not args.layerwise)
         other_sec = timed(hybrid_step, max(3, args.steps // 3), 1)
+        dense_other_sec = timed(dense_step, max(3, args.steps // 3), 1)
         set_mode(args.layerwise)
         dense_sec = timed(dense_step, max(3, args.steps // 3), 1)
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -212,10 +212,14 @@ def main() -> int:
         "gen_seconds": round(t_gen, 1),
     }
     if other_sec is not None:
-        result["layerwise_us" if not args.layerwise else "phased_us"] = round(other_sec * 1e6, 2)
+        # the dense kernel on identical buffers, in the same step order as `value` and in the other
+        other = "layerwise" if not args.layerwise else "phased"
+        result["%s_us" % other] = round(other_sec * 1e6, 2)
         result["dense_us"] = round(dense_sec * 1e6, 2)
+        result["dense_%s_us" % other] = round(dense_other_sec * 1e6, 2)
         result["dense_achieved_gbps"] = round(dense_bytes / dense_sec / 1e9, 1)
         result["speedup_vs_dense"] = round(dense_sec / sec, 3)
+        result["speedup_vs_dense_%s" % other] = round(dense_other_sec / other_sec, 3)
 
     # ---- the CPU oracle on a bounded sample of the same workload --------------------------
     if not args.no_cpu_baseline:

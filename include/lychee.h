@@ -145,6 +145,15 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
                        const int32_t *lengths, void *workspace, size_t workspace_bytes,
                        void *hip_stream);
 
+/* Dense attention for all layers of a step (Eq. 1 and o = A V for every head, no selection), in
+ * the order STEP_MODE names: PHASED = all layers' streaming pooled in one launch, then the
+ * combines; LAYERWISE = layer after layer as lychee_dense_decode_attn.  The in-run baseline of
+ * lychee_decode_step; arguments as there, workspace of lychee_step_workspace_bytes. */
+int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
+                             const void *const *q, const void *const *k_cache,
+                             const void *const *v_cache, void *const *out, const int32_t *lengths,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Debug helper (synchronous): counts entries of idx [B][H_kv][k] that break the index
  * conventions (out of [0, L_b), duplicated, or valid after a -1) into *n_bad (HOST). */
 int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,

@@ -27,6 +27,7 @@ EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
     "lychee_step_workspace_bytes",
     "lychee_decode_attn", "lychee_dense_decode_attn", "lychee_decode_step",
+    "lychee_dense_decode_step",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
 ]
@@ -64,6 +65,7 @@ def _load() -> ctypes.CDLL:
     lib.lychee_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_dense_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lychee_dense_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_validate_idx.argtypes = [vp, shp, vp, vp, ctypes.POINTER(i64), vp]
     lib.lychee_set_option.argtypes = [vp, i32, i32]
     lib.lychee_timing_enable.argtypes = [vp, ctypes.c_int]
@@ -188,6 +190,17 @@ class Context:
                                        _ptr(lengths), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(),
                                        _stream(stream)), "lychee_decode_step")
+
+    def dense_decode_step(self, shape: Shape, q: Sequence, k_cache: Sequence, v_cache: Sequence,
+                          out: Sequence, lengths, workspace, stream=None) -> None:
+        n = len(q)
+        arr = ctypes.c_void_p * n
+        _check(_lib.lychee_dense_decode_step(self._h, ctypes.byref(shape), n,
+                                             arr(*[_ptr(t) for t in q]), arr(*[_ptr(t) for t in k_cache]),
+                                             arr(*[_ptr(t) for t in v_cache]), arr(*[_ptr(t) for t in out]),
+                                             _ptr(lengths), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(),
+                                             _stream(stream)), "lychee_dense_decode_step")
 
     # -- helpers ------------------------------------------------------------------------
     def validate_idx(self, shape: Shape, idx, lengths, stream=None) -> int:

@@ -86,7 +86,7 @@ Workspace carve(const lychee_shape &s, int n_layers)
     w.part_o = take(heads * kPartSlots * kHeadDim * sizeof(float));
     w.part_ml = take(heads * kPartSlots * 2 * sizeof(float));
     w.part_count = take(heads * sizeof(int32_t));
-    w.list = take(groups * (size_t)w.list_row * sizeof(uint2));
+    w.list = take(groups * (size_t)w.list_row * sizeof(unsigned long long));
     w.list_count = take(groups * kSlices * sizeof(int32_t));
     w.idx_set = take(groups * s.k * sizeof(int32_t));
     w.layer_bytes = off;
@@ -169,7 +169,7 @@ void set_scratch(LayerDesc &d, const Workspace &w, char *ws, int layer_slot)
     d.part_o = reinterpret_cast<float *>(base + w.part_o);
     d.part_ml = reinterpret_cast<float *>(base + w.part_ml);
     d.part_count = reinterpret_cast<int32_t *>(base + w.part_count);
-    d.list = reinterpret_cast<uint2 *>(base + w.list);
+    d.list = reinterpret_cast<unsigned long long *>(base + w.list);
     d.list_count = reinterpret_cast<int32_t *>(base + w.list_count);
 }
 
@@ -512,6 +512,9 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
         d.idx_out = idx_set_of(w, ws, l);
         for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = cur[g];
         d.emit_sel = 1;
+#ifdef LYCHEE_TRACE
+        if (getenv("LYCHEE_TRACE_NOSEL")) d.emit_sel = 0;  // trace builds: cost of the score writes
+#endif
         d.copy_keep = 0;
         for (int i = 0; i < d.n_rgroups; ++i) cur[d.rgroup[i]] = d.idx_out;
     }
@@ -567,6 +570,54 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
         if ((rc = L.go(f)) != LYCHEE_OK) return rc;
     }
     return LYCHEE_OK;
+}
+
+int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
+                             const void *const *q, const void *const *k_cache,
+                             const void *const *v_cache, void *const *out, const int32_t *lengths,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (n_layers < 1 || n_layers >= kMaxLayers) return n_layers < 1 ? LYCHEE_EINVAL : LYCHEE_EUNSUPPORTED;
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, n_layers);
+    if (rc != LYCHEE_OK) return rc;
+    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr || lengths == nullptr)
+        return LYCHEE_EINVAL;
+    if (!aligned(lengths, 4)) return LYCHEE_EINVAL;
+    for (int l = 0; l < n_layers; ++l) {
+        if (q[l] == nullptr || k_cache[l] == nullptr || v_cache[l] == nullptr || out[l] == nullptr)
+            return LYCHEE_EINVAL;
+        if (!aligned(q[l], 16) || !aligned(k_cache[l], 16) || !aligned(v_cache[l], 16) ||
+            !aligned(out[l], 16))
+            return LYCHEE_EINVAL;
+    }
+    if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, n_layers);
+    std::vector<LayerDesc> descs((size_t)n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        LayerDesc &d = descs[l];
+        memset(&d, 0, sizeof d);
+        d.q = static_cast<const uint16_t *>(q[l]);
+        d.k_cache = static_cast<const uint16_t *>(k_cache[l]);
+        d.v_cache = static_cast<const uint16_t *>(v_cache[l]);
+        d.out = static_cast<uint16_t *>(out[l]);
+        set_groups(d, *shape, nullptr);
+        set_scratch(d, w, static_cast<char *>(workspace), l);
+    }
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    const Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+    if (ctx->step_mode != LYCHEE_STEP_PHASED || (int64_t)n_layers * shape->batch > kMaxItems) {
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = run_layer(L, l, false)) != LYCHEE_OK) return rc;
+        return LYCHEE_OK;
+    }
+    Ranges r;
+    r.r_first = 0, r.r_count = n_layers;
+    if ((rc = L.go(r)) != LYCHEE_OK) return rc;
+    Ranges c;
+    c.c_first = 0, c.c_count = n_layers;
+    return L.go(c);
 }
 
 int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,

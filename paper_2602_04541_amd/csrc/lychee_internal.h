@@ -58,7 +58,8 @@ struct LayerDesc {
     float *part_o;         // [B*H_q][part_stride][128] un-normalised partial outputs
     float *part_ml;        // [B*H_q][part_stride][2]   running maximum (raw dot units) and sum
     int32_t *part_count;   // [B*H_q] partial slots in use
-    uint2 *list;           // [B*n_rgroups][list_row] filtered (ordered key, position), slice by slice
+    unsigned long long *list;  // [B*n_rgroups][list_row] filtered scores, slice by slice: ordered key
+                               // in the low 32 bits, position in the high 32 bits
     int32_t *list_count;   // [B*n_rgroups][kSlices]
     int32_t *idx_out;      // [B][H_kv][k] where this layer's sets are written
     const int32_t *idx_src[kMaxKvHeads];  // per KV head: base of the [B][H_kv][k] array that

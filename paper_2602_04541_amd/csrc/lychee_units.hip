@@ -101,10 +101,38 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
     return (uint16_t)(u >> 16);
 }
 
+// Every buffer the units touch is device global memory, but most pointers reach the kernel
+// through the descriptor table, where the compiler can no longer see that.  Generic-address
+// ("flat") accesses make it wait for *all* outstanding loads before each use, which breaks the
+// load pipeline of the streaming loop; so every access goes through these casts.
+#define LYCHEE_GLOBAL __attribute__((address_space(1)))
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename T>
+__device__ __forceinline__ T gload(const T *p)
+{
+    return *(const LYCHEE_GLOBAL T *)p;
+}
+template <typename T>
+__device__ __forceinline__ void gstore(T *p, T v)
+{
+    *(LYCHEE_GLOBAL T *)p = v;
+}
+__device__ __forceinline__ float4 gload_f4(const float *p)
+{
+    const f32x4_t r = *(const LYCHEE_GLOBAL f32x4_t *)p;
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ uint4 gload_u4(const void *p)
+{
+    const u32x4_t r = *(const LYCHEE_GLOBAL u32x4_t *)p;
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
 // 16-byte streaming load: cache rows are read once per step and never again.
 __device__ __forceinline__ uint4 load_stream16(const uint16_t *p)
 {
-    const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    const u32x4_t r = __builtin_nontemporal_load((const LYCHEE_GLOBAL u32x4_t *)p);
     return make_uint4(r.x, r.y, r.z, r.w);
 }
 
@@ -285,12 +313,14 @@ __device__ __forceinline__ void consume_tile(const Tile &t, const uint4 (&qf)[NH
     }
 }
 
-#ifndef LYCHEE_RING_DEPTH
-#define LYCHEE_RING_DEPTH 2
-#endif
-
 // Streams rows [r0, r1) of one segment through the accumulators.  GATHER = false: cache rows
 // r0..r1-1; true: the cache rows named by set entries r0..r1-1, staged in idx_s[0 .. r1-r0).
+//
+// Rows are dealt in spans of 32 * kWaves: wavefront w owns rows 32w .. 32w+31 of every span,
+// as two tiles of 16 rows (4 rows per load instruction, K and V).  The two tile buffers
+// alternate: one tile's loads are in flight while the other is consumed.  After both tiles of
+// a span the wavefront writes its 32 selection scores as one full 128-byte line; writing
+// them in 16-byte fragments cost the streaming launch 14 % of its time.
 template <int NH, bool GATHER>
 __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kbase,
                                             const uint16_t *vbase, const uint4 (&qf)[NH],
@@ -301,18 +331,17 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
     const int wave = threadIdx.x >> 6;
     const int rs = lane >> 4;  // row slot: which of the 4 rows of a load this lane is in
     const int ch = lane & 15;  // 16-byte chunk of the 256-byte row
-    // A tile is kBlockRows consecutive rows shared by the wavefronts: load j of wavefront w
-    // covers rows 4*(kWaves*j + w) .. +3 of the tile, so that the workgroup's load j reads
-    // kWaves KiB of contiguous memory.
-    const int n_mine = (r1 - r0 + kBlockRows - 1) / kBlockRows;
+    constexpr int kSpan = 32 * kWaves;
+    const int n_spans = (r1 - r0 + kSpan - 1) / kSpan;
     const float c_log2e = c.scale_log2e;
 
-    auto issue = [&](Tile &t, int tile) {
-        const int base = r0 + tile * kBlockRows + 4 * wave;
+    // tile `half` (0 or 1) of span `span`: rows base .. base+15 of this wavefront
+    auto issue = [&](Tile &t, int span, int half) {
+        const int base = r0 + span * kSpan + 32 * wave + 16 * half;
         t.valid = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int r = base + 4 * kWaves * j + rs;
+            const int r = base + 4 * j + rs;
             int row;
             bool ok;
             if (GATHER) {
@@ -329,8 +358,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             t.v[j] = load_stream16(vbase + off);
         }
     };
-    auto consume = [&](const Tile &t, int tile) {
-        float sel_sum[4];
+    auto consume = [&](const Tile &t, float (&sel_sum)[4]) {
 #ifdef LYCHEE_PROBE_NOCOMPUTE
         {   // probe build only: touch the loaded data and nothing else
             uint32_t x = 0;
@@ -342,34 +370,41 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
 #else
         consume_tile<NH>(t, qf, acc, c_log2e, sel_sum);
 #endif
-        if (!GATHER && sel_row != nullptr) {
-            // lane ch (< 4) of each row slot stores the score of this lane's row of load ch
-            float mine = sel_sum[0];
-            mine = (ch == 1) ? sel_sum[1] : mine;
-            mine = (ch == 2) ? sel_sum[2] : mine;
-            mine = (ch == 3) ? sel_sum[3] : mine;
-            const int r = r0 + tile * kBlockRows + 4 * wave + 4 * kWaves * ch + rs;
-            if (ch < 4 && r < r1) sel_row[r] = mine * sel_mul + 0.0f;  // +0 turns -0 into +0
-        }
     };
 
     // Loads are issued unconditionally (a tile past the end re-reads the segment's last row
-    // and is marked invalid): a conditional refill would make the ring registers loop-carried
+    // and is marked invalid): a conditional refill would make the tile registers loop-carried
     // through a copy that has to wait for its load.
-    constexpr int kDepth = LYCHEE_RING_DEPTH;
-    Tile ring[kDepth];
-    if (n_mine == 0) return;
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) issue(ring[d], d);
+    Tile t0, t1;
+    if (n_spans == 0) return;
+    issue(t0, 0, 0);
+    issue(t1, 0, 1);
     TRACE(5);
-    for (int i = 0; i < n_mine; i += kDepth) {
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            if (i + d < n_mine) consume(ring[d], i + d);
-            if (i == 0 && d == 0) TRACE(6);
-            __builtin_amdgcn_sched_barrier(0);
-            issue(ring[d], i + d + kDepth);
-            __builtin_amdgcn_sched_barrier(0);
+    for (int span = 0; span < n_spans; ++span) {
+        float sel0[4], sel1[4];
+        consume(t0, sel0);
+        if (span == 0) TRACE(6);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(t0, span + 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(t1, sel1);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(t1, span + 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!GATHER && sel_row != nullptr) {
+            // lane ch (< 8) of each row slot stores the score of row 16*(ch/4) + 4*(ch%4) + rs:
+            // 32 lanes, 32 consecutive floats
+            const int j = ch & 3;
+            float lo = sel0[0], hi = sel1[0];
+            lo = (j == 1) ? sel0[1] : lo;
+            hi = (j == 1) ? sel1[1] : hi;
+            lo = (j == 2) ? sel0[2] : lo;
+            hi = (j == 2) ? sel1[2] : hi;
+            lo = (j == 3) ? sel0[3] : lo;
+            hi = (j == 3) ? sel1[3] : hi;
+            const float mine = (ch & 4) ? hi : lo;
+            const int r = r0 + span * kSpan + 32 * wave + 16 * ((ch >> 2) & 1) + 4 * j + rs;
+            if (ch < 8 && r < r1) gstore(sel_row + r, mine * sel_mul + 0.0f);  // +0 turns -0 into +0
         }
     }
 }
@@ -403,7 +438,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     uint4 qf[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h)
-        qf[h] = reinterpret_cast<const uint4 *>(q + ((int64_t)b * c.n_q_heads + heads[h]) * kHeadDim)[ch];
+        qf[h] = gload_u4(q + ((int64_t)b * c.n_q_heads + heads[h]) * kHeadDim + ch * 8);
 
     Acc<NH> acc;
 #pragma unroll
@@ -421,7 +456,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         for (int e0 = r0; e0 < r1; e0 += kIdxChunk) {
             const int e1 = e0 + kIdxChunk < r1 ? e0 + kIdxChunk : r1;
             __syncthreads();  // the previous chunk's readers are done
-            for (int i = threadIdx.x; i < e1 - e0; i += kThreads) sh.idx_s[i] = idx_src[e0 + i];
+            for (int i = threadIdx.x; i < e1 - e0; i += kThreads) sh.idx_s[i] = gload(idx_src + e0 + i);
             __syncthreads();
             stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, nullptr, 0.0f);
         }
@@ -480,11 +515,11 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             }
             const int64_t bh = (int64_t)b * c.n_q_heads + heads[h];
             const int64_t prow = bh * c.part_stride + slot;
-            part_o[prow * kHeadDim + threadIdx.x] = o;
+            gstore(part_o + prow * kHeadDim + threadIdx.x, o);
             if (threadIdx.x == 0) {
-                part_ml[prow * 2 + 0] = M;
-                part_ml[prow * 2 + 1] = l;
-                if (ends_segment) part_count[bh] = slot + 1;
+                gstore(part_ml + prow * 2 + 0, M);
+                gstore(part_ml + prow * 2 + 1, l);
+                if (ends_segment) gstore(part_count + bh, (int32_t)(slot + 1));
             }
         }
     }
@@ -512,18 +547,18 @@ __device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const ui
 __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p, int bh, SharedCombine &sh,
                                              SharedPool &pool)
 {
-    int count = p.part_count[bh];
+    int count = gload(p.part_count + bh);
     count = count < 0 ? 0 : (count > c.part_stride ? c.part_stride : count);
     const float *ml = p.part_ml + (int64_t)bh * c.part_stride * 2;
     const float *po = p.part_o + (int64_t)bh * c.part_stride * kHeadDim;
     float m_loc = kMinusBig;
     for (int s = threadIdx.x; s < count; s += kThreads)
-        if (ml[2 * s + 1] > 0.0f) m_loc = fmaxf(m_loc, ml[2 * s]);
+        if (gload(ml + 2 * s + 1) > 0.0f) m_loc = fmaxf(m_loc, gload(ml + 2 * s));
     const float M = block_max(m_loc, pool.fred);
     float l_loc = 0.0f;
     for (int s = threadIdx.x; s < count; s += kThreads) {
-        const float ls = ml[2 * s + 1];
-        const float w = ls > 0.0f ? fast_exp2((ml[2 * s] - M) * c.scale_log2e) : 0.0f;
+        const float ls = gload(ml + 2 * s + 1);
+        const float w = ls > 0.0f ? fast_exp2((gload(ml + 2 * s) - M) * c.scale_log2e) : 0.0f;
         sh.w[s] = w;
         l_loc = fmaf(w, ls, l_loc);
     }
@@ -541,7 +576,7 @@ __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p
             const int s = s0 + kLanes * u;
             wv[u] = s < count ? sh.w[s] : 0.0f;
             v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (wv[u] > 0.0f) v[u] = reinterpret_cast<const float4 *>(po + (int64_t)s * kHeadDim)[c4];
+            if (wv[u] > 0.0f) v[u] = gload_f4(po + (int64_t)s * kHeadDim + c4 * 4);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -558,7 +593,7 @@ __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p
 #pragma unroll
         for (int i = 0; i < kLanes; ++i) o += sh.red[i * kHeadDim + threadIdx.x];
         const float r = lsum > 0.0f ? o / lsum : 0.0f;
-        p.out[(int64_t)bh * kHeadDim + threadIdx.x] = f32_to_bf16_rne(r);
+        gstore(p.out + (int64_t)bh * kHeadDim + threadIdx.x, f32_to_bf16_rne(r));
     }
     __syncthreads();
 }
@@ -619,7 +654,7 @@ __device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p
     const int slen = slice_len_of(L, c.n_slices);
     const int s0 = slice * slen;
     if (n == L || s0 >= L) {  // everything is selected, or the slice is empty
-        if (threadIdx.x == 0) *count_out = 0;
+        if (threadIdx.x == 0) gstore(count_out, (int32_t)0);
         return;
     }
     const float *sel = p.sel + row * c.sel_stride;
@@ -634,7 +669,7 @@ __device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p
             const int i = threadIdx.x + u * kThreads;
             int pos = i;
             if (L > kSample) pos = (int)(((int64_t)(i >> 6) * L / kSampleBlocks) & ~3ll) + (i & 63);
-            sv[u] = i < n_sample ? sel[pos] : 0.0f;
+            sv[u] = i < n_sample ? gload(sel + pos) : 0.0f;
         }
 #pragma unroll
         for (int u = 0; u < kSample / kThreads; ++u)
@@ -668,7 +703,7 @@ __device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p
     // ---- ordered filter of the slice: rounds of kThreads*4 scores, four rounds per batch;
     // the next batch's loads are in flight while this one is scanned and written, and one
     // scan of four packed 16-bit counts places all four rounds
-    uint2 *dst = p.list + row * (int64_t)c.list_row + (int64_t)slice * slen;
+    unsigned long long *dst = p.list + row * (int64_t)c.list_row + (int64_t)slice * slen;
     const int s1 = s0 + slen < L ? s0 + slen : L;
     uint32_t base = 0;
     const int n_it = (s1 - s0 + kThreads * 4 - 1) / (kThreads * 4);
@@ -677,7 +712,7 @@ __device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p
         for (int u = 0; u < 4; ++u) {
             const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
             x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i0 < s1) x[u] = *reinterpret_cast<const float4 *>(sel + i0);  // rows are padded to 64
+            if (i0 < s1) x[u] = gload_f4(sel + i0);  // rows are padded to 64
         }
     };
     float4 cur[4], nxt[4];
@@ -706,13 +741,14 @@ __device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p
             uint32_t at = base + (uint32_t)((excl >> (16 * u)) & 0xFFFFull);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if ((pass[u] >> j) & 1u) dst[at++] = make_uint2(keys[u][j], (uint32_t)(i0 + j));
+                if ((pass[u] >> j) & 1u)
+                    gstore(dst + at++, (unsigned long long)keys[u][j] | ((unsigned long long)(uint32_t)(i0 + j) << 32));
             base += (uint32_t)((total >> (16 * u)) & 0xFFFFull);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
     }
-    if (threadIdx.x == 0) *count_out = (int32_t)base;
+    if (threadIdx.x == 0) gstore(count_out, (int32_t)base);
 }
 
 constexpr int kS2Regs = 40;  // candidates one thread keeps in registers in the fast path
@@ -778,10 +814,10 @@ __device__ __forceinline__ void select2_slow(const Common &c, int n, int total, 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if ((gt >> j) & 1u) {
-                dst[n_gt + (n_eq < r_eq ? n_eq : r_eq)] = (int32_t)poss[j];
+                gstore(dst + n_gt + (n_eq < r_eq ? n_eq : r_eq), (int32_t)poss[j]);
                 ++n_gt;
             } else if ((eq >> j) & 1u) {
-                if (n_eq < r_eq) dst[n_gt + n_eq] = (int32_t)poss[j];
+                if (n_eq < r_eq) gstore(dst + n_gt + n_eq, (int32_t)poss[j]);
                 ++n_eq;
             }
         }
@@ -800,24 +836,24 @@ __device__ __forceinline__ void select2_unit(const Common &c, const LayerDesc &p
     const int rgi = p.rindex[g];
     if (rgi == 0xFF) {  // no retrieval head in the group: the set is handed on unchanged
         const int32_t *src = p.idx_src[g] + bg * c.k;
-        for (int i = threadIdx.x; i < c.k; i += kThreads) dst[i] = src[i];
+        for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, gload(src + i));
         return;
     }
     const int L = clamp_len(c.lengths[b], c.max_len);
     const int n = c.k < L ? c.k : L;
     if (n == L) {  // everything is selected
-        for (int i = threadIdx.x; i < c.k; i += kThreads) dst[i] = i < L ? i : -1;
+        for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
         return;
     }
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     const float *sel = p.sel + row * c.sel_stride;
-    const uint2 *list = p.list + row * (int64_t)c.list_row;
+    const unsigned long long *list = p.list + row * (int64_t)c.list_row;
     const int slen = slice_len_of(L, c.n_slices);
     __syncthreads();
     if (threadIdx.x < 64) {  // one slice count per lane, prefix sum inside the wavefront
         int cnt = 0;
         if (threadIdx.x < c.n_slices) {
-            cnt = p.list_count[row * kSlices + threadIdx.x];
+            cnt = gload(p.list_count + row * kSlices + threadIdx.x);
             cnt = cnt < 0 ? 0 : (cnt > slen ? slen : cnt);
         }
         int incl = cnt;
@@ -837,16 +873,16 @@ __device__ __forceinline__ void select2_unit(const Common &c, const LayerDesc &p
     // element i of the candidate sequence (ascending by position in both cases)
     auto fetch = [&](int i, uint32_t &key, uint32_t &pos) {
         if (raw) {
-            key = ordered_key(sel[i]);
+            key = ordered_key(gload(sel + i));
             pos = (uint32_t)i;
         } else {
             int lo = 0;
 #pragma unroll
             for (int step = kSlices / 2; step >= 1; step >>= 1)
                 if (sh.slice_pre[lo + step] <= i) lo += step;
-            const uint2 e = list[(int64_t)lo * slen + (i - sh.slice_pre[lo])];
-            key = e.x;
-            pos = e.y;
+            const unsigned long long e = gload(list + (int64_t)lo * slen + (i - sh.slice_pre[lo]));
+            key = (uint32_t)e;
+            pos = (uint32_t)(e >> 32);
         }
     };
 
@@ -903,17 +939,17 @@ __device__ __forceinline__ void select2_unit(const Common &c, const LayerDesc &p
         for (int e = 0; e < kS2Regs; ++e) {
             if (poss[e] == 0xFFFFFFFFu) continue;
             if (keys[e] > T) {
-                dst[n_gt + (n_eq < r_eq ? n_eq : r_eq)] = (int32_t)poss[e];
+                gstore(dst + n_gt + (n_eq < r_eq ? n_eq : r_eq), (int32_t)poss[e]);
                 ++n_gt;
             } else if (keys[e] == T) {
-                if (n_eq < r_eq) dst[n_gt + n_eq] = (int32_t)poss[e];
+                if (n_eq < r_eq) gstore(dst + n_gt + n_eq, (int32_t)poss[e]);
                 ++n_eq;
             }
         }
     } else {
         select2_slow(c, n, total, fetch, dst, sh, pool);
     }
-    for (int i = n + threadIdx.x; i < c.k; i += kThreads) dst[i] = -1;
+    for (int i = n + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
 }
 
 // ------------------------------------------------------------------------------ the kernel

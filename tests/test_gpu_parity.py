@@ -424,3 +424,27 @@ def test_c5_budget_and_retrieval_fraction_sweep_with_ties(ctx, k, n_retrieval):
         for g in range(w.n_kv_heads):
             if mask[g * 4:(g + 1) * 4].any():
                 assert (idx_gpu[0, g] == np.arange(w.max_len)).all()
+
+
+@pytest.mark.parametrize("mode", ["phased", "layerwise"])
+def test_dense_decode_step(ctx, mode):
+    lb = H.binding()
+    n_layers = 3
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=2, max_len=2500, k=16, n_layers=n_layers, planted=16,
+                  len_lo=900, len_hi=2500)
+    lens_h = wl.lengths(w)
+    layers = [wl.make_layer(w, layer=l, device="cuda", lens=lens_h, l_cap=2500) for l in range(n_layers)]
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 2500, w.k, kv=layers[0].k_cache)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED if mode == "phased" else lb.STEP_LAYERWISE)
+    try:
+        ctx.dense_decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                              [ly.v_cache for ly in layers], outs, torch.from_numpy(lens_h).cuda(), ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+    for l, ly in enumerate(layers):
+        ref = lo.dense_attn(wl.bf16_bits(ly.q), wl.bf16_bits(ly.k_cache), wl.bf16_bits(ly.v_cache), lens_h)
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), ref, "dense step layer %d" % l)
