@@ -127,7 +127,7 @@ def main() -> int:
     ctx.timing_enable(False)
     stream_us = 1e3 * ms_cls[lb.KERNEL_STREAM] / max(1, n_cls[lb.KERNEL_STREAM])
     launches_per_step = {name: n_cls[i] // args.steps for i, name in
-                         enumerate(["stream", "gather", "select1", "select2", "combine"])}
+                         enumerate(["stream", "gather", "threshold", "select", "combine"])}
 
     # ---- the other step order, the dense kernel, the streaming-read ceiling ---------------
     other_sec = dense_sec = dense_other_sec = None
@@ -200,7 +200,7 @@ def main() -> int:
         "read_ceiling_gbps": round(read_ceiling, 1),
         "launches_per_step": launches_per_step,
         "launch_us_per_step": {name: round(1e3 * ms_cls[i] / args.steps, 2) for i, name in
-                               enumerate(["stream", "gather", "select1", "select2", "combine"])},
+                               enumerate(["stream", "gather", "threshold", "select", "combine"])},
         "paper_context": "paper reports up to 2.7x end-to-end TPOT speed-up over full attention at "
                          "128K, batch 1, budget 4096 (Sec. 4.3.1; GPU of that run not stated, kernel "
                          "study on one NVIDIA A800)",

@@ -80,7 +80,7 @@ int lychee_destroy(lychee_ctx *ctx);
  * lychee_check_shape: validates `shape`; if `head_type_mask` (HOST, [H_q]) is given it also
  *   checks that sparse heads come with an inherited set (`has_idx_in` != 0).
  * lychee_workspace_bytes: bytes of scratch any call below needs for `shape` (selection
- *   scores, split partials, select lists); 0 if the shape is invalid.  lychee_decode_step
+ *   candidates and scores, split partials); 0 if the shape is invalid.  lychee_decode_step
  *   needs lychee_step_workspace_bytes (the same per layer).
  *   The workspace must be 256-byte aligned; its contents are don't-care on entry. */
 int    lychee_check_shape(const lychee_shape *shape, const uint8_t *head_type_mask, int has_idx_in);
@@ -129,9 +129,9 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
  *   workspace                  at least lychee_step_workspace_bytes(shape, n_layers) bytes
  * Because every layer's query is an input of the call, only the sparse heads of layer l+1
  * depend on layer l (through its sets).  STEP_MODE chooses how that is used:
- *   LYCHEE_STEP_PHASED (default)  five launches for the whole step: the retrieval streaming
- *     of all layers pooled in one launch, then select phase 1, select phase 2, the sparse
- *     gathers of all layers, and the combines.  out[l] of every layer is complete only
+ *   LYCHEE_STEP_PHASED (default)  five launches for the whole step: the selection
+ *     thresholds of all layers, the retrieval streaming of all layers pooled in one launch,
+ *     the selects, the sparse gathers of all layers, and the combines.  out[l] of every layer is complete only
  *     when the call's work has finished.
  *   LYCHEE_STEP_LAYERWISE  layer after layer, each as lychee_decode_attn (three dependent
  *     launches); out[l] is complete before layer l+1 starts, as a model that computes
@@ -168,12 +168,19 @@ int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_
  *                 dynamically, in small chunks, after their fixed share (0..1000, default 250; launches too short to hold several chunks per workgroup use none);
  *                 it levels out compute units that stream at different speeds
  *   GATHER_BLOCK  set entries whose gather is balanced against 64 streamed rows (a multiple
- *                 of 16 in [16, 128], default 48: a gathered row costs more than a streamed one) */
+ *                 of 16 in [16, 128], default 48: a gathered row costs more than a streamed one)
+ *   SELECT_MARGIN tenths of a standard deviation by which the sampled selection threshold is
+ *                 lowered below its estimate of the k-th score (-10000..100000, default 60).
+ *                 A larger margin makes more rows candidates of the exact select; a margin so
+ *                 small that fewer than k rows pass, or so large that the candidate list
+ *                 overflows, costs time (the row is then ranked from all of its scores) but
+ *                 never changes a result */
 #define LYCHEE_OPT_WG_PER_CU    1
 #define LYCHEE_OPT_STEP_MODE    2
 #define LYCHEE_OPT_GATHER_BLOCK 6
 #define LYCHEE_OPT_N_WG         7
 #define LYCHEE_OPT_TAIL_PERMILLE 8
+#define LYCHEE_OPT_SELECT_MARGIN 9
 #define LYCHEE_STEP_PHASED      1
 #define LYCHEE_STEP_LAYERWISE   0
 int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
@@ -185,9 +192,9 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
  * carried (arrays of LYCHEE_N_KERNEL_CLASSES entries). */
 #define LYCHEE_KERNEL_STREAM  0   /* retrieval streaming (alone or with gather work)       */
 #define LYCHEE_KERNEL_GATHER  1   /* sparse gather only                                     */
-#define LYCHEE_KERNEL_SELECT1 2   /* select phase 1 (alone or with combine)                 */
-#define LYCHEE_KERNEL_SELECT2 3   /* select phase 2 / set copies only                       */
-#define LYCHEE_KERNEL_COMBINE 4   /* combine (alone or with set copies)                     */
+#define LYCHEE_KERNEL_THRESHOLD 2 /* selection thresholds                                   */
+#define LYCHEE_KERNEL_SELECT  3   /* select / set copies only                               */
+#define LYCHEE_KERNEL_COMBINE 4   /* combine (alone, with select or with set copies)        */
 #define LYCHEE_N_KERNEL_CLASSES 5
 int lychee_timing_enable(lychee_ctx *ctx, int on);
 int lychee_timing_read(lychee_ctx *ctx, float *ms_per_class, int32_t *launches_per_class);

@@ -18,9 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblychee.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
-KERNEL_STREAM, KERNEL_GATHER, KERNEL_SELECT1, KERNEL_SELECT2, KERNEL_COMBINE = 0, 1, 2, 3, 4
+KERNEL_STREAM, KERNEL_GATHER, KERNEL_THRESHOLD, KERNEL_SELECT, KERNEL_COMBINE = 0, 1, 2, 3, 4
 N_KERNEL_CLASSES = 5
-OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE = 1, 2, 6, 7, 8
+OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE, OPT_SELECT_MARGIN = 1, 2, 6, 7, 8, 9
 STEP_PHASED, STEP_LAYERWISE = 1, 0
 
 EXPORTS = [

@@ -26,6 +26,7 @@ struct lychee_ctx {
     int32_t step_mode = LYCHEE_STEP_PHASED;
     int32_t g_block_rows = 48;
     int32_t tail_permille = 250;
+    int32_t select_margin = 60;  // tenths of a standard deviation, see LYCHEE_OPT_SELECT_MARGIN
     uint32_t launch_seq = 0;   // pooled launches so far: picks the chunk counter
     bool timing = false;
     struct Rec {
@@ -55,16 +56,22 @@ constexpr int kPartSlots = 1024;  // partial slots per head in the workspace: st
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-// Entries of one score row's filtered list: every slice can keep all of its scores, and
-// slices are rounded up to the filter's quantum.
-int32_t list_row_entries(int32_t max_len)
+// Capacity of one score row's candidate list.  A threshold unit aims at n = min(k, L)
+// candidates plus six standard deviations of its sample (a few thousand at the usual sizes),
+// and makes every row a candidate when L <= kDirectLen or L <= 2k.  A list that still
+// overflows is not an error: the select unit then ranks the whole row itself.
+int32_t list_row_entries(int32_t max_len, int32_t k)
 {
-    return (int32_t)(round_up(max_len, kSliceQuantum) + (int64_t)kSlices * kSliceQuantum);
+    int64_t cap = 4ll * k;
+    if (cap < (int64_t)k + 16384) cap = (int64_t)k + 16384;
+    if (cap < max_len / 64) cap = max_len / 64;
+    const int64_t all = round_up(max_len, 64);
+    return (int32_t)(cap < all ? cap : all);
 }
 
 // Per-layer scratch, laid out layer after layer.
 struct Workspace {
-    size_t sel, part_o, part_ml, part_count, list, list_count, idx_set;  // offsets inside a layer
+    size_t sel, part_o, part_ml, part_count, list, list_count, thr, idx_set;  // offsets inside a layer
     size_t layer_bytes, total;
     int32_t sel_stride, list_row;
 };
@@ -73,7 +80,7 @@ Workspace carve(const lychee_shape &s, int n_layers)
 {
     Workspace w;
     w.sel_stride = (int32_t)round_up(s.max_len, 64);
-    w.list_row = list_row_entries(s.max_len);
+    w.list_row = list_row_entries(s.max_len, s.k);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -87,7 +94,8 @@ Workspace carve(const lychee_shape &s, int n_layers)
     w.part_ml = take(heads * kPartSlots * 2 * sizeof(float));
     w.part_count = take(heads * sizeof(int32_t));
     w.list = take(groups * (size_t)w.list_row * sizeof(unsigned long long));
-    w.list_count = take(groups * kSlices * sizeof(int32_t));
+    w.list_count = take(groups * sizeof(int32_t));
+    w.thr = take(groups * sizeof(uint32_t));
     w.idx_set = take(groups * s.k * sizeof(int32_t));
     w.layer_bytes = off;
     w.total = off * (size_t)n_layers;
@@ -171,6 +179,7 @@ void set_scratch(LayerDesc &d, const Workspace &w, char *ws, int layer_slot)
     d.part_count = reinterpret_cast<int32_t *>(base + w.part_count);
     d.list = reinterpret_cast<unsigned long long *>(base + w.list);
     d.list_count = reinterpret_cast<int32_t *>(base + w.list_count);
+    d.thr = reinterpret_cast<uint32_t *>(base + w.thr);
 }
 
 int32_t *idx_set_of(const Workspace &w, char *ws, int layer_slot)
@@ -214,7 +223,7 @@ const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &d
 
 struct Ranges {
     int r_first = 0, r_count = 0, g_first = 0, g_count = 0, c_first = 0, c_count = 0;
-    int s1_first = 0, s1_count = 0, s2_first = 0, s2_count = 0;
+    int t_first = 0, t_count = 0, s_first = 0, s_count = 0;
 };
 
 hipEvent_t take_event(lychee_ctx *ctx)
@@ -236,29 +245,21 @@ struct Launcher {
     const int32_t *lengths;
     const LayerDesc *table;
     hipStream_t stream;
-    int n_slices;  // slices per score row, the same in the S1 and S2 launches of a call
 
     int grid() const
     {
         const int n_wg = ctx->n_wg > 0 ? ctx->n_wg : ctx->n_cu * ctx->wg_per_cu;
         return n_wg > kWsWg ? kWsWg : n_wg;
     }
-    // Enough slices to give every workgroup a filter unit, for `rows` score rows.
-    void choose_slices(int64_t rows)
-    {
-        n_slices = 1;
-        while (n_slices < kSlices && rows * n_slices * 2 <= grid()) n_slices *= 2;
-    }
-
     int go(const Ranges &r) const
     {
-        if (r.r_count + r.g_count + r.c_count + r.s1_count + r.s2_count == 0) return LYCHEE_OK;
+        if (r.r_count + r.g_count + r.c_count + r.t_count + r.s_count == 0) return LYCHEE_OK;
 #ifdef LYCHEE_TRACE
         {   // trace builds: LYCHEE_TRACE_STOP=n drops every launch after the n-th of a call
             static int budget = -1, left = 0;
             if (budget < 0) budget = getenv("LYCHEE_TRACE_STOP") ? atoi(getenv("LYCHEE_TRACE_STOP")) : 0;
             if (budget > 0) {
-                if (r.r_count > 1 || (r.r_count == 1 && r.r_first == 0)) left = budget;
+                if (r.t_count > 0 && r.t_first == 0) left = budget;  // a call starts with its thresholds
                 if (left-- <= 0) return LYCHEE_OK;
             }
         }
@@ -278,7 +279,6 @@ struct Launcher {
         c.max_len = s.max_len;
         c.sel_stride = w.sel_stride;
         c.list_row = w.list_row;
-        c.n_slices = n_slices;
         c.n_wg = grid();
         c.part_stride = kPartSlots;
         c.g_block_rows = ctx->g_block_rows;
@@ -290,17 +290,18 @@ struct Launcher {
         c.chunk_blocks = (int32_t)((seg_blocks + 191) / 192);
         if (c.chunk_blocks < 2) c.chunk_blocks = 2;
         if (r.r_count || r.g_count) c.ticket_slot = (int32_t)(ctx->launch_seq++ % kTicketRing);
+        c.sel_margin = 0.1f * (float)ctx->select_margin;
         c.scale = (float)(1.0 / sqrt((double)kHeadDim));
         c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
         p.layers = table;
         p.r_first = r.r_first, p.r_count = r.r_count;
         p.g_first = r.g_first, p.g_count = r.g_count;
         p.c_first = r.c_first, p.c_count = r.c_count;
-        p.s1_first = r.s1_first, p.s1_count = r.s1_count;
-        p.s2_first = r.s2_first, p.s2_count = r.s2_count;
+        p.t_first = r.t_first, p.t_count = r.t_count;
+        p.s_first = r.s_first, p.s_count = r.s_count;
         const int cls = r.r_count ? LYCHEE_KERNEL_STREAM : r.g_count ? LYCHEE_KERNEL_GATHER
-                        : r.s1_count ? LYCHEE_KERNEL_SELECT1 : r.c_count ? LYCHEE_KERNEL_COMBINE
-                        : LYCHEE_KERNEL_SELECT2;
+                        : r.t_count ? LYCHEE_KERNEL_THRESHOLD : r.c_count ? LYCHEE_KERNEL_COMBINE
+                        : LYCHEE_KERNEL_SELECT;
         if (!ctx->timing) return launch_units(p, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
         lychee_ctx::Rec rec{cls, take_event(ctx), take_event(ctx)};
         if (rec.start == nullptr || rec.stop == nullptr) return LYCHEE_EHIP;
@@ -312,20 +313,23 @@ struct Launcher {
     }
 };
 
-// Layer `l` of the table, three dependent launches: R+G, then S1+C, then S2.
+// Layer `l` of the table, dependent launches: T (only when the layer selects), then R+G,
+// then S+C.
 int run_layer(const Launcher &L, int l, bool select)
 {
+    int rc;
+    if (select) {
+        Ranges t;
+        t.t_first = l, t.t_count = 1;
+        if ((rc = L.go(t)) != LYCHEE_OK) return rc;
+    }
     Ranges a;
     a.r_first = a.g_first = l, a.r_count = a.g_count = 1;
-    int rc = L.go(a);
-    if (rc != LYCHEE_OK) return rc;
+    if ((rc = L.go(a)) != LYCHEE_OK) return rc;
     Ranges b;
     b.c_first = l, b.c_count = 1;
-    if (select) b.s1_first = l, b.s1_count = 1;
-    if ((rc = L.go(b)) != LYCHEE_OK) return rc;
-    Ranges c;
-    if (select) c.s2_first = l, c.s2_count = 1;
-    return L.go(c);
+    if (select) b.s_first = l, b.s_count = 1;
+    return L.go(b);
 }
 
 }  // namespace
@@ -428,8 +432,7 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
     d.copy_keep = 1;
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    Launcher L{ctx, *shape, w, lengths, table, stream, 1};
-    L.choose_slices((int64_t)shape->batch * d.n_rgroups);
+    const Launcher L{ctx, *shape, w, lengths, table, stream};
     return run_layer(L, 0, true);
 }
 
@@ -459,7 +462,7 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
     set_scratch(d, w, static_cast<char *>(workspace), 0);
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+    const Launcher L{ctx, *shape, w, lengths, table, stream};
     return run_layer(L, 0, false);
 }
 
@@ -497,6 +500,9 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
     // group holds no retrieval head keeps reading the array of the last layer that selected
     // for it (Sec. 3.1: the set is propagated unchanged), so nothing is copied between layers.
     // Entry n_layers of the table only assembles the caller's idx_out from those arrays.
+    const bool assemble = idx_out != nullptr;
+    // the last layer's selection is only needed if the caller wants the final sets
+    const int n_select = assemble ? n_layers : n_layers - 1;
     std::vector<LayerDesc> descs((size_t)n_layers + 1);
     const int32_t *cur[kMaxKvHeads];
     for (int g = 0; g < shape->n_kv_heads; ++g) cur[g] = idx_in;
@@ -511,9 +517,9 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
         set_scratch(d, w, ws, l);
         d.idx_out = idx_set_of(w, ws, l);
         for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = cur[g];
-        d.emit_sel = 1;
+        d.emit_sel = l < n_select;
 #ifdef LYCHEE_TRACE
-        if (getenv("LYCHEE_TRACE_NOSEL")) d.emit_sel = 0;  // trace builds: cost of the score writes
+        if (getenv("LYCHEE_TRACE_NOSEL")) d.emit_sel = 0;  // trace builds: cost of collecting candidates
 #endif
         d.copy_keep = 0;
         for (int i = 0; i < d.n_rgroups; ++i) cur[d.rgroup[i]] = d.idx_out;
@@ -526,47 +532,38 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
     }
     fin.idx_out = idx_out;
     fin.copy_keep = 1;
-    const bool assemble = idx_out != nullptr;
-    // the last layer's selection is only needed if the caller wants the final sets
-    const int n_select = assemble ? n_layers : n_layers - 1;
 
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+    const Launcher L{ctx, *shape, w, lengths, table, stream};
 
     const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && (int64_t)n_layers * shape->batch <= kMaxItems;
     if (!phased) {
-        int max_rg = 1;
-        for (int l = 0; l < n_layers; ++l) max_rg = descs[l].n_rgroups > max_rg ? descs[l].n_rgroups : max_rg;
-        L.choose_slices((int64_t)shape->batch * max_rg);
         for (int l = 0; l < n_layers; ++l)
             if ((rc = run_layer(L, l, l < n_select)) != LYCHEE_OK) return rc;
     } else {
-        int64_t rows = 0;
-        for (int l = 0; l < n_select; ++l) rows += (int64_t)shape->batch * descs[l].n_rgroups;
-        L.choose_slices(rows);
         // All layers at once, one launch per phase; each phase needs only earlier phases:
-        //   R (streaming, every layer)  ->  S1  ->  S2  ->  G (gather)  ->  C (combine)
+        //   T (thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
+        Ranges t;
+        t.t_first = 0, t.t_count = n_select;
+        if ((rc = L.go(t)) != LYCHEE_OK) return rc;
         Ranges r;
         r.r_first = 0, r.r_count = n_layers;
         if ((rc = L.go(r)) != LYCHEE_OK) return rc;
-        Ranges s1;
-        s1.s1_first = 0, s1.s1_count = n_select;
-        if ((rc = L.go(s1)) != LYCHEE_OK) return rc;
-        Ranges s2;
-        s2.s2_first = 0, s2.s2_count = n_select;
-        if ((rc = L.go(s2)) != LYCHEE_OK) return rc;
+        Ranges sl;
+        sl.s_first = 0, sl.s_count = n_select;
+        if ((rc = L.go(sl)) != LYCHEE_OK) return rc;
         Ranges g;
         g.g_first = 0, g.g_count = n_layers;
         if ((rc = L.go(g)) != LYCHEE_OK) return rc;
         Ranges c;
         c.c_first = 0, c.c_count = n_layers;
-        if (assemble) c.s2_first = n_layers, c.s2_count = 1;  // the set copies ride along
+        if (assemble) c.s_first = n_layers, c.s_count = 1;  // the set copies ride along
         if ((rc = L.go(c)) != LYCHEE_OK) return rc;
     }
     if (assemble && !phased) {
         Ranges f;
-        f.s2_first = n_layers, f.s2_count = 1;
+        f.s_first = n_layers, f.s_count = 1;
         if ((rc = L.go(f)) != LYCHEE_OK) return rc;
     }
     return LYCHEE_OK;
@@ -606,7 +603,7 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
     }
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, stream, 1};
+    const Launcher L{ctx, *shape, w, lengths, table, stream};
     if (ctx->step_mode != LYCHEE_STEP_PHASED || (int64_t)n_layers * shape->batch > kMaxItems) {
         for (int l = 0; l < n_layers; ++l)
             if ((rc = run_layer(L, l, false)) != LYCHEE_OK) return rc;
@@ -661,6 +658,10 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
     case LYCHEE_OPT_TAIL_PERMILLE:
         if (value < 0 || value > 1000) return LYCHEE_EINVAL;
         ctx->tail_permille = value;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_SELECT_MARGIN:
+        if (value < -10000 || value > 100000) return LYCHEE_EINVAL;
+        ctx->select_margin = value;
         return LYCHEE_OK;
     case LYCHEE_OPT_GATHER_BLOCK:
         if (value < 16 || value > 128 || value % 16) return LYCHEE_EINVAL;

@@ -17,17 +17,17 @@ constexpr int kThreads = LYCHEE_THREADS;  // threads of every workgroup (256 or 
 constexpr int kWaves = kThreads / 64;
 constexpr int kTileRows = 16;            // rows one wavefront handles per iteration
 constexpr int kBlockRows = kWaves * kTileRows;  // cache rows per block of the pooled row space
-constexpr int kSliceQuantum = kThreads * 4;     // select-filter slices are multiples of this
 constexpr int kMaxWg = 1024;             // upper bound of the grid of one launch
 constexpr int kIdxChunk = 2048;          // set entries staged in LDS at a time
-constexpr int kSlices = 32;              // most slices of one score row in the select filter
-constexpr int kSampleBlocks = 64;        // the threshold sample: 64 blocks of 64 scores
-constexpr int kSample = 4096;
+constexpr int kSampleTilesMin = 128;     // the threshold sample: 128 to 256 tiles of 16 rows
+constexpr int kSampleTilesMax = 256;
+constexpr int kDirectLen = 4096;         // sequences this short are ranked without a threshold
+constexpr int kCandBuf = 256;            // candidates a wavefront collects in LDS between flushes
 constexpr float kMinusBig = -1.0e30f;    // "no score yet" sentinel of the running maximum
 
 constexpr int kMaxLayers = 128;          // layers one launch can cover
-constexpr int kMaxItems = 2048;
-constexpr int kTicketRing = 64;          // chunk counters; one is cleared 32 launches before its use          // (layer, sequence) pairs of one launch's pooled rows
+constexpr int kMaxItems = 2048;          // (layer, sequence) pairs of one launch's pooled rows
+constexpr int kTicketRing = 64;          // chunk counters; one is cleared 32 launches before its use
 
 // What every part of a launch shares.
 struct Common {
@@ -35,8 +35,7 @@ struct Common {
     int64_t stride_b, stride_h, stride_t;
     int32_t batch, n_q_heads, n_kv_heads, group;
     int32_t k, max_len, sel_stride;
-    int32_t list_row;     // entries of one score row's filtered list
-    int32_t n_slices;     // slices one score row is filtered in (a power of two <= kSlices)
+    int32_t list_row;     // capacity, in entries, of one score row's candidate list
     int32_t n_wg;         // grid size of this launch
     int32_t part_stride;  // partial slots per head
     uint32_t *tickets;    // ring of kTicketRing chunk counters, zero except the ones in use
@@ -45,6 +44,7 @@ struct Common {
     int32_t chunk_blocks; //   chunk_blocks blocks, to whichever workgroup asks next
     int32_t g_block_rows; // set entries per pooled block of gather work (fewer than kBlockRows:
                           // a gathered row costs more than a streamed one)
+    float sel_margin;     // standard deviations the threshold sample's target rank is raised by
     float scale;          // 1 / sqrt(head_dim)
     float scale_log2e;    // log2(e) / sqrt(head_dim)
 };
@@ -54,19 +54,21 @@ struct Common {
 struct LayerDesc {
     const uint16_t *q, *k_cache, *v_cache;
     uint16_t *out;         // bf16 [B][H_q][128]
-    float *sel;            // [B][n_rgroups][sel_stride] pooled selection scores (scaled logits)
+    float *sel;            // [B][n_rgroups][sel_stride] pooled selection scores (scaled logits),
+                           // written only for a row whose candidate list cannot be used
     float *part_o;         // [B*H_q][part_stride][128] un-normalised partial outputs
     float *part_ml;        // [B*H_q][part_stride][2]   running maximum (raw dot units) and sum
     int32_t *part_count;   // [B*H_q] partial slots in use
-    unsigned long long *list;  // [B*n_rgroups][list_row] filtered scores, slice by slice: ordered key
-                               // in the low 32 bits, position in the high 32 bits
-    int32_t *list_count;   // [B*n_rgroups][kSlices]
+    unsigned long long *list;  // [B*n_rgroups][list_row] candidates in no particular order:
+                               // ordered key in the low 32 bits, position in the high 32 bits
+    int32_t *list_count;   // [B*n_rgroups] candidates found (may exceed list_row: list unusable)
+    uint32_t *thr;         // [B*n_rgroups] ordered key a score must reach to be a candidate
     int32_t *idx_out;      // [B][H_kv][k] where this layer's sets are written
     const int32_t *idx_src[kMaxKvHeads];  // per KV head: base of the [B][H_kv][k] array that
                                           // holds the set this layer inherits for that head
     int32_t n_rgroups, n_sgroups;
-    int32_t emit_sel;      // R units write selection scores
-    int32_t copy_keep;     // S2 also copies the inherited sets of heads that keep theirs
+    int32_t emit_sel;      // R units collect selection candidates
+    int32_t copy_keep;     // S also copies the inherited sets of heads that keep theirs
     uint8_t rgroup[kMaxKvHeads];  // KV heads whose group holds a retrieval head
     uint8_t sgroup[kMaxKvHeads];  // KV heads whose group holds a sparse head
     uint8_t rmask[kMaxKvHeads];   // per KV head: bit i = query head g*G+i is a retrieval head
@@ -80,8 +82,8 @@ struct LaunchPlan {
     int32_t r_first, r_count;    // retrieval streaming
     int32_t g_first, g_count;    // sparse gather
     int32_t c_first, c_count;    // combine
-    int32_t s1_first, s1_count;  // select phase 1
-    int32_t s2_first, s2_count;  // select phase 2 (and set copies)
+    int32_t t_first, t_count;    // selection thresholds
+    int32_t s_first, s_count;    // select (and set copies)
 };
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream);

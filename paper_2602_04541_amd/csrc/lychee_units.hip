@@ -1,23 +1,32 @@
 // The work-unit kernel of liblychee for gfx950 (CDNA4).
 //
 // One launch runs a pooled list of work for a fixed grid of workgroups (about two per CU):
-//   R  retrieval streaming   Eq. 1, o = A V and the pooled selection score ranked by Eq. 2
+//   T  selection threshold   a score that somewhat more than k rows reach, read off a sample
+//                            of the row's pooled scores (Eq. 2's ranking needs only those)
+//   R  retrieval streaming   Eq. 1, o = A V; rows whose pooled score reaches the threshold
+//                            are collected as candidates of Eq. 2's top-k
+//   S  select                exact radix select over the candidates (ties to the lower
+//                            position), ascending write of the set; verbatim copy for groups
+//                            that keep theirs
 //   G  sparse gather         Eq. 3 on the inherited set
 //   C  combine               log-sum-exp merge of a head's partials into its bf16 output
-//   S1 select, phase 1       threshold from a sample of the scores, ordered filter into a list
-//   S2 select, phase 2       exact radix select over the list (ties to the lower position),
-//                            ordered write of the set; verbatim copy for groups that keep theirs
 // A launch names, for each kind, the range of layers it covers in a table of layer
 // descriptors in device memory.  The units of one launch are mutually independent;
 // everything that depends on another unit's result runs in a later launch, so there are no
-// device-side waits, fences or atomics on global memory.
+// device-side waits or fences; the only atomics on global memory are counters whose final
+// value, not the order of the additions, is what later launches use.
+//
+// Why candidates and not scores: writing every pooled score (4 bytes per 516 streamed) cost
+// the streaming launch 12 % of its time, most of it HBM write traffic interleaved with the
+// read stream, and a later pass had to read the scores back.  With a threshold known before
+// the rows stream by, only about 6 % of the scores leave the CU, in bursts.
 //
 // Pooling (App. C describes pooling full and sparse block work into uniform splits).  The R
 // and G rows of a launch, over all its layers, sequences and KV heads, form one row space
 // cut into blocks of 64 rows (fewer for gathered rows, which cost more); every workgroup
 // takes an equal, contiguous run of blocks.  A run may cross from one (layer, sequence, KV
 // head) segment into the next; each (workgroup, segment) piece leaves one partial per head in
-// a slot that depends only on the shapes, never on timing.  Small units (C, S1, S2) are
+// a slot that depends only on the shapes, never on timing.  Small units (T, S, C) are
 // dealt round-robin.
 //
 // Data path of R and G.  Cache rows go from HBM to registers with 16-byte nontemporal loads:
@@ -39,10 +48,11 @@ struct SharedAttn {
     int32_t idx_s[kIdxChunk];
     float red_o[kWaves * kMaxGroup * kHeadDim];
     float red_ml[kWaves * kMaxGroup * 2];
+    unsigned long long cand[kWaves][kCandBuf];  // per wavefront: candidates not yet flushed
 };
 struct SharedSelect {
-    uint32_t hist[4096];
-    int32_t slice_pre[kSlices + 1];
+    uint32_t hist[4096];                   // radix histograms; position bitmap of the ordered write
+    uint32_t samp[kSampleTilesMax * 16];   // ordered keys of the threshold sample
     uint32_t found[2];
 };
 struct SharedCombine {
@@ -50,7 +60,6 @@ struct SharedCombine {
     float red[(kThreads / 32) * kHeadDim];
 };
 union SharedUnit {
-    SharedAttn attn;
     SharedSelect sel;
     SharedCombine comb;
 };
@@ -244,6 +253,21 @@ struct Acc {
     float l[NH];  // running sum of exp
 };
 
+// q . k of one cache row: each of the row's 16 lanes holds 8 elements; all 16 end with the sum.
+__device__ __forceinline__ float row_score(const uint4 &kr, const uint4 &qh)
+{
+    float a = dot2_bf16(kr.x, qh.x, 0.0f);
+    a = dot2_bf16(kr.y, qh.y, a);
+    a = dot2_bf16(kr.z, qh.z, a);
+    a = dot2_bf16(kr.w, qh.w, a);
+    return row16_sum(a);
+}
+
+// The pooled selection score of a row (App. F: the group's retrieval heads are averaged) from
+// the sum of its heads' dot products; sel_mul = 1 / (sqrt(d) * heads).  Adding +0 turns a -0
+// into +0, so equal scores have equal bits.
+__device__ __forceinline__ float sel_value(float pooled_sum, float sel_mul) { return pooled_sum * sel_mul + 0.0f; }
+
 template <int NH>
 __device__ __forceinline__ void consume_tile(const Tile &t, const uint4 (&qf)[NH], Acc<NH> &acc,
                                              float c_log2e, float (&sel_sum)[4])
@@ -253,13 +277,7 @@ __device__ __forceinline__ void consume_tile(const Tile &t, const uint4 (&qf)[NH
     for (int j = 0; j < 4; ++j) {
         const bool ok = (t.valid >> j) & 1;
 #pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            float a = dot2_bf16(t.k[j].x, qf[h].x, 0.0f);
-            a = dot2_bf16(t.k[j].y, qf[h].y, a);
-            a = dot2_bf16(t.k[j].z, qf[h].z, a);
-            a = dot2_bf16(t.k[j].w, qf[h].w, a);
-            s[h][j] = row16_sum(a);
-        }
+        for (int h = 0; h < NH; ++h) s[h][j] = row_score(t.k[j], qf[h]);
         float pooled = s[0][j];
 #pragma unroll
         for (int h = 1; h < NH; ++h) pooled += s[h][j];
@@ -313,19 +331,42 @@ __device__ __forceinline__ void consume_tile(const Tile &t, const uint4 (&qf)[NH
     }
 }
 
+// Where the candidates of one segment's score row go.
+struct Emit {
+    unsigned long long *list;  // nullptr: the segment collects no candidates
+    int32_t *count;
+    uint32_t thr;              // a row is a candidate when its ordered key reaches this
+    int32_t cap;
+};
+
+// Appends a wavefront's n buffered candidates to the row's list.  The counter keeps counting
+// past the capacity, which is how the select unit learns that the list is incomplete.
+__device__ __forceinline__ void flush_candidates(const unsigned long long *buf, int n, const Emit &em)
+{
+    const int lane = threadIdx.x & 63;
+    int base = 0;
+    if (lane == 0)
+        base = __hip_atomic_fetch_add((LYCHEE_GLOBAL int32_t *)em.count, (int32_t)n, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (int i = lane; i < n; i += 64)
+        if (base + i < em.cap) gstore(em.list + base + i, buf[i]);
+}
+
 // Streams rows [r0, r1) of one segment through the accumulators.  GATHER = false: cache rows
 // r0..r1-1; true: the cache rows named by set entries r0..r1-1, staged in idx_s[0 .. r1-r0).
 //
 // Rows are dealt in spans of 32 * kWaves: wavefront w owns rows 32w .. 32w+31 of every span,
 // as two tiles of 16 rows (4 rows per load instruction, K and V).  The two tile buffers
 // alternate: one tile's loads are in flight while the other is consumed.  After both tiles of
-// a span the wavefront writes its 32 selection scores as one full 128-byte line; writing
-// them in 16-byte fragments cost the streaming launch 14 % of its time.
+// a span the wavefront compares its 32 pooled scores with the threshold and puts the rows
+// that reach it into its LDS buffer, which goes to the list in bursts.
 template <int NH, bool GATHER>
 __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kbase,
                                             const uint16_t *vbase, const uint4 (&qf)[NH],
                                             Acc<NH> &acc, int L, int r0, int r1,
-                                            const int32_t *idx_s, float *sel_row, float sel_mul)
+                                            const int32_t *idx_s, const Emit &em, float sel_mul,
+                                            unsigned long long *cand_buf)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -359,23 +400,14 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
         }
     };
     auto consume = [&](const Tile &t, float (&sel_sum)[4]) {
-#ifdef LYCHEE_PROBE_NOCOMPUTE
-        {   // probe build only: touch the loaded data and nothing else
-            uint32_t x = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) x ^= t.k[j].x ^ t.k[j].y ^ t.k[j].z ^ t.k[j].w ^ t.v[j].x ^ t.v[j].y ^ t.v[j].z ^ t.v[j].w;
-            acc.o[0][0] += __builtin_bit_cast(float, x & 0x3F800000u);
-            sel_sum[0] = sel_sum[1] = sel_sum[2] = sel_sum[3] = acc.o[0][0];
-        }
-#else
         consume_tile<NH>(t, qf, acc, c_log2e, sel_sum);
-#endif
     };
 
     // Loads are issued unconditionally (a tile past the end re-reads the segment's last row
     // and is marked invalid): a conditional refill would make the tile registers loop-carried
     // through a copy that has to wait for its load.
     Tile t0, t1;
+    int cand_n = 0;  // candidates in cand_buf; the same in every lane
     if (n_spans == 0) return;
     issue(t0, 0, 0);
     issue(t1, 0, 1);
@@ -391,9 +423,8 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
         __builtin_amdgcn_sched_barrier(0);
         issue(t1, span + 1, 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (!GATHER && sel_row != nullptr) {
-            // lane ch (< 8) of each row slot stores the score of row 16*(ch/4) + 4*(ch%4) + rs:
-            // 32 lanes, 32 consecutive floats
+        if (!GATHER && em.list != nullptr) {
+            // lane ch (< 8) of each row slot holds the score of row 16*(ch/4) + 4*(ch%4) + rs
             const int j = ch & 3;
             float lo = sel0[0], hi = sel1[0];
             lo = (j == 1) ? sel0[1] : lo;
@@ -404,9 +435,22 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             hi = (j == 3) ? sel1[3] : hi;
             const float mine = (ch & 4) ? hi : lo;
             const int r = r0 + span * kSpan + 32 * wave + 16 * ((ch >> 2) & 1) + 4 * j + rs;
-            if (ch < 8 && r < r1) gstore(sel_row + r, mine * sel_mul + 0.0f);  // +0 turns -0 into +0
+            const uint32_t key = ordered_key(sel_value(mine, sel_mul));
+            const bool hit = ch < 8 && r < r1 && key >= em.thr;
+            const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
+            if (hits != 0) {  // wave-uniform
+                const int before = (int)__builtin_amdgcn_mbcnt_hi(
+                    (uint32_t)(hits >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hits, 0u));
+                if (hit) cand_buf[cand_n + before] = (unsigned long long)key | ((unsigned long long)(uint32_t)r << 32);
+                cand_n += __builtin_popcountll(hits);
+                if (cand_n > kCandBuf - 32) {
+                    flush_candidates(cand_buf, cand_n, em);
+                    cand_n = 0;
+                }
+            }
         }
     }
+    if (!GATHER && em.list != nullptr && cand_n > 0) flush_candidates(cand_buf, cand_n, em);
 }
 
 // One (workgroup, segment) piece: rows/entries [r0, r1) of segment (b, g) for the heads in
@@ -415,7 +459,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
 template <int NH, bool GATHER>
 __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, const uint16_t *k_cache,
                                           const uint16_t *v_cache, const int32_t *idx_src,
-                                          float *sel_row, float *part_o, float *part_ml,
+                                          const Emit &em, float *part_o, float *part_ml,
                                           int32_t *part_count, int b, int g, uint32_t hmask, int L,
                                           int r0, int r1, int slot, bool ends_segment,
                                           SharedAttn &sh)
@@ -458,10 +502,10 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             __syncthreads();  // the previous chunk's readers are done
             for (int i = threadIdx.x; i < e1 - e0; i += kThreads) sh.idx_s[i] = gload(idx_src + e0 + i);
             __syncthreads();
-            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, nullptr, 0.0f);
+            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr);
         }
     } else {
-        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, sel_row, sel_mul);
+        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave]);
     }
 
     TRACE(7);
@@ -528,16 +572,16 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
 template <bool GATHER>
 __device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const uint16_t *q,
                                                const uint16_t *k_cache, const uint16_t *v_cache,
-                                               const int32_t *idx_src, float *sel_row, float *part_o,
+                                               const int32_t *idx_src, const Emit &em, float *part_o,
                                                float *part_ml, int32_t *part_count, int b, int g,
                                                uint32_t hmask, int L, int r0, int r1, int slot,
                                                bool ends_segment, SharedAttn &sh)
 {
     switch (nh) {
-    case 1: run_piece<1, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
-    case 2: run_piece<2, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
-    case 3: run_piece<3, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
-    default: run_piece<4, GATHER>(c, q, k_cache, v_cache, idx_src, sel_row, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    case 1: run_piece<1, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    case 2: run_piece<2, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    case 3: run_piece<3, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    default: run_piece<4, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
     }
 }
 
@@ -598,13 +642,7 @@ __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p
     __syncthreads();
 }
 
-// ------------------------------------------------------------------------------ S1 and S2
-__device__ __forceinline__ int slice_len_of(int L, int n_slices)
-{
-    const int per = (L + n_slices - 1) / n_slices;
-    return (per + kSliceQuantum - 1) / kSliceQuantum * kSliceQuantum;
-}
-
+// ------------------------------------------------------------------------------ T and S
 // In the histogram of `n_bins` digits, finds the highest digit d whose suffix count
 // (keys with digit >= d) reaches `need`; returns d and need minus the count above d.
 template <int kBins>
@@ -640,126 +678,229 @@ __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t need, 
     __syncthreads();
 }
 
-// Phase 1 of the selection for slice `slice` of score row (b, rgi): a threshold T0 that keeps
-// somewhat more than n = min(k, L) scores is read off a histogram of a fixed sample of the
-// row (every slice derives the same T0); the slice's scores >= T0 are written, in position
-// order, as (ordered key, position) pairs.
-__device__ __forceinline__ void select1_unit(const Common &c, const LayerDesc &p, int b, int rgi, int slice,
-                                             SharedSelect &sh, SharedPool &pool)
+template <int NH>
+__device__ __forceinline__ void load_q(const Common &c, const uint16_t *q, int b, int g, uint32_t hmask,
+                                       uint4 (&qf)[NH])
 {
+    const int ch = threadIdx.x & 15;
+    uint32_t mk = hmask;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        const int bit = __builtin_ctz(mk);
+        mk &= mk - 1;
+        qf[h] = gload_u4(q + ((int64_t)b * c.n_q_heads + g * c.group + bit) * kHeadDim + ch * 8);
+    }
+}
+
+// Pooled scores of the 16 rows base .. base+15 of one KV head (rows past L-1 repeat row L-1);
+// afterwards lane (rs, ch) with ch < 4 holds the score of row base + 4*ch + rs.
+template <int NH>
+__device__ __forceinline__ float tile_pooled_score(const uint4 (&kr)[4], const uint4 (&qf)[NH], float sel_mul)
+{
+    const int ch = threadIdx.x & 15;
+    float mine = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float pooled = row_score(kr[j], qf[0]);
+#pragma unroll
+        for (int h = 1; h < NH; ++h) pooled += row_score(kr[j], qf[h]);
+        mine = (ch == j) ? sel_value(pooled, sel_mul) : mine;
+    }
+    return mine;
+}
+
+// T unit of score row (b, rgi): the ordered key that a row's pooled score has to reach to
+// become a candidate.  The key is the target-th largest of a sample of the row's scores,
+// to 22 bits, where target is the number of sampled rows expected among the top n = min(k, L)
+// plus sel_margin (six, unless the caller changes it) standard deviations; the streamed rows
+// that reach it are then very likely at least n and a few thousand more at most.  Whatever the sample yields, the select unit
+// checks the candidate count and ranks the whole row itself when the list cannot be used.
+// The sample is one 16-row tile at a hashed offset inside each of n_tiles equal strata.
+template <int NH>
+__device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc &p, int b, int rgi,
+                                               SharedSelect &sh, SharedPool &pool)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rs = lane >> 4;
+    const int ch = lane & 15;
     const int L = clamp_len(c.lengths[b], c.max_len);
     const int n = c.k < L ? c.k : L;
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
-    int32_t *count_out = p.list_count + row * kSlices + slice;
-    const int slen = slice_len_of(L, c.n_slices);
-    const int s0 = slice * slen;
-    if (n == L || s0 >= L) {  // everything is selected, or the slice is empty
-        if (threadIdx.x == 0) gstore(count_out, (int32_t)0);
+    if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
+    if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
+        // everything is selected anyway (no candidates wanted), or every row is a candidate
+        if (threadIdx.x == 0) gstore(p.thr + row, n == L ? 0xFFFFFFFFu : 0u);
         return;
     }
-    const float *sel = p.sel + row * c.sel_stride;
-    // ---- threshold from the sample
+    int n_tiles = L / 1024;
+    n_tiles = n_tiles < kSampleTilesMin ? kSampleTilesMin : (n_tiles > kSampleTilesMax ? kSampleTilesMax : n_tiles);
+    const int n_sample = n_tiles * 16;
+    const int g = p.rgroup[rgi];
+    const uint32_t hmask = p.rmask[g] & ((1u << c.group) - 1u);
+    uint4 qf[NH];
+    load_q<NH>(c, p.q, b, g, hmask, qf);
+    const uint16_t *kbase = p.k_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
+    const float sel_mul = c.scale / (float)NH;
     for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
     __syncthreads();
-    const int n_sample = L <= kSample ? L : kSample;
-    float sv[kSample / kThreads];
-    {
+
+    constexpr int kBatch = 8;  // tiles a wavefront has in flight
+    const int stratum = L / n_tiles;  // >= 32
+    for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
+        uint4 kr[kBatch][4];
 #pragma unroll
-        for (int u = 0; u < kSample / kThreads; ++u) {
-            const int i = threadIdx.x + u * kThreads;
-            int pos = i;
-            if (L > kSample) pos = (int)(((int64_t)(i >> 6) * L / kSampleBlocks) & ~3ll) + (i & 63);
-            sv[u] = i < n_sample ? gload(sel + pos) : 0.0f;
+        for (int u = 0; u < kBatch; ++u) {
+            const int t = t0 + u < n_tiles ? t0 + u : n_tiles - 1;
+            const uint32_t hsh = ((uint32_t)t * 2654435761u + (uint32_t)row * 40503u) >> 12;
+            const int base = t * stratum + (int)(hsh % (uint32_t)(stratum - 15));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                kr[u][j] = gload_u4(kbase + (int64_t)(base + 4 * j + rs) * c.stride_t + ch * 8);
         }
 #pragma unroll
-        for (int u = 0; u < kSample / kThreads; ++u)
-            if (threadIdx.x + u * kThreads < n_sample) atomicAdd(&sh.hist[ordered_key(sv[u]) >> 20], 1u);
+        for (int u = 0; u < kBatch; ++u) {
+            const uint32_t key = ordered_key(tile_pooled_score<NH>(kr[u], qf, sel_mul));
+            if (t0 + u < n_tiles && ch < 4) {
+                sh.samp[(t0 + u) * 16 + 4 * ch + rs] = key;
+                atomicAdd(&sh.hist[key >> 20], 1u);
+            }
+        }
     }
     __syncthreads();
-    uint32_t target;
-    if (L <= kSample) {
-        target = (uint32_t)n;
-    } else {
-        const float f = (float)n_sample * (float)n / (float)L;
-        target = (uint32_t)(f + 4.0f * sqrtf(f) + 8.0f);
-    }
-    uint32_t t0 = 0;
+    const float f = (float)n_sample * (float)n / (float)L;
+    const float want = f + c.sel_margin * sqrtf(f) + 6.0f;
+    const uint32_t target = want < 1.0f ? 1u : (want > (float)n_sample ? (uint32_t)n_sample : (uint32_t)want);
+    uint32_t t_key = 0;
     if (target < (uint32_t)n_sample) {
-        // the sample's target-th largest key, to 22 bits: top 12 bits, then the next 10
+        // the sample's target-th largest key: top 12 bits, then the next 10
         uint32_t d1, rest1, d2, rest2;
         find_digit<4096>(sh.hist, target, sh.found, pool.scan, d1, rest1);
         for (int i = threadIdx.x; i < 1024; i += kThreads) sh.hist[i] = 0;
         __syncthreads();
-#pragma unroll
-        for (int u = 0; u < kSample / kThreads; ++u) {
-            const uint32_t key = ordered_key(sv[u]);
-            if (threadIdx.x + u * kThreads < n_sample && (key >> 20) == d1)
-                atomicAdd(&sh.hist[(key >> 10) & 1023u], 1u);
+        for (int i = threadIdx.x; i < n_sample; i += kThreads) {
+            const uint32_t key = sh.samp[i];
+            if ((key >> 20) == d1) atomicAdd(&sh.hist[(key >> 10) & 1023u], 1u);
         }
         __syncthreads();
         find_digit<1024>(sh.hist, rest1, sh.found, pool.scan, d2, rest2);
-        t0 = (d1 << 20) | (d2 << 10);
+        t_key = (d1 << 20) | (d2 << 10);
     }
-    // ---- ordered filter of the slice: rounds of kThreads*4 scores, four rounds per batch;
-    // the next batch's loads are in flight while this one is scanned and written, and one
-    // scan of four packed 16-bit counts places all four rounds
-    unsigned long long *dst = p.list + row * (int64_t)c.list_row + (int64_t)slice * slen;
-    const int s1 = s0 + slen < L ? s0 + slen : L;
-    uint32_t base = 0;
-    const int n_it = (s1 - s0 + kThreads * 4 - 1) / (kThreads * 4);
-    auto load_batch = [&](float4 (&x)[4], int it0) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
-            x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i0 < s1) x[u] = gload_f4(sel + i0);  // rows are padded to 64
-        }
-    };
-    float4 cur[4], nxt[4];
-    load_batch(cur, 0);
-    for (int it0 = 0; it0 < n_it; it0 += 4) {
-        load_batch(nxt, it0 + 4);  // past the end: nothing is loaded
-        uint32_t keys[4][4], pass[4];
-        unsigned long long packed = 0;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
-            const float xs[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
-            pass[u] = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                keys[u][j] = ordered_key(xs[j]);
-                pass[u] |= (uint32_t)(i0 + j < s1 && keys[u][j] >= t0) << j;
-            }
-            packed |= (unsigned long long)__builtin_popcount(pass[u]) << (16 * u);
-        }
-        unsigned long long total;
-        const unsigned long long excl = block_scan64(packed, pool.scan64, total) - packed;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i0 = s0 + (it0 + u) * kThreads * 4 + threadIdx.x * 4;
-            uint32_t at = base + (uint32_t)((excl >> (16 * u)) & 0xFFFFull);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((pass[u] >> j) & 1u)
-                    gstore(dst + at++, (unsigned long long)keys[u][j] | ((unsigned long long)(uint32_t)(i0 + j) << 32));
-            base += (uint32_t)((total >> (16 * u)) & 0xFFFFull);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
-    }
-    if (threadIdx.x == 0) gstore(count_out, (int32_t)base);
+    if (threadIdx.x == 0) gstore(p.thr + row, t_key);
 }
 
-constexpr int kS2Regs = 40;  // candidates one thread keeps in registers in the fast path
-
-// Radix select + ordered compaction straight from memory (any number of candidates).
-template <typename Fetch>
-__device__ __forceinline__ void select2_slow(const Common &c, int n, int total, Fetch &fetch, int32_t *dst,
-                                             SharedSelect &sh, SharedPool &pool)
+// Writes the pooled score of every row of (b, g) into sel[0 .. L): what the select unit falls
+// back on when a row's candidate list is short of n entries or has overflowed.
+template <int NH>
+__device__ __forceinline__ void score_row_unit(const Common &c, const LayerDesc &p, int b, int g, int L, float *sel)
 {
-    // ---- radix select: the n-th largest key
-    uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)n;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rs = lane >> 4;
+    const int ch = lane & 15;
+    const uint32_t hmask = p.rmask[g] & ((1u << c.group) - 1u);
+    uint4 qf[NH];
+    load_q<NH>(c, p.q, b, g, hmask, qf);
+    const uint16_t *kbase = p.k_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
+    const float sel_mul = c.scale / (float)NH;
+    const int n_tiles = (L + 15) / 16;
+    constexpr int kBatch = 4;
+    for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
+        uint4 kr[kBatch][4];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int r = (t0 + u) * 16 + 4 * j + rs;
+                r = r < L ? r : L - 1;
+                kr[u][j] = gload_u4(kbase + (int64_t)r * c.stride_t + ch * 8);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const float v = tile_pooled_score<NH>(kr[u], qf, sel_mul);
+            const int r = (t0 + u) * 16 + 4 * ch + rs;
+            if (ch < 4 && r < L) gstore(sel + r, v);
+        }
+    }
+}
+
+// The three sources of (ordered key, position) entries the select unit ranks.
+constexpr int kSelRegs = 40;  // entries one thread keeps in registers
+struct RegEntries {           // up to kThreads * kSelRegs list entries, loaded once
+    uint32_t key[kSelRegs], pos[kSelRegs];
+    __device__ __forceinline__ void load(const unsigned long long *list, int total)
+    {
+#pragma unroll
+        for (int e = 0; e < kSelRegs; ++e) {
+            const int i = threadIdx.x + e * kThreads;
+            key[e] = 0;
+            pos[e] = 0xFFFFFFFFu;  // marks "no entry"
+            if (i < total) {
+                const unsigned long long v = gload(list + i);
+                key[e] = (uint32_t)v;
+                pos[e] = (uint32_t)(v >> 32);
+            }
+        }
+    }
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+#pragma unroll
+        for (int e = 0; e < kSelRegs; ++e) {
+            if (pos[e] != 0xFFFFFFFFu) f(key[e], pos[e]);
+            // one entry after the other: interleaving all 40 costs more registers than there are
+            if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+};
+struct ListEntries {          // a longer list, read from memory on every pass
+    const unsigned long long *list;
+    int total;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kThreads) {
+            unsigned long long v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                v[u] = gload(list + (i < total ? i : total - 1));  // unconditional: the loads overlap
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (i0 + u * kThreads < total) f((uint32_t)v[u], (uint32_t)(v[u] >> 32));
+        }
+    }
+};
+struct RowEntries {           // every row of the sequence, from its recomputed scores
+    const float *sel;
+    int total;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kThreads) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                v[u] = gload(sel + (i < total ? i : total - 1));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (i0 + u * kThreads < total) f(ordered_key(v[u]), (uint32_t)(i0 + u * kThreads));
+        }
+    }
+};
+
+// The `need`-th largest of the 32-bit values val(key, pos) over the entries that pass
+// `among`, by radix select (12 + 10 + 10 bits); `rest` = how many entries equal to the
+// result are among the `need` largest.
+template <typename Entries, typename Val, typename Among>
+__device__ __forceinline__ uint32_t radix_select(const Entries &E, uint32_t need, Val val, Among among,
+                                                 uint32_t &rest, SharedSelect &sh, SharedPool &pool)
+{
+    uint32_t prefix = 0, prefix_mask = 0;
 #pragma unroll
     for (int pass = 0; pass < 3; ++pass) {
         const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
@@ -767,69 +908,85 @@ __device__ __forceinline__ void select2_slow(const Common &c, int n, int total, 
         const uint32_t digit_mask = (uint32_t)n_bins - 1u;
         for (int i = threadIdx.x; i < n_bins; i += kThreads) sh.hist[i] = 0;
         __syncthreads();
-        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kThreads) {
-            uint32_t key[8], pos[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = i0 + u * kThreads;
-                fetch(i < total ? i : total - 1, key[u], pos[u]);  // unconditional: loads overlap
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (i0 + u * kThreads < total && (key[u] & prefix_mask) == prefix)
-                    atomicAdd(&sh.hist[(key[u] >> shift) & digit_mask], 1u);
-        }
+        E.for_each([&](uint32_t key, uint32_t pos) {
+            const uint32_t v = val(key, pos);
+            if (among(key, pos) && (v & prefix_mask) == prefix) atomicAdd(&sh.hist[(v >> shift) & digit_mask], 1u);
+        });
         __syncthreads();
-        uint32_t digit, rest;
+        uint32_t digit, left;
         if (pass == 0)
-            find_digit<4096>(sh.hist, need, sh.found, pool.scan, digit, rest);
+            find_digit<4096>(sh.hist, need, sh.found, pool.scan, digit, left);
         else
-            find_digit<1024>(sh.hist, need, sh.found, pool.scan, digit, rest);
+            find_digit<1024>(sh.hist, need, sh.found, pool.scan, digit, left);
         prefix |= digit << shift;
         prefix_mask |= digit_mask << shift;
-        need = rest;
+        need = left;
     }
-    const uint32_t T = prefix;   // the n-th largest key
-    const uint32_t r_eq = need;  // how many keys == T are kept: those at the lowest positions
+    rest = need;
+    return prefix;
+}
 
-    // ---- ordered compaction: keys > T, and the first r_eq keys == T, in position order
-    uint32_t base_gt = 0, base_eq = 0;
-    for (int t0 = 0; t0 < total; t0 += kThreads * 4) {
-        const int i0 = t0 + threadIdx.x * 4;
-        uint32_t gt = 0, eq = 0, poss[4];
+// Exact top-n of the entries by key, ties to the lower position (Eq. 2), written to dst in
+// ascending position order.  The entries may come in any order: the n-th largest key T and the
+// number r_eq of entries equal to T that belong to the top n come from a radix select; when
+// more than r_eq entries equal T, a second radix select finds the r_eq-th lowest position
+// among them; the chosen positions are then marked in an LDS bitmap, 131072 positions at a
+// time, and read back in order.
+template <typename Entries>
+__device__ __forceinline__ void select_from(const Entries &E, int n, int L, int32_t *dst, SharedSelect &sh,
+                                            SharedPool &pool)
+{
+    uint32_t r_eq;
+    const uint32_t T = radix_select(
+        E, (uint32_t)n, [](uint32_t key, uint32_t) { return key; }, [](uint32_t, uint32_t) { return true; }, r_eq,
+        sh, pool);
+    uint32_t my_eq = 0;
+    E.for_each([&](uint32_t key, uint32_t) { my_eq += (uint32_t)(key == T); });
+    uint32_t n_eq;
+    (void)block_scan(my_eq, pool.scan, n_eq);
+    uint32_t pos_cut = 0xFFFFFFFFu;  // entries equal to T are taken up to this position
+    if (r_eq < n_eq) {
+        uint32_t unused;
+        pos_cut = ~radix_select(
+            E, r_eq, [](uint32_t, uint32_t pos) { return ~pos; }, [&](uint32_t key, uint32_t) { return key == T; },
+            unused, sh, pool);
+    }
+    constexpr uint32_t kWindow = 4096u * 32u;
+    constexpr int kPer = 4096 / kThreads;
+    uint32_t base = 0;
+    for (uint32_t w0 = 0; w0 < (uint32_t)L; w0 += kWindow) {
+        for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
+        __syncthreads();
+        E.for_each([&](uint32_t key, uint32_t pos) {
+            const uint32_t rel = pos - w0;
+            if ((key > T || (key == T && pos <= pos_cut)) && rel < kWindow) atomicOr(&sh.hist[rel >> 5], 1u << (rel & 31u));
+        });
+        __syncthreads();
+        uint32_t words[kPer], cnt = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (i0 + j < total) {
-                uint32_t key;
-                fetch(i0 + j, key, poss[j]);
-                gt |= (uint32_t)(key > T) << j;
-                eq |= (uint32_t)(key == T) << j;
-            }
+        for (int j = 0; j < kPer; ++j) {
+            words[j] = sh.hist[threadIdx.x * kPer + j];
+            cnt += (uint32_t)__builtin_popcount(words[j]);
         }
-        const uint32_t packed = (uint32_t)__builtin_popcount(gt) | ((uint32_t)__builtin_popcount(eq) << 16);
         uint32_t tot;
-        const uint32_t excl = block_scan(packed, pool.scan, tot) - packed;
-        uint32_t n_gt = base_gt + (excl & 0xFFFFu);
-        uint32_t n_eq = base_eq + (excl >> 16);
+        uint32_t at = base + block_scan(cnt, pool.scan, tot) - cnt;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if ((gt >> j) & 1u) {
-                gstore(dst + n_gt + (n_eq < r_eq ? n_eq : r_eq), (int32_t)poss[j]);
-                ++n_gt;
-            } else if ((eq >> j) & 1u) {
-                if (n_eq < r_eq) gstore(dst + n_gt + n_eq, (int32_t)poss[j]);
-                ++n_eq;
+        for (int j = 0; j < kPer; ++j) {
+            uint32_t wd = words[j];
+            while (wd != 0) {
+                const uint32_t bit = (uint32_t)__builtin_ctz(wd);
+                wd &= wd - 1u;
+                if (at < (uint32_t)n) gstore(dst + at, (int32_t)(w0 + (uint32_t)(threadIdx.x * kPer + j) * 32u + bit));
+                ++at;
             }
         }
-        base_gt += tot & 0xFFFFu;
-        base_eq += tot >> 16;
+        base += tot;
     }
 }
 
-// Phase 2 for KV head (b, g): exact top-n of the row from the filtered list (or from the raw
-// scores when the list is too short), ties to the lower position, written ascending.
-__device__ __forceinline__ void select2_unit(const Common &c, const LayerDesc &p, int b, int g,
-                                             SharedSelect &sh, SharedPool &pool)
+// S unit of KV head (b, g): the set the next layer's sparse heads of the group inherit.
+__device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p, int b, int g,
+                                            SharedSelect &sh, SharedPool &pool)
 {
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
@@ -846,108 +1003,30 @@ __device__ __forceinline__ void select2_unit(const Common &c, const LayerDesc &p
         return;
     }
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
-    const float *sel = p.sel + row * c.sel_stride;
     const unsigned long long *list = p.list + row * (int64_t)c.list_row;
-    const int slen = slice_len_of(L, c.n_slices);
-    __syncthreads();
-    if (threadIdx.x < 64) {  // one slice count per lane, prefix sum inside the wavefront
-        int cnt = 0;
-        if (threadIdx.x < c.n_slices) {
-            cnt = gload(p.list_count + row * kSlices + threadIdx.x);
-            cnt = cnt < 0 ? 0 : (cnt > slen ? slen : cnt);
-        }
-        int incl = cnt;
-#pragma unroll
-        for (int d = 1; d < kSlices; d <<= 1) {
-            const int y = __shfl_up(incl, d);
-            if ((int)threadIdx.x >= d) incl += y;
-        }
-        if (threadIdx.x < kSlices) sh.slice_pre[threadIdx.x + 1] = incl;
-        if (threadIdx.x == 0) sh.slice_pre[0] = 0;
-    }
-    __syncthreads();
-    int total = sh.slice_pre[kSlices];
+    const int total = gload(p.list_count + row);
     TRACE(5);
-    const bool raw = total < n;  // the sampled threshold kept too few: rank the raw row
-    if (raw) total = L;
-    // element i of the candidate sequence (ascending by position in both cases)
-    auto fetch = [&](int i, uint32_t &key, uint32_t &pos) {
-        if (raw) {
-            key = ordered_key(gload(sel + i));
-            pos = (uint32_t)i;
-        } else {
-            int lo = 0;
-#pragma unroll
-            for (int step = kSlices / 2; step >= 1; step >>= 1)
-                if (sh.slice_pre[lo + step] <= i) lo += step;
-            const unsigned long long e = gload(list + (int64_t)lo * slen + (i - sh.slice_pre[lo]));
-            key = (uint32_t)e;
-            pos = (uint32_t)(e >> 32);
-        }
-    };
-
-    if (!raw && total <= kThreads * kS2Regs) {
-        // Fast path: thread t keeps candidates [t*per, (t+1)*per) in registers, loaded with
-        // all loads in flight at once; the passes then never touch global memory again.
-        const int per = (total + kThreads - 1) / kThreads;
-        uint32_t keys[kS2Regs], poss[kS2Regs];
-#pragma unroll
-        for (int e = 0; e < kS2Regs; ++e) {
-            const int i = threadIdx.x * per + e;
-            keys[e] = 0;
-            poss[e] = 0xFFFFFFFFu;  // marks "no candidate"
-            if (e < per && i < total) fetch(i, keys[e], poss[e]);
-        }
-        uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)n;
-        if (keys[0] == 0xDEADBEEFu) prefix = 1;  // (trace builds: forces the loads to land here)
+    if (total >= n && total <= kThreads * kSelRegs && total <= c.list_row) {
+        RegEntries E;
+        E.load(list, total);
         TRACE(6);
-#pragma unroll
-        for (int pass = 0; pass < 3; ++pass) {
-            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
-            const int n_bins = pass == 0 ? 4096 : 1024;
-            const uint32_t digit_mask = (uint32_t)n_bins - 1u;
-            for (int i = threadIdx.x; i < n_bins; i += kThreads) sh.hist[i] = 0;
-            __syncthreads();
-#pragma unroll
-            for (int e = 0; e < kS2Regs; ++e)
-                if (poss[e] != 0xFFFFFFFFu && (keys[e] & prefix_mask) == prefix)
-                    atomicAdd(&sh.hist[(keys[e] >> shift) & digit_mask], 1u);
-            __syncthreads();
-            uint32_t digit, rest;
-            if (pass == 0)
-                find_digit<4096>(sh.hist, need, sh.found, pool.scan, digit, rest);
-            else
-                find_digit<1024>(sh.hist, need, sh.found, pool.scan, digit, rest);
-            prefix |= digit << shift;
-            prefix_mask |= digit_mask << shift;
-            need = rest;
-        }
-        const uint32_t T = prefix, r_eq = need;
-        TRACE(7);
-        uint32_t cnt_gt = 0, cnt_eq = 0;
-#pragma unroll
-        for (int e = 0; e < kS2Regs; ++e) {
-            const bool have = poss[e] != 0xFFFFFFFFu;
-            cnt_gt += (uint32_t)(have && keys[e] > T);
-            cnt_eq += (uint32_t)(have && keys[e] == T);
-        }
-        const uint32_t packed = cnt_gt | (cnt_eq << 16);
-        uint32_t tot;
-        const uint32_t excl = block_scan(packed, pool.scan, tot) - packed;
-        uint32_t n_gt = excl & 0xFFFFu, n_eq = excl >> 16;
-#pragma unroll
-        for (int e = 0; e < kS2Regs; ++e) {
-            if (poss[e] == 0xFFFFFFFFu) continue;
-            if (keys[e] > T) {
-                gstore(dst + n_gt + (n_eq < r_eq ? n_eq : r_eq), (int32_t)poss[e]);
-                ++n_gt;
-            } else if (keys[e] == T) {
-                if (n_eq < r_eq) gstore(dst + n_gt + n_eq, (int32_t)poss[e]);
-                ++n_eq;
-            }
-        }
+        select_from(E, n, L, dst, sh, pool);
+    } else if (total >= n && total <= c.list_row) {
+        const ListEntries E{list, total};
+        select_from(E, n, L, dst, sh, pool);
     } else {
-        select2_slow(c, n, total, fetch, dst, sh, pool);
+        // too few candidates reached the threshold, or too many for the list: rank the row
+        float *sel = p.sel + row * c.sel_stride;
+        switch (__builtin_popcount(p.rmask[g] & ((1u << c.group) - 1u))) {
+        case 1: score_row_unit<1>(c, p, b, g, L, sel); break;
+        case 2: score_row_unit<2>(c, p, b, g, L, sel); break;
+        case 3: score_row_unit<3>(c, p, b, g, L, sel); break;
+        default: score_row_unit<4>(c, p, b, g, L, sel); break;
+        }
+        __threadfence();
+        __syncthreads();  // the scores are read back by other threads of the workgroup
+        const RowEntries E{sel, L};
+        select_from(E, n, L, dst, sh, pool);
     }
     for (int i = n + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
 }
@@ -964,7 +1043,8 @@ __device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
     return lo;
 }
 
-__global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan P)
+// Launches that carry T, S and C units: unit j runs on workgroup j mod W.
+__global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchPlan P)
 {
     __shared__ SharedUnit su;
     __shared__ SharedPool pool;
@@ -974,18 +1054,18 @@ __global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan
     const int W = c.n_wg;
     TRACE(0);
 
-    // ---- small units.  Kinds in a fixed order (S2 on retrieval groups, C, S1, S2 set
-    // copies); within a kind layer by layer; unit j runs on workgroup j mod W.
-    if (P.s2_count + P.c_count + P.s1_count > 0) {
+    // Kinds in a fixed order (S on retrieval groups, C, T, S set copies); within a kind layer
+    // by layer.
+    {
         uint32_t cnt[4] = {0, 0, 0, 0};
         const int t = threadIdx.x;
-        if (t < P.s2_count) {
-            const LayerDesc &L = layers[P.s2_first + t];
+        if (t < P.s_count) {
+            const LayerDesc &L = layers[P.s_first + t];
             cnt[0] = (uint32_t)(c.batch * L.n_rgroups);
             cnt[3] = L.copy_keep ? (uint32_t)(c.batch * (c.n_kv_heads - L.n_rgroups)) : 0u;
         }
         if (t < P.c_count) cnt[1] = (uint32_t)(c.batch * c.n_q_heads);
-        if (t < P.s1_count) cnt[2] = (uint32_t)(c.batch * layers[P.s1_first + t].n_rgroups * c.n_slices);
+        if (t < P.t_count) cnt[2] = (uint32_t)(c.batch * layers[P.t_first + t].n_rgroups);
         uint32_t tot[4];
 #pragma unroll
         for (int kd = 0; kd < 4; ++kd) {
@@ -998,38 +1078,56 @@ __global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan
         for (int j = w; j < n_small; j += W) {
             int u = j;
             if (u < (int)tot[0]) {
-                const int li = find_item(pool.upre[0], P.s2_count, u);
-                const LayerDesc &L = layers[P.s2_first + li];
+                const int li = find_item(pool.upre[0], P.s_count, u);
+                const LayerDesc &L = layers[P.s_first + li];
                 u -= pool.upre[0][li];
                 const int b = u / L.n_rgroups;
-                select2_unit(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
+                select_unit(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
             } else if ((u -= (int)tot[0]) < (int)tot[1]) {
                 const int li = u / (c.batch * c.n_q_heads);
                 combine_unit(c, layers[P.c_first + li], u % (c.batch * c.n_q_heads), su.comb, pool);
             } else if ((u -= (int)tot[1]) < (int)tot[2]) {
-                const int li = find_item(pool.upre[2], P.s1_count, u);
-                const LayerDesc &L = layers[P.s1_first + li];
+                const int li = find_item(pool.upre[2], P.t_count, u);
+                const LayerDesc &L = layers[P.t_first + li];
                 u -= pool.upre[2][li];
-                const int slice = u % c.n_slices;
-                const int rgi = (u / c.n_slices) % L.n_rgroups;
-                const int b = u / (c.n_slices * L.n_rgroups);
-                select1_unit(c, L, b, rgi, slice, su.sel, pool);
+                const int rgi = u % L.n_rgroups;
+                const int b = u / L.n_rgroups;
+                switch (__builtin_popcount(L.rmask[L.rgroup[rgi]] & ((1u << c.group) - 1u))) {
+                case 1: threshold_unit<1>(c, L, b, rgi, su.sel, pool); break;
+                case 2: threshold_unit<2>(c, L, b, rgi, su.sel, pool); break;
+                case 3: threshold_unit<3>(c, L, b, rgi, su.sel, pool); break;
+                default: threshold_unit<4>(c, L, b, rgi, su.sel, pool); break;
+                }
             } else {  // copy of the set of a KV head whose group holds no retrieval head
                 u -= (int)tot[2];
-                const int li = find_item(pool.upre[3], P.s2_count, u);
-                const LayerDesc &L = layers[P.s2_first + li];
+                const int li = find_item(pool.upre[3], P.s_count, u);
+                const LayerDesc &L = layers[P.s_first + li];
                 u -= pool.upre[3][li];
                 const int n_keep = c.n_kv_heads - L.n_rgroups;
                 const int b = u / n_keep;
                 int want = u % n_keep, g = 0;
                 for (int gg = 0; gg < c.n_kv_heads; ++gg)
                     if (L.rindex[gg] == 0xFF && want-- == 0) g = gg;
-                select2_unit(c, L, b, g, su.sel, pool);
+                select_unit(c, L, b, g, su.sel, pool);
             }
             __syncthreads();
         }
     }
     TRACE(1);
+}
+
+// Launches that carry pooled R and G rows.  Two workgroups per CU must fit (the static shares
+// assume that every workgroup runs from the start): at most 256 registers per lane.
+template <bool HAS_R, bool HAS_G>
+__global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPlan P)
+{
+    __shared__ SharedAttn sa;
+    __shared__ SharedPool pool;
+    const Common &c = P.c;
+    const LayerDesc *layers = P.layers;
+    const int w = blockIdx.x;
+    const int W = c.n_wg;
+    TRACE(0);
     const int n_items = (P.r_count + P.g_count) * c.batch;
     if (n_items == 0) return;
 
@@ -1099,7 +1197,7 @@ __global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan
             const int it = find_item(pool.ipre, n_items, x);
             const int li = it / c.batch;
             const int b = it % c.batch;
-            const bool gather = li >= P.r_count;
+            const bool gather = HAS_G && (!HAS_R || li >= P.r_count);
             const LayerDesc &L = gather ? layers[P.g_first + li - P.r_count] : layers[P.r_first + li];
             const int len_b = pool.len[b];
             const int seg_rows = gather ? (c.k < len_b ? c.k : len_b) : len_b;
@@ -1120,17 +1218,25 @@ __global__ __launch_bounds__(kThreads) void lychee_units_kernel(const LaunchPlan
             if (!gather) {
                 const int g = L.rgroup[gi];
                 const uint32_t hmask = L.rmask[g] & gmask;
-                float *sel_row = L.emit_sel ? L.sel + ((int64_t)b * L.n_rgroups + gi) * c.sel_stride : nullptr;
-                dispatch_piece<false>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, nullptr, sel_row,
+                Emit em{nullptr, nullptr, 0u, 0};
+                if (L.emit_sel) {
+                    const int64_t row = (int64_t)b * L.n_rgroups + gi;
+                    em.list = L.list + row * c.list_row;
+                    em.count = L.list_count + row;
+                    em.thr = gload(L.thr + row);
+                    em.cap = c.list_row;
+                }
+                dispatch_piece<false>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, nullptr, em,
                                       L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
-                                      su.attn);
+                                      sa);
             } else {
                 const int g = L.sgroup[gi];
                 const uint32_t hmask = ~(uint32_t)L.rmask[g] & gmask;
                 const int32_t *idx_src = L.idx_src[g] + ((int64_t)b * c.n_kv_heads + g) * c.k;
-                dispatch_piece<true>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, idx_src, nullptr,
+                dispatch_piece<true>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, idx_src,
+                                     Emit{nullptr, nullptr, 0u, 0},
                                      L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
-                                     su.attn);
+                                     sa);
             }
             x += len;
             TRACE(3);
@@ -1213,7 +1319,18 @@ extern "C" int lychee_trace_read(unsigned long long *host, int n_wg)
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
 {
     if (plan.c.n_wg < 1 || plan.c.n_wg > kMaxWg) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(lychee_units_kernel, dim3(plan.c.n_wg), dim3(kThreads), 0, stream, plan);
+    const bool pooled = plan.r_count + plan.g_count > 0;
+    const bool small = plan.t_count + plan.s_count + plan.c_count > 0;
+    if (pooled == small) return hipErrorInvalidValue;  // a launch carries one family of units
+    const dim3 grid(plan.c.n_wg), block(kThreads);
+    if (small)
+        hipLaunchKernelGGL(lychee_small_kernel, grid, block, 0, stream, plan);
+    else if (plan.g_count == 0)
+        hipLaunchKernelGGL((lychee_pool_kernel<true, false>), grid, block, 0, stream, plan);
+    else if (plan.r_count == 0)
+        hipLaunchKernelGGL((lychee_pool_kernel<false, true>), grid, block, 0, stream, plan);
+    else
+        hipLaunchKernelGGL((lychee_pool_kernel<true, true>), grid, block, 0, stream, plan);
     return hipGetLastError();
 }
 

@@ -448,3 +448,38 @@ def test_dense_decode_step(ctx, mode):
     for l, ly in enumerate(layers):
         ref = lo.dense_attn(wl.bf16_bits(ly.q), wl.bf16_bits(ly.k_cache), wl.bf16_bits(ly.v_cache), lens_h)
         H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), ref, "dense step layer %d" % l)
+
+
+# ------------------------------------------------------------------ every route of the select
+@pytest.mark.parametrize("margin,route", [(60, "candidates in registers"),
+                                          (1250, "candidates read from memory"),
+                                          (-1000, "too few candidates: whole row ranked"),
+                                          (100000, "list overflow: whole row ranked")])
+def test_select_routes_give_the_same_sets(ctx, margin, route):
+    """The sampled threshold only decides how the exact top-k is computed, never its result:
+    the margin option drives the select through each of its routes."""
+    lb = H.binding()
+    w = wl.scaled(wl.WORKLOADS["c1"], max_len=40000, k=500, planted=16)
+    inp = wl.make_layer(w, l_cap=40000)
+    _, _, sel0 = H.oracle_layer(inp, np.ones(w.n_q_heads, np.uint8), w.k, None)
+    src = np.zeros((1, w.n_kv_heads, 8), np.int64)
+    for g in range(w.n_kv_heads):
+        order = np.argsort(-sel0[0, g, :40000], kind="stable")
+        src[0, g] = order[w.k - 4:w.k + 4]     # duplicates of rows around the k-th score
+    wl.plant_ties(inp, 3000, src)
+    _say("select route: %s (margin %d)" % (route, margin))
+    ctx.set_option(lb.OPT_SELECT_MARGIN, margin)
+    try:
+        H.check_layer(ctx, inp, np.ones(w.n_q_heads, np.uint8), w.k, None, route, exact_sets=True)
+        H.check_layer(ctx, inp, inp.mask, w.k, H.previous_layer_sets(inp, w.k), route, exact_sets=True)
+    finally:
+        ctx.set_option(lb.OPT_SELECT_MARGIN, 60)
+
+
+def test_sequence_longer_than_one_bitmap_window(ctx):
+    """The ordered write marks positions in windows of 131072: a longer sequence needs two."""
+    w = wl.scaled(wl.WORKLOADS["c1"], n_q_heads=2, n_kv_heads=1, max_len=150000, k=700, planted=32)
+    inp = wl.make_layer(w, l_cap=150000, mask=np.ones(2, np.uint8))
+    _say("two bitmap windows: L 150000")
+    _, _, idx_gpu, _, _, _ = H.check_layer(ctx, inp, np.ones(2, np.uint8), w.k, None, "two windows")
+    assert (idx_gpu[0, 0] >= 131072).any() and (idx_gpu[0, 0][:10] < 131072).all()
