@@ -154,11 +154,12 @@ def main() -> int:
     del copy_dst
 
     # ---- algorithmic bytes ---------------------------------------------------------------
-    # per step: every K+V row streamed or gathered (512 B), the fp32 selection score written
-    # and read once per streamed row, the index sets, q and out
+    # per step: every K+V row streamed or gathered (512 B), the index sets, q and out.  Not
+    # counted, although the library moves them: the threshold sample's K rows (256 B each,
+    # 2048 per score row) and the candidate lists (8 B per candidate, written and read once)
     step_bytes = sum(wl.algorithmic_bytes(w, masks[l], lens_h) for l in range(n_layers))
     dense_bytes = n_layers * wl.dense_bytes(w, lens_h)
-    # per streaming launch: 512 B of K+V and 4 B of score per streamed row, plus q
+    # per streaming launch: 512 B of K+V per streamed row, plus q
     G = w.group
     rows_streamed = 0
     rows_gathered = 0
@@ -169,9 +170,9 @@ def main() -> int:
         rows_gathered += sum(n_s * min(w.k, int(L)) for L in lens_h)
     n_stream_launches = max(1, launches_per_step["stream"])
     if args.layerwise:          # the streaming launch of a layer also carries its gathers
-        stream_bytes = (rows_streamed + rows_gathered) * 512 + rows_streamed * 4
+        stream_bytes = (rows_streamed + rows_gathered) * 512
     else:
-        stream_bytes = rows_streamed * (512 + 4)
+        stream_bytes = rows_streamed * 512
     stream_bytes = (stream_bytes + n_layers * w.batch * w.n_q_heads * 256) / n_stream_launches
     achieved = stream_bytes / (stream_us * 1e-6) / 1e9 if stream_us > 0 else 0.0
     traffic = measured_traffic() if (args.workload == "c3" and not args.layerwise and not args.layers) else None

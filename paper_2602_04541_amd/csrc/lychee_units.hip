@@ -456,13 +456,13 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
 // One (workgroup, segment) piece: rows/entries [r0, r1) of segment (b, g) for the heads in
 // hmask.  Leaves one un-normalised partial per head in `slot`; the piece that ends the
 // segment also records how many slots the segment has.
-template <int NH, bool GATHER>
+template <int NH, bool GATHER, typename Hook>
 __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, const uint16_t *k_cache,
                                           const uint16_t *v_cache, const int32_t *idx_src,
                                           const Emit &em, float *part_o, float *part_ml,
                                           int32_t *part_count, int b, int g, uint32_t hmask, int L,
                                           int r0, int r1, int slot, bool ends_segment,
-                                          SharedAttn &sh)
+                                          SharedAttn &sh, Hook &at_rows_done)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -509,6 +509,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     }
 
     TRACE(7);
+    at_rows_done();  // what the caller wants in flight while the partial is merged and written
     // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).
     const float c_log2e = c.scale_log2e;
 #pragma unroll
@@ -569,19 +570,19 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     }
 }
 
-template <bool GATHER>
+template <bool GATHER, typename Hook>
 __device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const uint16_t *q,
                                                const uint16_t *k_cache, const uint16_t *v_cache,
                                                const int32_t *idx_src, const Emit &em, float *part_o,
                                                float *part_ml, int32_t *part_count, int b, int g,
                                                uint32_t hmask, int L, int r0, int r1, int slot,
-                                               bool ends_segment, SharedAttn &sh)
+                                               bool ends_segment, SharedAttn &sh, Hook &at_rows_done)
 {
     switch (nh) {
-    case 1: run_piece<1, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
-    case 2: run_piece<2, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
-    case 3: run_piece<3, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
-    default: run_piece<4, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh); break;
+    case 1: run_piece<1, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    case 2: run_piece<2, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    case 3: run_piece<3, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    default: run_piece<4, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
     }
 }
 
@@ -1031,7 +1032,28 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     for (int i = n + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
 }
 
-// ------------------------------------------------------------------------------ the kernel
+// ------------------------------------------------------------------------------ the kernels
+// Fields of a layer descriptor staged in LDS as 32-bit words.  The values are the same in
+// every lane; reading them back through readfirstlane tells the compiler so (scalar registers,
+// scalar address arithmetic in the streaming loop).
+constexpr int kDescWords = (int)(sizeof(LayerDesc) / 4);
+static_assert(sizeof(LayerDesc) % 4 == 0 && kDescWords <= kThreads, "one word per thread");
+
+__device__ __forceinline__ uint32_t desc_u32(const uint32_t *dw, size_t off)
+{
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)dw[off / 4]);
+}
+__device__ __forceinline__ uint32_t desc_u8(const uint32_t *dw, size_t off)
+{
+    return (desc_u32(dw, off & ~(size_t)3) >> (8 * (off & 3))) & 0xFFu;
+}
+template <typename T>
+__device__ __forceinline__ T *desc_ptr(const uint32_t *dw, size_t off)
+{
+    const uint64_t lo = desc_u32(dw, off), hi = desc_u32(dw, off + 4);
+    return reinterpret_cast<T *>(lo | (hi << 32));
+}
+
 // Largest i in [0, n) with pre[i] <= x, for a non-decreasing pre[0..n] with pre[0] <= x < pre[n].
 __device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
 {
@@ -1123,6 +1145,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
 {
     __shared__ SharedAttn sa;
     __shared__ SharedPool pool;
+    __shared__ uint32_t desc_s[2][kDescWords];
     const Common &c = P.c;
     const LayerDesc *layers = P.layers;
     const int w = blockIdx.x;
@@ -1189,6 +1212,19 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
     }
     TRACE(2);
 
+    // A piece needs its layer's descriptor before it can issue its first load.  Read through
+    // the table pointer that is a chain of dependent loads; instead the descriptor is staged
+    // in LDS, and the one for the piece after this one is fetched while this piece's partial is
+    // merged and written, so that a piece starts with LDS reads only.
+    auto layer_of_block = [&](int blk) {
+        const int li = find_item(pool.ipre, n_items, blk) / c.batch;
+        return HAS_G && (!HAS_R || li >= P.r_count) ? P.g_first + li - P.r_count : P.r_first + li;
+    };
+    auto fetch_desc = [&](int layer) {
+        return threadIdx.x < kDescWords ? gload(reinterpret_cast<const uint32_t *>(layers + layer) + threadIdx.x) : 0u;
+    };
+    int cur = 0, held[2] = {-1, -1};  // which layer's descriptor each LDS buffer holds
+
     int item = w;
     int x = w * share;
     int x1 = x + share;
@@ -1198,7 +1234,19 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             const int li = it / c.batch;
             const int b = it % c.batch;
             const bool gather = HAS_G && (!HAS_R || li >= P.r_count);
-            const LayerDesc &L = gather ? layers[P.g_first + li - P.r_count] : layers[P.r_first + li];
+            const int layer = gather ? P.g_first + li - P.r_count : P.r_first + li;
+            __syncthreads();  // a descriptor stashed after the previous piece is visible
+            if (held[cur] != layer) {
+                if (held[cur ^ 1] == layer) {
+                    cur ^= 1;
+                } else {
+                    const uint32_t v = fetch_desc(layer);
+                    if (threadIdx.x < kDescWords) desc_s[cur][threadIdx.x] = v;
+                    held[cur] = layer;
+                    __syncthreads();
+                }
+            }
+            const uint32_t *dw = desc_s[cur];
             const int len_b = pool.len[b];
             const int seg_rows = gather ? (c.k < len_b ? c.k : len_b) : len_b;
             const int brows = gather ? c.g_block_rows : kBlockRows;
@@ -1215,28 +1263,60 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             const int slot = item - item_of(seg_start);
             const bool ends = blk + len == nb;
             const uint32_t gmask = (1u << c.group) - 1u;
+
+            // where the next piece starts decides which descriptor to fetch meanwhile
+            const bool run_ends = x + len >= x1;
+            uint32_t ahead = 0;
+            int ahead_layer = -1;
+            auto at_rows_done = [&]() {
+                int xn = x + len;
+                if (run_ends) {  // the next piece is the chunk whose ticket is already here
+                    __syncthreads();
+                    if (threadIdx.x == 0) pool.scan[0] = next_ticket;
+                    __syncthreads();
+                    const int ticket = (int)pool.scan[0];
+                    xn = ticket < n_chunks ? T_static + ticket * chunk : -1;
+                }
+                if (xn >= 0) {
+                    const int ln = layer_of_block(xn);
+                    if (ln != layer) {
+                        ahead = fetch_desc(ln);
+                        ahead_layer = ln;
+                    }
+                }
+            };
+
+            const uint16_t *dq = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, q));
+            const uint16_t *dk = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, k_cache));
+            const uint16_t *dv = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, v_cache));
+            float *d_part_o = desc_ptr<float>(dw, offsetof(LayerDesc, part_o));
+            float *d_part_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_ml));
+            int32_t *d_part_count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, part_count));
             if (!gather) {
-                const int g = L.rgroup[gi];
-                const uint32_t hmask = L.rmask[g] & gmask;
+                const int g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
+                const uint32_t hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
                 Emit em{nullptr, nullptr, 0u, 0};
-                if (L.emit_sel) {
-                    const int64_t row = (int64_t)b * L.n_rgroups + gi;
-                    em.list = L.list + row * c.list_row;
-                    em.count = L.list_count + row;
-                    em.thr = gload(L.thr + row);
+                if (desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
+                    const int64_t row = (int64_t)b * (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) + gi;
+                    em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
+                    em.count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, list_count)) + row;
+                    em.thr = gload(desc_ptr<uint32_t>(dw, offsetof(LayerDesc, thr)) + row);
                     em.cap = c.list_row;
                 }
-                dispatch_piece<false>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, nullptr, em,
-                                      L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
-                                      sa);
+                dispatch_piece<false>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
+                                      d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa, at_rows_done);
             } else {
-                const int g = L.sgroup[gi];
-                const uint32_t hmask = ~(uint32_t)L.rmask[g] & gmask;
-                const int32_t *idx_src = L.idx_src[g] + ((int64_t)b * c.n_kv_heads + g) * c.k;
-                dispatch_piece<true>(__builtin_popcount(hmask), c, L.q, L.k_cache, L.v_cache, idx_src,
-                                     Emit{nullptr, nullptr, 0u, 0},
-                                     L.part_o, L.part_ml, L.part_count, b, g, hmask, len_b, r0, r1, slot, ends,
-                                     sa);
+                const int g = (int)desc_u8(dw, offsetof(LayerDesc, sgroup) + gi);
+                const uint32_t hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
+                const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)g) +
+                                         ((int64_t)b * c.n_kv_heads + g) * c.k;
+                dispatch_piece<true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{nullptr, nullptr, 0u, 0},
+                                     d_part_o, d_part_ml, d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa,
+                                     at_rows_done);
+            }
+            if (ahead_layer >= 0) {  // wave-uniform; readers of this buffer finished a piece ago
+                if (threadIdx.x < kDescWords) desc_s[cur ^ 1][threadIdx.x] = ahead;
+                held[cur ^ 1] = ahead_layer;
             }
             x += len;
             TRACE(3);

@@ -229,10 +229,12 @@ def bf16_bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def algorithmic_bytes(w: Workload, mask: np.ndarray, lens: np.ndarray) -> int:
+def algorithmic_bytes(w: Workload, mask: np.ndarray, lens: np.ndarray, score_bytes: int = 0) -> int:
     """HBM bytes one hybrid layer call must move: K+V rows streamed for groups holding a
-    retrieval head, K+V rows gathered for groups holding a sparse head, the fp32
-    selection scores (written once, read once), the index sets and q / out."""
+    retrieval head, K+V rows gathered for groups holding a sparse head, the index sets and
+    q / out.  `score_bytes` adds that many bytes per streamed row for an implementation that
+    materialises the selection scores (8 = fp32 written once and read once); the library
+    does not, so its figures use 0."""
     G, Hkv, d = w.group, w.n_kv_heads, HEAD_DIM
     row = 2 * d * 2
     n_r = sum(1 for g in range(Hkv) if mask[g * G:(g + 1) * G].any())
@@ -240,7 +242,7 @@ def algorithmic_bytes(w: Workload, mask: np.ndarray, lens: np.ndarray) -> int:
     total = 0
     for L in lens:
         L = int(L)
-        total += n_r * L * row + n_s * min(w.k, L) * row + n_r * L * 4 * 2
+        total += n_r * L * row + n_s * min(w.k, L) * row + n_r * L * score_bytes
         total += Hkv * w.k * 4 * 2
     total += w.batch * w.n_q_heads * d * 2 * 2
     return total
