@@ -25,7 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "lychee_units_kernel_c3_stream_pmc.txt")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "lychee_pool_kernel_c3_stream_pmc.txt")
 
 
 def measured_traffic():
@@ -205,7 +205,7 @@ def main() -> int:
         "paper_context": "paper reports up to 2.7x end-to-end TPOT speed-up over full attention at "
                          "128K, batch 1, budget 4096 (Sec. 4.3.1; GPU of that run not stated, kernel "
                          "study on one NVIDIA A800)",
-        "roofline": {"bound": "hbm", "kernel": "lychee_units_kernel (streaming launch)",
+        "roofline": {"bound": "hbm", "kernel": "lychee_pool_kernel<true, false, true> (the streaming launch of the phased step)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "avg_launch_us": round(stream_us, 2),

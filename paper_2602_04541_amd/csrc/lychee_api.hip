@@ -243,7 +243,8 @@ struct Launcher {
     const lychee_shape &s;
     const Workspace &w;
     const int32_t *lengths;
-    const LayerDesc *table;
+    const LayerDesc *table;       // in device memory
+    const LayerDesc *host_table;  // the same descriptors on the host
     hipStream_t stream;
 
     int grid() const
@@ -299,6 +300,8 @@ struct Launcher {
         p.c_first = r.c_first, p.c_count = r.c_count;
         p.t_first = r.t_first, p.t_count = r.t_count;
         p.s_first = r.s_first, p.s_count = r.s_count;
+        for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.collect |= host_table[l].emit_sel;
+        for (int l = r.s_first; l < r.s_first + r.s_count; ++l) p.selects |= host_table[l].n_rgroups > 0;
         const int cls = r.r_count ? LYCHEE_KERNEL_STREAM : r.g_count ? LYCHEE_KERNEL_GATHER
                         : r.t_count ? LYCHEE_KERNEL_THRESHOLD : r.c_count ? LYCHEE_KERNEL_COMBINE
                         : LYCHEE_KERNEL_SELECT;
@@ -432,7 +435,7 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
     d.copy_keep = 1;
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, stream};
+    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     return run_layer(L, 0, true);
 }
 
@@ -462,7 +465,7 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
     set_scratch(d, w, static_cast<char *>(workspace), 0);
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, stream};
+    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     return run_layer(L, 0, false);
 }
 
@@ -535,7 +538,7 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
 
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, stream};
+    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
 
     const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && (int64_t)n_layers * shape->batch <= kMaxItems;
     if (!phased) {
@@ -603,7 +606,7 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
     }
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, stream};
+    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     if (ctx->step_mode != LYCHEE_STEP_PHASED || (int64_t)n_layers * shape->batch > kMaxItems) {
         for (int l = 0; l < n_layers; ++l)
             if ((rc = run_layer(L, l, false)) != LYCHEE_OK) return rc;

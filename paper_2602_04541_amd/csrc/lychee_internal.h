@@ -84,6 +84,8 @@ struct LaunchPlan {
     int32_t c_first, c_count;    // combine
     int32_t t_first, t_count;    // selection thresholds
     int32_t s_first, s_count;    // select (and set copies)
+    int32_t collect;             // some R layer of the launch collects selection candidates
+    int32_t selects;             // some S layer of the launch has a retrieval group to select for
 };
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream);

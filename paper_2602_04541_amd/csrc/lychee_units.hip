@@ -985,18 +985,24 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
     }
 }
 
-// S unit of KV head (b, g): the set the next layer's sparse heads of the group inherit.
+// The set of a KV head (b, g) whose group holds no retrieval head is handed on unchanged
+// (Sec. 3.1): a verbatim copy.
+__device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &p, int b, int g)
+{
+    const int64_t bg = (int64_t)b * c.n_kv_heads + g;
+    int32_t *dst = p.idx_out + bg * c.k;
+    const int32_t *src = p.idx_src[g] + bg * c.k;
+    for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, gload(src + i));
+}
+
+// S unit of KV head (b, g), whose group holds a retrieval head: the set the next layer's
+// sparse heads of the group inherit.
 __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p, int b, int g,
                                             SharedSelect &sh, SharedPool &pool)
 {
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
     const int rgi = p.rindex[g];
-    if (rgi == 0xFF) {  // no retrieval head in the group: the set is handed on unchanged
-        const int32_t *src = p.idx_src[g] + bg * c.k;
-        for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, gload(src + i));
-        return;
-    }
     const int L = clamp_len(c.lengths[b], c.max_len);
     const int n = c.k < L ? c.k : L;
     if (n == L) {  // everything is selected
@@ -1065,7 +1071,10 @@ __device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
     return lo;
 }
 
-// Launches that carry T, S and C units: unit j runs on workgroup j mod W.
+// Launches that carry T, S and C units: unit j runs on workgroup j mod W.  SELECTS = false
+// is the lighter build for launches without S units on retrieval groups (their candidates held
+// in registers set this kernel's register budget, and spill code with it).
+template <bool SELECTS>
 __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchPlan P)
 {
     __shared__ SharedUnit su;
@@ -1104,7 +1113,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
                 const LayerDesc &L = layers[P.s_first + li];
                 u -= pool.upre[0][li];
                 const int b = u / L.n_rgroups;
-                select_unit(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
+                if (SELECTS) select_unit(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
             } else if ((u -= (int)tot[0]) < (int)tot[1]) {
                 const int li = u / (c.batch * c.n_q_heads);
                 combine_unit(c, layers[P.c_first + li], u % (c.batch * c.n_q_heads), su.comb, pool);
@@ -1130,7 +1139,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
                 int want = u % n_keep, g = 0;
                 for (int gg = 0; gg < c.n_kv_heads; ++gg)
                     if (L.rindex[gg] == 0xFF && want-- == 0) g = gg;
-                select_unit(c, L, b, g, su.sel, pool);
+                copy_set_unit(c, L, b, g);
             }
             __syncthreads();
         }
@@ -1140,7 +1149,8 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
 
 // Launches that carry pooled R and G rows.  Two workgroups per CU must fit (the static shares
 // assume that every workgroup runs from the start): at most 256 registers per lane.
-template <bool HAS_R, bool HAS_G>
+// COLLECT = false is the dense baseline's streaming: no layer selects anything.
+template <bool HAS_R, bool HAS_G, bool COLLECT>
 __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPlan P)
 {
     __shared__ SharedAttn sa;
@@ -1296,7 +1306,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                 const int g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
                 const uint32_t hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
                 Emit em{nullptr, nullptr, 0u, 0};
-                if (desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
+                if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
                     const int64_t row = (int64_t)b * (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) + gi;
                     em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
                     em.count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, list_count)) + row;
@@ -1403,14 +1413,20 @@ hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
     const bool small = plan.t_count + plan.s_count + plan.c_count > 0;
     if (pooled == small) return hipErrorInvalidValue;  // a launch carries one family of units
     const dim3 grid(plan.c.n_wg), block(kThreads);
-    if (small)
-        hipLaunchKernelGGL(lychee_small_kernel, grid, block, 0, stream, plan);
-    else if (plan.g_count == 0)
-        hipLaunchKernelGGL((lychee_pool_kernel<true, false>), grid, block, 0, stream, plan);
+    if (small && plan.selects)
+        hipLaunchKernelGGL((lychee_small_kernel<true>), grid, block, 0, stream, plan);
+    else if (small)
+        hipLaunchKernelGGL((lychee_small_kernel<false>), grid, block, 0, stream, plan);
     else if (plan.r_count == 0)
-        hipLaunchKernelGGL((lychee_pool_kernel<false, true>), grid, block, 0, stream, plan);
+        hipLaunchKernelGGL((lychee_pool_kernel<false, true, false>), grid, block, 0, stream, plan);
+    else if (plan.g_count == 0 && plan.collect)
+        hipLaunchKernelGGL((lychee_pool_kernel<true, false, true>), grid, block, 0, stream, plan);
+    else if (plan.g_count == 0)
+        hipLaunchKernelGGL((lychee_pool_kernel<true, false, false>), grid, block, 0, stream, plan);
+    else if (plan.collect)
+        hipLaunchKernelGGL((lychee_pool_kernel<true, true, true>), grid, block, 0, stream, plan);
     else
-        hipLaunchKernelGGL((lychee_pool_kernel<true, true>), grid, block, 0, stream, plan);
+        hipLaunchKernelGGL((lychee_pool_kernel<true, true, false>), grid, block, 0, stream, plan);
     return hipGetLastError();
 }
 
