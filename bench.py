@@ -46,6 +46,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
+    ap.add_argument("--k", type=int, default=0, help="override the budget (the c5 sweep)")
+    ap.add_argument("--retrieval", type=int, default=0, help="override the retrieval heads per layer (the c5 sweep)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--tail", type=int, default=-1)
     ap.add_argument("--gather-block", type=int, default=0)
@@ -66,6 +68,10 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     w = wl.WORKLOADS[args.workload]
+    if args.k:
+        w = wl.scaled(w, k=args.k)
+    if args.retrieval:
+        w = wl.scaled(w, n_retrieval=args.retrieval)
     n_layers = args.layers or w.n_layers
     ctx = lb.Context(0)
     if args.wg_per_cu:
@@ -175,7 +181,8 @@ def main() -> int:
         stream_bytes = rows_streamed * 512
     stream_bytes = (stream_bytes + n_layers * w.batch * w.n_q_heads * 256) / n_stream_launches
     achieved = stream_bytes / (stream_us * 1e-6) / 1e9 if stream_us > 0 else 0.0
-    traffic = measured_traffic() if (args.workload == "c3" and not args.layerwise and not args.layers) else None
+    default_run = args.workload == "c3" and not (args.layerwise or args.layers or args.k or args.retrieval)
+    traffic = measured_traffic() if default_run else None
 
     result = {
         "metric": "us per decode-step attention (all layers) at 128K",

@@ -826,7 +826,12 @@ __device__ __forceinline__ void score_row_unit(const Common &c, const LayerDesc 
     }
 }
 
-// The three sources of (ordered key, position) entries the select unit ranks.
+// The three sources of (ordered key, position) entries the select unit ranks.  for_each may
+// also hand out "no entry" (position kNoEntry).  The visitors below fold everything that
+// decides whether an entry counts into one flag, with bitwise operators, and guard a single
+// LDS operation with it: short-circuit conditions made the compiler keep a lane mask per entry
+// and condition, spill them, and branch several times per entry.
+constexpr uint32_t kNoEntry = 0xFFFFFFFFu;
 constexpr int kSelRegs = 40;  // entries one thread keeps in registers
 struct RegEntries {           // up to kThreads * kSelRegs list entries, loaded once
     uint32_t key[kSelRegs], pos[kSelRegs];
@@ -835,24 +840,16 @@ struct RegEntries {           // up to kThreads * kSelRegs list entries, loaded 
 #pragma unroll
         for (int e = 0; e < kSelRegs; ++e) {
             const int i = threadIdx.x + e * kThreads;
-            key[e] = 0;
-            pos[e] = 0xFFFFFFFFu;  // marks "no entry"
-            if (i < total) {
-                const unsigned long long v = gload(list + i);
-                key[e] = (uint32_t)v;
-                pos[e] = (uint32_t)(v >> 32);
-            }
+            const unsigned long long v = gload(list + (i < total ? i : 0));  // total >= 1
+            key[e] = (uint32_t)v;
+            pos[e] = i < total ? (uint32_t)(v >> 32) : kNoEntry;
         }
     }
     template <typename F>
     __device__ __forceinline__ void for_each(F f) const
     {
 #pragma unroll
-        for (int e = 0; e < kSelRegs; ++e) {
-            if (pos[e] != 0xFFFFFFFFu) f(key[e], pos[e]);
-            // one entry after the other: interleaving all 40 costs more registers than there are
-            if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-        }
+        for (int e = 0; e < kSelRegs; ++e) f(key[e], pos[e]);
     }
 };
 struct ListEntries {          // a longer list, read from memory on every pass
@@ -870,7 +867,7 @@ struct ListEntries {          // a longer list, read from memory on every pass
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (i0 + u * kThreads < total) f((uint32_t)v[u], (uint32_t)(v[u] >> 32));
+                f((uint32_t)v[u], i0 + u * kThreads < total ? (uint32_t)(v[u] >> 32) : kNoEntry);
         }
     }
 };
@@ -888,8 +885,10 @@ struct RowEntries {           // every row of the sequence, from its recomputed 
                 v[u] = gload(sel + (i < total ? i : total - 1));
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (i0 + u * kThreads < total) f(ordered_key(v[u]), (uint32_t)(i0 + u * kThreads));
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                f(ordered_key(v[u]), i < total ? (uint32_t)i : kNoEntry);
+            }
         }
     }
 };
@@ -911,7 +910,8 @@ __device__ __forceinline__ uint32_t radix_select(const Entries &E, uint32_t need
         __syncthreads();
         E.for_each([&](uint32_t key, uint32_t pos) {
             const uint32_t v = val(key, pos);
-            if (among(key, pos) && (v & prefix_mask) == prefix) atomicAdd(&sh.hist[(v >> shift) & digit_mask], 1u);
+            const bool in = (pos != kNoEntry) & among(key, pos) & ((v & prefix_mask) == prefix);
+            if (in) atomicAdd(&sh.hist[(v >> shift) & digit_mask], 1u);
         });
         __syncthreads();
         uint32_t digit, left;
@@ -941,11 +941,12 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
     const uint32_t T = radix_select(
         E, (uint32_t)n, [](uint32_t key, uint32_t) { return key; }, [](uint32_t, uint32_t) { return true; }, r_eq,
         sh, pool);
+    TRACE(7);
     uint32_t my_eq = 0;
-    E.for_each([&](uint32_t key, uint32_t) { my_eq += (uint32_t)(key == T); });
+    E.for_each([&](uint32_t key, uint32_t pos) { my_eq += (uint32_t)((key == T) & (pos != kNoEntry)); });
     uint32_t n_eq;
     (void)block_scan(my_eq, pool.scan, n_eq);
-    uint32_t pos_cut = 0xFFFFFFFFu;  // entries equal to T are taken up to this position
+    uint32_t pos_cut = 0xFFFFFFFEu;  // entries equal to T are taken up to this position
     if (r_eq < n_eq) {
         uint32_t unused;
         pos_cut = ~radix_select(
@@ -959,10 +960,12 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
         __syncthreads();
         E.for_each([&](uint32_t key, uint32_t pos) {
-            const uint32_t rel = pos - w0;
-            if ((key > T || (key == T && pos <= pos_cut)) && rel < kWindow) atomicOr(&sh.hist[rel >> 5], 1u << (rel & 31u));
+            const uint32_t rel = pos - w0;  // "no entry" lies outside every window
+            const bool take = ((key > T) | ((key == T) & (pos <= pos_cut))) & (rel < kWindow);
+            if (take) atomicOr(&sh.hist[rel >> 5], 1u << (rel & 31u));
         });
         __syncthreads();
+        TRACE(2);
         uint32_t words[kPer], cnt = 0;
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
@@ -971,6 +974,9 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         }
         uint32_t tot;
         uint32_t at = base + block_scan(cnt, pool.scan, tot) - cnt;
+        TRACE(3);
+        // (handing neighbouring words to neighbouring lanes, for store addresses that share
+        // cache lines, was measured to be slower: the loop below is bound by its divergence)
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
             uint32_t wd = words[j];
@@ -983,6 +989,7 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         }
         base += tot;
     }
+    TRACE(4);
 }
 
 // The set of a KV head (b, g) whose group holds no retrieval head is handed on unchanged
