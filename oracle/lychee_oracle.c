@@ -23,7 +23,11 @@
  *     retrieval head passes its set on unchanged;
  *   - ties are broken towards the lower position; the returned set is ascending by
  *     position and padded with -1 when k exceeds the sequence length;
- *   - lengths count the current token; no sink / window positions are forced.
+ *   - lengths count the current token; no sink / window positions are forced;
+ *   - the Ratio rule of Sec. 4.4.1 keeps a budget proportional to the sequence length;
+ *     App. E.2's sparsity table shows that its theta is the share of tokens dropped, so
+ *     the share kept is 1 - theta.  The oracle takes the kept share in parts per million
+ *     and rounds the budget up (the paper does not say how it rounds).
  *
  * Every function is a direct loop nest: no blocking, no fusion, no reordering.
  * OpenMP only spreads the independent (sequence, KV head) pairs over cores.
@@ -118,9 +122,23 @@ static int by_int_asc(const void *a, const void *b)
     return (x > y) - (x < y);
 }
 
+/* The Ratio rule's budget (Sec. 4.4.1: a budget proportional to the sequence length) for a
+ * sequence of L rows: ceil(L * keep_ppm / 10^6) positions, at least 1, at most L and at most
+ * the capacity k of a set.  keep_ppm = 0 switches the rule off: min(k, L), the Top-k rule. */
+int32_t lo_ratio_budget(int32_t L, int32_t k, int32_t keep_ppm)
+{
+    int64_t n = k < L ? k : L;
+    if (keep_ppm > 0) {
+        int64_t r = ((int64_t)L * keep_ppm + 999999) / 1000000;
+        if (r < 1) r = 1;
+        if (r < n) n = r;
+    }
+    return (int32_t)n;
+}
+
 /* Eq. 2 by brute force: sort every position by (score descending, position ascending),
- * keep the first min(k, L), return them ascending by position, pad with -1 up to k. */
-void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
+ * keep the first min(n, L), return them ascending by position, pad with -1 up to k >= n. */
+void lo_topk_n(const double *sel, int32_t L, int32_t n, int32_t k, int32_t *idx_out)
 {
     scored_pos *all = malloc((size_t)(L > 0 ? L : 1) * sizeof *all);
     for (int32_t t = 0; t < L; ++t) {
@@ -128,11 +146,17 @@ void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
         all[t].t = t;
     }
     qsort(all, (size_t)L, sizeof *all, by_score_desc_then_pos);
-    int32_t n = k < L ? k : L;
+    if (n > L) n = L;
     for (int32_t j = 0; j < n; ++j) idx_out[j] = all[j].t;
     qsort(idx_out, (size_t)n, sizeof *idx_out, by_int_asc);
     for (int32_t j = n; j < k; ++j) idx_out[j] = -1;
     free(all);
+}
+
+/* Eq. 2 with the fixed budget k. */
+void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
+{
+    lo_topk_n(sel, L, k, k, idx_out);
 }
 
 /*
@@ -148,15 +172,18 @@ void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
  *   idx_out    [B][Hkv][k], may be NULL
  *   sel_out    fp64 [B][Hkv][max_len] pooled selection scores of groups that hold a
  *              retrieval head (other groups and t >= L_b: NaN); may be NULL
+ *   keep_ppm   0: Eq. 2's fixed budget k.  > 0: the Ratio rule, lo_ratio_budget() positions
+ *              per sequence, in sets of capacity k
  * Returns 0, or -1 on an argument it cannot serve.
  */
-int lo_decode_attn(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
-                   const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
-                   int64_t stride_h, int64_t stride_t, const uint8_t *mask,
-                   const int32_t *idx_in, const int32_t *lengths, double *out,
-                   int32_t *idx_out, double *sel_out)
+int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
+                        const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
+                        int64_t stride_h, int64_t stride_t, const uint8_t *mask,
+                        const int32_t *idx_in, const int32_t *lengths, double *out,
+                        int32_t *idx_out, double *sel_out, int32_t keep_ppm)
 {
     if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || d < 1 || k < 1) return -1;
+    if (keep_ppm < 0 || keep_ppm > 1000000) return -1;
     const int32_t G = Hq / Hkv;
     int any_sparse = 0;
     for (int32_t h = 0; h < Hq; ++h)
@@ -214,7 +241,7 @@ int lo_decode_attn(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int
             if (idx_out != NULL) {
                 int32_t *dst = idx_out + ((int64_t)b * Hkv + g) * k;
                 if (n_retrieval > 0)
-                    lo_topk(sel, L, k, dst);
+                    lo_topk_n(sel, L, lo_ratio_budget(L, k, keep_ppm), k, dst);
                 else
                     memcpy(dst, idx_in + ((int64_t)b * Hkv + g) * k, (size_t)k * sizeof *dst);
             }
@@ -231,6 +258,17 @@ int lo_decode_attn(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int
         }
     }
     return 0;
+}
+
+/* The same with Eq. 2's fixed budget. */
+int lo_decode_attn(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
+                   const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
+                   int64_t stride_h, int64_t stride_t, const uint8_t *mask,
+                   const int32_t *idx_in, const int32_t *lengths, double *out,
+                   int32_t *idx_out, double *sel_out)
+{
+    return lo_decode_attn_rule(B, Hq, Hkv, d, k, max_len, q, K, V, stride_b, stride_h, stride_t, mask,
+                               idx_in, lengths, out, idx_out, sel_out, 0);
 }
 
 /* Number of threads the (sequence, KV head) loop above spreads over. */

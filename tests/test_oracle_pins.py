@@ -262,3 +262,56 @@ def test_oracle_rejects_bad_arguments():
     with pytest.raises(ValueError):                          # index beyond the length
         lo.decode_attn(q, K, V, np.zeros(4, np.uint8), 2,
                        np.full((1, 2, 2), 7, np.int32), np.array([5], np.int32))
+
+
+# ------------------------------------------------------------------ the Ratio rule (Sec. 4.4.1)
+def test_ratio_budget_is_the_rounded_up_share_clamped_to_the_set_capacity():
+    from fractions import Fraction
+    import math
+    for L in (1, 2, 7, 64, 1000, 4097, 131072):
+        for ppm in (1, 100000, 300000, 333333, 500000, 999999, 1000000):
+            want = max(1, math.ceil(Fraction(L * ppm, 1000000)))     # exact rational arithmetic
+            for k in (1, 5, L, 2 * L):
+                assert lo.ratio_budget(L, k, ppm) == min(want, k, L), (L, ppm, k)
+    # theta = 70 % of the tokens dropped (App. E.2's sparsity table) keeps 30 % of them
+    assert lo.ratio_budget(100000, 10 ** 6, 300000) == 30000
+    assert lo.ratio_budget(10, 4, 0) == 4 and lo.ratio_budget(3, 4, 0) == 3   # rule off: min(k, L)
+
+
+def test_ratio_rule_selects_the_top_share_per_sequence_and_nests():
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, d, cap = 3, 4, 2, 128, 40
+    lens = np.array([37, 80, 5], np.int32)
+    q = round_to_bf16_bits(rng.standard_normal((B, Hq, d)))
+    K = round_to_bf16_bits(rng.standard_normal((B, Hkv, 80, d)))
+    K[:, :, 10] = K[:, :, 3]                       # an exact tie inside every head
+    V = round_to_bf16_bits(rng.standard_normal((B, Hkv, 80, d)))
+    mask = np.ones(Hq, np.uint8)
+    prev = None
+    for ppm in (100000, 250000, 500000, 1000000):
+        out, idx, sel = lo.decode_attn(q, K, V, mask, cap, None, lens, want_sel=True, keep_ppm=ppm)
+        out0, _, _ = lo.decode_attn(q, K, V, mask, cap, None, lens)
+        assert (out == out0).all()                 # the rule changes the sets, not this layer's output
+        for b in range(B):
+            L = int(lens[b])
+            n = min(cap, L, max(1, -(-L * ppm // 1000000)))
+            for g in range(Hkv):
+                order = sorted(range(L), key=lambda t: (-sel[b, g, t], t))      # brute force
+                want = sorted(order[:n])
+                got = idx[b, g]
+                assert list(got[:n]) == want and (got[n:] == -1).all(), (ppm, b, g)
+                if prev is not None:               # a larger share keeps everything a smaller one kept
+                    assert set(prev[b, g][prev[b, g] >= 0]) <= set(got[got >= 0])
+        prev = idx
+
+
+def test_ratio_rule_with_the_share_that_gives_k_equals_topk():
+    rng = np.random.default_rng(12)
+    q = round_to_bf16_bits(rng.standard_normal((1, 2, 128)))
+    K = round_to_bf16_bits(rng.standard_normal((1, 1, 200, 128)))
+    V = round_to_bf16_bits(rng.standard_normal((1, 1, 200, 128)))
+    lens = np.array([200], np.int32)
+    mask = np.ones(2, np.uint8)
+    _, idx_k, _ = lo.decode_attn(q, K, V, mask, 50, None, lens)
+    _, idx_r, _ = lo.decode_attn(q, K, V, mask, 64, None, lens, keep_ppm=250000)   # 25 % of 200 = 50
+    assert (idx_r[0, 0, :50] == idx_k[0, 0]).all() and (idx_r[0, 0, 50:] == -1).all()
