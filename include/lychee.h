@@ -67,9 +67,16 @@ typedef struct lychee_shape {
     int32_t head_dim;    /* must be LYCHEE_HEAD_DIM                                          */
     int32_t max_len;     /* host-known upper bound of lengths[]; sizes grids and workspace,
                             so that no call has to read lengths[] on the host              */
-    int32_t k;           /* token budget of Eq. 2 / Eq. 3, >= 1                              */
+    int32_t k;           /* token budget of Eq. 2 / Eq. 3, >= 1; the capacity of every set      */
     int64_t kv_stride_batch, kv_stride_head, kv_stride_tok; /* elements; each a multiple of 8
                             (16-byte vector loads), kv_stride_tok >= 128                    */
+    int32_t keep_ppm;    /* 0: Eq. 2 selects min(k, L_b) positions.  1 .. 1000000: the Ratio rule
+                            of Sec. 4.4.1, a budget proportional to the sequence length:
+                            min(k, ceil(L_b * keep_ppm / 10^6)) positions, at least 1.  (The
+                            paper's theta is the share of tokens dropped, App. E.2: theta = 70 %
+                            is keep_ppm = 300000.)  Sparse heads attend over whatever valid
+                            entries the inherited set holds, under either rule.               */
+    int32_t reserved;    /* 0 */
 } lychee_shape;
 
 /* Create / destroy a context bound to HIP device `device`.  Needs a GPU. */

@@ -112,6 +112,7 @@ int check_shape(const lychee_shape *s)
     if (s->n_kv_heads > kMaxKvHeads) return LYCHEE_EUNSUPPORTED;
     if (s->n_q_heads / s->n_kv_heads > kMaxGroup) return LYCHEE_EUNSUPPORTED;
     if (s->max_len > (1 << 24) || s->batch > kMaxBatch) return LYCHEE_EUNSUPPORTED;
+    if (s->keep_ppm < 0 || s->keep_ppm > 1000000 || s->reserved != 0) return LYCHEE_EINVAL;
     if (s->kv_stride_tok < kHeadDim || s->kv_stride_batch < 0 || s->kv_stride_head < 0)
         return LYCHEE_EINVAL;
     if (s->kv_stride_tok % 8 || s->kv_stride_head % 8 || s->kv_stride_batch % 8) return LYCHEE_EINVAL;
@@ -277,6 +278,7 @@ struct Launcher {
         c.n_kv_heads = s.n_kv_heads;
         c.group = s.n_q_heads / s.n_kv_heads;
         c.k = s.k;
+        c.keep_ppm = s.keep_ppm;
         c.max_len = s.max_len;
         c.sel_stride = w.sel_stride;
         c.list_row = w.list_row;

@@ -35,6 +35,7 @@ struct Common {
     int64_t stride_b, stride_h, stride_t;
     int32_t batch, n_q_heads, n_kv_heads, group;
     int32_t k, max_len, sel_stride;
+    int32_t keep_ppm;     // > 0: the Ratio rule's share of a sequence, in parts per million
     int32_t list_row;     // capacity, in entries, of one score row's candidate list
     int32_t n_wg;         // grid size of this launch
     int32_t part_stride;  // partial slots per head

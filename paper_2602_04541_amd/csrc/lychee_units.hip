@@ -153,6 +153,20 @@ __device__ __forceinline__ uint32_t ordered_key(float x)
 
 __device__ __forceinline__ int clamp_len(int L, int max_len) { return L < 1 ? 1 : (L > max_len ? max_len : L); }
 
+// Positions selected for a sequence of L rows: Eq. 2's fixed budget, min(k, L), or under the
+// Ratio rule (Sec. 4.4.1: a budget proportional to the sequence length) the rounded-up share
+// keep_ppm / 10^6 of L, at least 1 and at most the fixed budget.
+__device__ __forceinline__ int budget_of(const Common &c, int L)
+{
+    int n = c.k < L ? c.k : L;
+    if (c.keep_ppm > 0) {
+        long long r = ((long long)L * c.keep_ppm + 999999) / 1000000;
+        r = r < 1 ? 1 : r;
+        n = r < n ? (int)r : n;
+    }
+    return n;
+}
+
 // Inclusive prefix sum over the 256 threads of the workgroup; `total` = sum of all.
 __device__ __forceinline__ uint32_t block_scan(uint32_t v, uint32_t *wave_tot, uint32_t &total)
 {
@@ -726,7 +740,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     const int rs = lane >> 4;
     const int ch = lane & 15;
     const int L = clamp_len(c.lengths[b], c.max_len);
-    const int n = c.k < L ? c.k : L;
+    const int n = budget_of(c, L);
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
     if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
@@ -1011,7 +1025,7 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     int32_t *dst = p.idx_out + bg * c.k;
     const int rgi = p.rindex[g];
     const int L = clamp_len(c.lengths[b], c.max_len);
-    const int n = c.k < L ? c.k : L;
+    const int n = budget_of(c, L);
     if (n == L) {  // everything is selected
         for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
         return;

@@ -96,3 +96,13 @@ def test_create_fails_cleanly_without_a_gpu(lb):
     with pytest.raises(lb.LycheeError) as e:
         lb.Context(0)
     assert e.value.code == lb.EHIP
+
+
+def test_ratio_rule_field_is_validated(lb):
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=300000)) == lb.OK
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=1000000)) == lb.OK
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=1000001)) == lb.EINVAL
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=-1)) == lb.EINVAL
+    s = lb.make_shape(1, 8, 2, 4096, 256)
+    s.reserved = 7
+    assert lb.check_shape(s) == lb.EINVAL

@@ -483,3 +483,56 @@ def test_sequence_longer_than_one_bitmap_window(ctx):
     _say("two bitmap windows: L 150000")
     _, _, idx_gpu, _, _, _ = H.check_layer(ctx, inp, np.ones(2, np.uint8), w.k, None, "two windows")
     assert (idx_gpu[0, 0] >= 131072).any() and (idx_gpu[0, 0][:10] < 131072).all()
+
+
+# ------------------------------------------------------------------ the Ratio rule (Sec. 4.4.1)
+@pytest.mark.parametrize("keep_ppm", [300000, 100000, 1000, 1000000])
+def test_ratio_rule_layer_with_ragged_batch(ctx, keep_ppm):
+    """A budget proportional to each sequence's length, in sets of capacity k."""
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=3, max_len=9000, k=3000, planted=16, len_lo=300, len_hi=9000)
+    lens_h = wl.lengths(w)
+    inp = wl.make_layer(w, lens=lens_h, l_cap=9000)
+    _say("ratio rule: keep %d ppm of lengths %s" % (keep_ppm, lens_h.tolist()))
+    mask = np.ones(w.n_q_heads, np.uint8)
+    _, _, idx_gpu, _, _, _ = H.check_layer(ctx, inp, mask, w.k, None, "ratio all-retrieval", keep_ppm=keep_ppm)
+    for b in range(w.batch):
+        want = min(w.k, int(lens_h[b]), max(1, -(-int(lens_h[b]) * keep_ppm // 1000000)))
+        assert ((idx_gpu[b] >= 0).sum(axis=1) == want).all()
+    # a hybrid layer whose sparse heads inherit sets of the same rule
+    _, idx_prev, _ = H.oracle_layer(inp, mask, w.k, None, keep_ppm)
+    H.check_layer(ctx, inp, inp.mask, w.k, idx_prev, "ratio hybrid", keep_ppm=keep_ppm)
+
+
+def test_ratio_rule_decode_step(ctx):
+    lb = H.binding()
+    n_layers, keep_ppm = 4, 200000
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=20000, k=4096, n_layers=n_layers, planted=64)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=20000) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, w.k, idx, keep_ppm)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 20000, w.k, kv=layers[0].k_cache,
+                          keep_ppm=keep_ppm)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    _say("ratio rule: 4-layer phased step, 20 % of 20000 rows")
+    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                    [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "ratio step layer %d" % l)
+    got = idx_final.cpu().numpy()
+    assert ((got[0] >= 0).sum(axis=1) == 4000).all()
+    G = w.group
+    for g in range(w.n_kv_heads):
+        if layers[-1].mask[g * G:(g + 1) * G].any():
+            ok, _, msg = H.index_sets_match(got[0, g], refs[-1][1][0, g], refs[-1][2][0, g, :20000], 4000, H.TIE_REL)
+            assert ok, msg
+        else:
+            assert (got[0, g] == refs[-1][1][0, g]).all()
