@@ -27,7 +27,13 @@
  *   - the Ratio rule of Sec. 4.4.1 keeps a budget proportional to the sequence length;
  *     App. E.2's sparsity table shows that its theta is the share of tokens dropped, so
  *     the share kept is 1 - theta.  The oracle takes the kept share in parts per million
- *     and rounds the budget up (the paper does not say how it rounds).
+ *     and rounds the budget up (the paper does not say how it rounds);
+ *   - the block-granular variant: App. C's kernel takes *block* indices (Alg. 2, block size
+ *     64 in Sec. 4.3.2) but the paper never says how a block is scored.  Here a block's score
+ *     is the largest pooled token score inside it (so the block holding the best token is
+ *     always kept), blocks are ranked like tokens (ties to the lower block), a set entry e
+ *     names the positions [e*block, (e+1)*block) below the sequence length, and the budget
+ *     counts blocks.  block = 1 is the token-granular method itself.
  *
  * Every function is a direct loop nest: no blocking, no fusion, no reordering.
  * OpenMP only spreads the independent (sequence, KV head) pairs over cores.
@@ -172,17 +178,19 @@ void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
  *   idx_out    [B][Hkv][k], may be NULL
  *   sel_out    fp64 [B][Hkv][max_len] pooled selection scores of groups that hold a
  *              retrieval head (other groups and t >= L_b: NaN); may be NULL
- *   keep_ppm   0: Eq. 2's fixed budget k.  > 0: the Ratio rule, lo_ratio_budget() positions
+ *   keep_ppm   0: Eq. 2's fixed budget k.  > 0: the Ratio rule, lo_ratio_budget() entries
  *              per sequence, in sets of capacity k
+ *   block      positions one set entry stands for (1: tokens; 64: the blocks of App. C).  The
+ *              entries of idx_in / idx_out are then block numbers and k counts blocks.
  * Returns 0, or -1 on an argument it cannot serve.
  */
-int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
-                        const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
-                        int64_t stride_h, int64_t stride_t, const uint8_t *mask,
-                        const int32_t *idx_in, const int32_t *lengths, double *out,
-                        int32_t *idx_out, double *sel_out, int32_t keep_ppm)
+int lo_decode_attn_block(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
+                         const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
+                         int64_t stride_h, int64_t stride_t, const uint8_t *mask,
+                         const int32_t *idx_in, const int32_t *lengths, double *out,
+                         int32_t *idx_out, double *sel_out, int32_t keep_ppm, int32_t block)
 {
-    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || d < 1 || k < 1) return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || d < 1 || k < 1 || block < 1) return -1;
     if (keep_ppm < 0 || keep_ppm > 1000000) return -1;
     const int32_t G = Hq / Hkv;
     int any_sparse = 0;
@@ -194,7 +202,7 @@ int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k
     if (idx_in != NULL)
         for (int32_t b = 0; b < B; ++b)
             for (int64_t j = 0; j < (int64_t)Hkv * k; ++j)
-                if (idx_in[(int64_t)b * Hkv * k + j] >= lengths[b]) return -1;
+                if ((int64_t)idx_in[(int64_t)b * Hkv * k + j] * block >= lengths[b]) return -1;
 
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int32_t b = 0; b < B; ++b) {
@@ -202,21 +210,26 @@ int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k
             const int32_t L = lengths[b];
             const uint16_t *Kg = K + b * stride_b + g * stride_h;
             const uint16_t *Vg = V + b * stride_b + g * stride_h;
+            const int32_t n_units = (L + block - 1) / block;  /* blocks of this sequence */
             double *s = malloc((size_t)L * sizeof *s);
-            double *w = malloc((size_t)(L > k ? L : k) * sizeof *w);
+            double *w = malloc((size_t)L * sizeof *w);
             double *sel = malloc((size_t)L * sizeof *sel);
+            double *unit_score = malloc((size_t)n_units * sizeof *unit_score);
             int32_t *every = malloc((size_t)L * sizeof *every);
-            int32_t *set = malloc((size_t)k * sizeof *set);
+            int32_t *set = malloc((size_t)L * sizeof *set);
             for (int32_t t = 0; t < L; ++t) {
                 every[t] = t;
                 sel[t] = 0.0;
             }
-            /* the inherited set of this KV head: valid entries of idx_in */
+            /* the inherited set of this KV head: the positions below L that the valid
+             * entries of idx_in stand for (entries are distinct, so no position repeats) */
             int32_t n_set = 0;
             if (idx_in != NULL)
                 for (int32_t j = 0; j < k; ++j) {
-                    int32_t t = idx_in[((int64_t)b * Hkv + g) * k + j];
-                    if (t >= 0) set[n_set++] = t;
+                    int32_t e = idx_in[((int64_t)b * Hkv + g) * k + j];
+                    if (e < 0) continue;
+                    for (int32_t t = e * block; t < (e + 1) * block && t < L && n_set < L; ++t)
+                        set[n_set++] = t;
                 }
             int32_t n_retrieval = 0;
             for (int32_t h = g * G; h < (g + 1) * G; ++h) {
@@ -240,8 +253,16 @@ int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k
                 for (int32_t t = 0; t < L; ++t) sel[t] /= (double)n_retrieval;
             if (idx_out != NULL) {
                 int32_t *dst = idx_out + ((int64_t)b * Hkv + g) * k;
-                if (n_retrieval > 0)
-                    lo_topk_n(sel, L, lo_ratio_budget(L, k, keep_ppm), k, dst);
+                if (n_retrieval > 0) {
+                    /* a block is as good as its best token */
+                    for (int32_t u = 0; u < n_units; ++u) {
+                        double best = sel[u * block];
+                        for (int32_t t = u * block + 1; t < (u + 1) * block && t < L; ++t)
+                            if (sel[t] > best) best = sel[t];
+                        unit_score[u] = best;
+                    }
+                    lo_topk_n(unit_score, n_units, lo_ratio_budget(n_units, k, keep_ppm), k, dst);
+                }
                 else
                     memcpy(dst, idx_in + ((int64_t)b * Hkv + g) * k, (size_t)k * sizeof *dst);
             }
@@ -253,11 +274,23 @@ int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k
             free(s);
             free(w);
             free(sel);
+            free(unit_score);
             free(every);
             free(set);
         }
     }
     return 0;
+}
+
+/* Token-granular sets (the method as Sec. 3.1 states it), either rule. */
+int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
+                        const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
+                        int64_t stride_h, int64_t stride_t, const uint8_t *mask,
+                        const int32_t *idx_in, const int32_t *lengths, double *out,
+                        int32_t *idx_out, double *sel_out, int32_t keep_ppm)
+{
+    return lo_decode_attn_block(B, Hq, Hkv, d, k, max_len, q, K, V, stride_b, stride_h, stride_t, mask,
+                                idx_in, lengths, out, idx_out, sel_out, keep_ppm, 1);
 }
 
 /* The same with Eq. 2's fixed budget. */

@@ -55,6 +55,8 @@ def _load():
         lib.lo_decode_attn.restype = ctypes.c_int
         lib.lo_decode_attn_rule.argtypes = lib.lo_decode_attn.argtypes + [i32]
         lib.lo_decode_attn_rule.restype = ctypes.c_int
+        lib.lo_decode_attn_block.argtypes = lib.lo_decode_attn.argtypes + [i32, i32]
+        lib.lo_decode_attn_block.restype = ctypes.c_int
         lib.lo_ratio_budget.argtypes = [i32, i32, i32]
         lib.lo_ratio_budget.restype = i32
         lib.lo_topk_n.argtypes = [f64p, i32, i32, i32, i32p]
@@ -127,10 +129,12 @@ def ratio_budget(L: int, k: int, keep_ppm: int) -> int:
 
 def decode_attn(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, mask: np.ndarray,
                 k: int, idx_in: Optional[np.ndarray], lengths: np.ndarray,
-                want_sel: bool = False, keep_ppm: int = 0
+                want_sel: bool = False, keep_ppm: int = 0, block: int = 1
                 ) -> Tuple[np.ndarray, np.ndarray, Optional[np.ndarray]]:
     """One layer of Alg. 1's per-head loop.  keep_ppm > 0: the Ratio rule of Sec. 4.4.1
-    (ratio_budget() positions per sequence, in sets of capacity k) instead of the fixed budget.
+    (ratio_budget() entries per sequence, in sets of capacity k) instead of the fixed budget.
+    block > 1: the block-granular variant (App. C): set entries are block numbers, k counts
+    blocks, a block is scored by its best token.
 
     q_bits [B,Hq,d], k_bits / v_bits [B,Hkv,L_cap,d] (uint16 bf16 bit patterns, any
     strides numpy can express with a contiguous last axis), mask [Hq] uint8, idx_in
@@ -152,12 +156,12 @@ def decode_attn(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, mask
     out = np.empty((B, Hq, d), dtype=np.float64)
     idx_out = np.empty((B, Hkv, k), dtype=np.int32)
     sel = np.empty((B, Hkv, l_cap), dtype=np.float64) if want_sel else None
-    rc = _load().lo_decode_attn_rule(B, Hq, Hkv, d, k, l_cap, _ptr(q, ctypes.c_uint16),
+    rc = _load().lo_decode_attn_block(B, Hq, Hkv, d, k, l_cap, _ptr(q, ctypes.c_uint16),
                                      _ptr(k_bits, ctypes.c_uint16), _ptr(v_bits, ctypes.c_uint16),
                                      sb, sh, st, _ptr(mask, ctypes.c_uint8),
                                      _ptr(idx_in, ctypes.c_int32), _ptr(lengths, ctypes.c_int32),
                                      _ptr(out, ctypes.c_double), _ptr(idx_out, ctypes.c_int32),
-                                     _ptr(sel, ctypes.c_double), int(keep_ppm))
+                                     _ptr(sel, ctypes.c_double), int(keep_ppm), int(block))
     if rc != 0:
         raise ValueError("oracle rejected its arguments (rc=%d)" % rc)
     return out, idx_out, sel

@@ -315,3 +315,62 @@ def test_ratio_rule_with_the_share_that_gives_k_equals_topk():
     _, idx_k, _ = lo.decode_attn(q, K, V, mask, 50, None, lens)
     _, idx_r, _ = lo.decode_attn(q, K, V, mask, 64, None, lens, keep_ppm=250000)   # 25 % of 200 = 50
     assert (idx_r[0, 0, :50] == idx_k[0, 0]).all() and (idx_r[0, 0, 50:] == -1).all()
+
+
+# ------------------------------------------------------------------ block-granular sets (App. C)
+def _block_case(seed, B=2, Hq=4, Hkv=2, L_cap=300, lens=(300, 170)):
+    rng = np.random.default_rng(seed)
+    q = round_to_bf16_bits(rng.standard_normal((B, Hq, 128)))
+    K = round_to_bf16_bits(rng.standard_normal((B, Hkv, L_cap, 128)))
+    V = round_to_bf16_bits(rng.standard_normal((B, Hkv, L_cap, 128)))
+    return q, K, V, np.array(lens, np.int32)
+
+
+@pytest.mark.parametrize("block", [4, 64])
+def test_block_sets_rank_blocks_by_their_best_token(block):
+    q, K, V, lens = _block_case(21)
+    K[:, :, 7] = K[:, :, 150]                      # a tie between the best tokens of two blocks
+    mask = np.ones(4, np.uint8)
+    for kb in (1, 2, 3, 100):
+        _, idx, sel = lo.decode_attn(q, K, V, mask, kb, None, lens, want_sel=True, block=block)
+        for b in range(2):
+            L = int(lens[b])
+            units = -(-L // block)
+            n = min(kb, units)
+            for g in range(2):
+                score = [max(sel[b, g, u * block:min((u + 1) * block, L)]) for u in range(units)]
+                order = sorted(range(units), key=lambda u: (-score[u], u))    # brute force
+                assert list(idx[b, g][:n]) == sorted(order[:n]) and (idx[b, g][n:] == -1).all()
+                best_token = int(np.argmax(sel[b, g, :L]))
+                assert best_token // block in idx[b, g][:n]   # the best token's block is always kept
+
+
+def test_block_sparse_attention_equals_token_sparse_attention_on_the_same_positions():
+    block = 16
+    q, K, V, lens = _block_case(22, lens=(300, 171))          # 171: the last block is ragged
+    K[:, :, 171:] = 1000.0                                     # rows past a length must never be read
+    mask = np.array([0, 1, 0, 0], np.uint8)
+    idx_blocks = np.full((2, 2, 5), -1, np.int32)
+    idx_blocks[0, :, :4] = [0, 3, 9, 18]                       # 18 is the last block of 300 rows
+    idx_blocks[1, :, :3] = [10, 2, 5]                          # 10 is the ragged last block of 171 rows
+    out_b, idx_b, _ = lo.decode_attn(q, K, V, mask, 5, idx_blocks, lens, block=block)
+    idx_tok = np.full((2, 2, 5 * block), -1, np.int32)
+    for b in range(2):
+        for g in range(2):
+            pos = [t for e in idx_blocks[b, g] if e >= 0 for t in range(e * block, min((e + 1) * block, int(lens[b])))]
+            idx_tok[b, g, :len(pos)] = pos
+    out_t, _, _ = lo.decode_attn(q, K, V, mask, 5 * block, idx_tok, lens, block=1)
+    sparse_heads = [0, 2, 3]
+    assert (out_b[:, sparse_heads] == out_t[:, sparse_heads]).all()
+    assert (idx_b[:, 1] == idx_blocks[:, 1]).all()            # group 1 holds no retrieval head: handed on
+
+
+def test_block_of_one_is_the_token_method_and_ratio_counts_blocks():
+    q, K, V, lens = _block_case(23)
+    mask = np.ones(4, np.uint8)
+    a = lo.decode_attn(q, K, V, mask, 40, None, lens)
+    b = lo.decode_attn(q, K, V, mask, 40, None, lens, block=1)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
+    _, idx, _ = lo.decode_attn(q, K, V, mask, 40, None, lens, keep_ppm=250000, block=8)
+    assert ((idx[0] >= 0).sum(axis=1) == 10).all()            # 300 rows = 38 blocks of 8; a quarter, rounded up
+    assert ((idx[1] >= 0).sum(axis=1) == 6).all()             # 170 rows = 22 blocks; ceil(5.5) = 6
