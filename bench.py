@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--k", type=int, default=0, help="override the budget (the c5 sweep)")
     ap.add_argument("--retrieval", type=int, default=0, help="override the retrieval heads per layer (the c5 sweep)")
+    ap.add_argument("--block", action="store_true",
+                    help="block-granular sets (App. C): the budget becomes k/64 blocks of 64 positions")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--tail", type=int, default=-1)
     ap.add_argument("--gather-block", type=int, default=0)
@@ -88,15 +90,18 @@ def main() -> int:
     masks = np.stack([ly.mask for ly in layers])
     lens_h = layers[0].lengths
     lens = torch.from_numpy(lens_h).to(dev)
-    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, w.k, kv=layers[0].k_cache)
+    unit = 64 if args.block else 1          # positions one set entry names
+    k_set = max(1, w.k // unit)             # entries per set
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, k_set, kv=layers[0].k_cache,
+                          block_size=unit)
     ws = lb.alloc_workspace(shape, dev, n_layers=n_layers)
     outs = [torch.zeros_like(ly.q) for ly in layers]
-    idx_final = torch.zeros((w.batch, w.n_kv_heads, w.k), dtype=torch.int32, device=dev)
+    idx_final = torch.zeros((w.batch, w.n_kv_heads, k_set), dtype=torch.int32, device=dev)
     idx0 = None
     if not masks[0].all():      # single-layer workloads: some inherited sets to gather from
-        idx0_h = np.tile(np.arange(w.k, dtype=np.int32), (w.batch, w.n_kv_heads, 1))
+        idx0_h = np.tile(np.arange(k_set, dtype=np.int32), (w.batch, w.n_kv_heads, 1))
         for b in range(w.batch):
-            idx0_h[b] = np.minimum(idx0_h[b], int(lens_h[b]) - 1)
+            idx0_h[b] = np.minimum(idx0_h[b], (int(lens_h[b]) - 1) // unit)
         idx0 = torch.from_numpy(idx0_h).to(dev)
     qs = [ly.q for ly in layers]
     ks = [ly.k_cache for ly in layers]
@@ -181,7 +186,8 @@ def main() -> int:
         stream_bytes = rows_streamed * 512
     stream_bytes = (stream_bytes + n_layers * w.batch * w.n_q_heads * 256) / n_stream_launches
     achieved = stream_bytes / (stream_us * 1e-6) / 1e9 if stream_us > 0 else 0.0
-    default_run = args.workload == "c3" and not (args.layerwise or args.layers or args.k or args.retrieval)
+    default_run = args.workload == "c3" and not (args.layerwise or args.layers or args.k or args.retrieval
+                                                 or args.block)
     traffic = measured_traffic() if default_run else None
 
     result = {
@@ -201,7 +207,8 @@ def main() -> int:
                                "layer 0 all-retrieval then %d retrieval heads per layer" % (
                                    w.name, n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.max_len,
                                    w.k, w.n_retrieval),
-                   "step_mode": "layerwise" if args.layerwise else "phased"},
+                   "step_mode": "layerwise" if args.layerwise else "phased",
+                   "sets": "blocks of 64 positions" if args.block else "positions"},
         "step_algorithmic_bytes": step_bytes,
         "step_achieved_gbps": round(step_bytes / sec / 1e9, 1),
         "step_hbm_frac": round(step_bytes / sec / 1e9 / HBM_PEAK_GBPS, 4),
@@ -240,7 +247,7 @@ def main() -> int:
             ly = layers[l]
             qb, kb, vb = (wl.bf16_bits(t) for t in (ly.q, ly.k_cache, ly.v_cache))
             t0 = time.perf_counter()
-            _, idx, _ = lo.decode_attn(qb, kb, vb, masks[l], w.k, idx, lens_h)
+            _, idx, _ = lo.decode_attn(qb, kb, vb, masks[l], k_set, idx, lens_h, block=unit)
             t_cpu += time.perf_counter() - t0
         result["cpu_baseline"] = {"value": round(t_cpu * 1e6, 0), "unit": "us", "cores": lo.num_threads(),
                                   "kind": "oracle",

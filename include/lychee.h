@@ -76,7 +76,10 @@ typedef struct lychee_shape {
                             paper's theta is the share of tokens dropped, App. E.2: theta = 70 %
                             is keep_ppm = 300000.)  Sparse heads attend over whatever valid
                             entries the inherited set holds, under either rule.               */
-    int32_t reserved;    /* 0 */
+    int32_t block_size;  /* 0 or 1: sets name positions (Sec. 3.1).  64: the block-granular variant of
+                            App. C / Sec. 4.3.2: a set entry e names the positions [64e, 64e+63]
+                            below L_b, a block is ranked by the best pooled score inside it, and k,
+                            idx_in / idx_out and the Ratio rule all count blocks.               */
 } lychee_shape;
 
 /* Create / destroy a context bound to HIP device `device`.  Needs a GPU. */

@@ -40,7 +40,7 @@ class Shape(ctypes.Structure):
                 ("max_len", ctypes.c_int32), ("k", ctypes.c_int32),
                 ("kv_stride_batch", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
                 ("kv_stride_tok", ctypes.c_int64), ("keep_ppm", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("block_size", ctypes.c_int32)]
 
 
 class LycheeError(RuntimeError):
@@ -111,7 +111,8 @@ def _stream(stream) -> Optional[int]:
 
 def make_shape(batch: int, n_q_heads: int, n_kv_heads: int, max_len: int, k: int,
                kv: Optional[torch.Tensor] = None, head_dim: int = 128,
-               strides: Optional[Sequence[int]] = None, keep_ppm: int = 0) -> Shape:
+               strides: Optional[Sequence[int]] = None, keep_ppm: int = 0,
+               block_size: int = 0) -> Shape:
     """A `lychee_shape`; KV strides (elements) come from a [B,H_kv,L_cap,128] tensor or `strides`."""
     if strides is None:
         if kv is not None:
@@ -119,7 +120,7 @@ def make_shape(batch: int, n_q_heads: int, n_kv_heads: int, max_len: int, k: int
         else:
             strides = (n_kv_heads * max_len * head_dim, max_len * head_dim, head_dim)
     return Shape(batch, n_q_heads, n_kv_heads, head_dim, max_len, k, *[int(s) for s in strides],
-                 int(keep_ppm), 0)
+                 int(keep_ppm), int(block_size))
 
 
 def check_shape(shape: Shape, head_type_mask: Optional[np.ndarray] = None,

@@ -112,7 +112,8 @@ int check_shape(const lychee_shape *s)
     if (s->n_kv_heads > kMaxKvHeads) return LYCHEE_EUNSUPPORTED;
     if (s->n_q_heads / s->n_kv_heads > kMaxGroup) return LYCHEE_EUNSUPPORTED;
     if (s->max_len > (1 << 24) || s->batch > kMaxBatch) return LYCHEE_EUNSUPPORTED;
-    if (s->keep_ppm < 0 || s->keep_ppm > 1000000 || s->reserved != 0) return LYCHEE_EINVAL;
+    if (s->keep_ppm < 0 || s->keep_ppm > 1000000) return LYCHEE_EINVAL;
+    if (s->block_size != 0 && s->block_size != 1 && s->block_size != 64) return LYCHEE_EUNSUPPORTED;
     if (s->kv_stride_tok < kHeadDim || s->kv_stride_batch < 0 || s->kv_stride_head < 0)
         return LYCHEE_EINVAL;
     if (s->kv_stride_tok % 8 || s->kv_stride_head % 8 || s->kv_stride_batch % 8) return LYCHEE_EINVAL;
@@ -279,6 +280,7 @@ struct Launcher {
         c.group = s.n_q_heads / s.n_kv_heads;
         c.k = s.k;
         c.keep_ppm = s.keep_ppm;
+        c.block_shift = s.block_size == 64 ? 6 : 0;
         c.max_len = s.max_len;
         c.sel_stride = w.sel_stride;
         c.list_row = w.list_row;
@@ -323,7 +325,7 @@ struct Launcher {
 int run_layer(const Launcher &L, int l, bool select)
 {
     int rc;
-    if (select) {
+    if (select && L.s.block_size != 64) {  // block scores need no threshold: every block is ranked
         Ranges t;
         t.t_first = l, t.t_count = 1;
         if ((rc = L.go(t)) != LYCHEE_OK) return rc;
@@ -550,7 +552,7 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
         // All layers at once, one launch per phase; each phase needs only earlier phases:
         //   T (thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
         Ranges t;
-        t.t_first = 0, t.t_count = n_select;
+        t.t_first = 0, t.t_count = shape->block_size == 64 ? 0 : n_select;
         if ((rc = L.go(t)) != LYCHEE_OK) return rc;
         Ranges r;
         r.r_first = 0, r.r_count = n_layers;
@@ -635,7 +637,7 @@ int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_
     unsigned long long host = 0;
     bool ok = hipMemcpyAsync(dev, &host, sizeof host, hipMemcpyHostToDevice, stream) == hipSuccess;
     ok = ok && launch_validate_idx(idx, lengths, shape->batch, shape->n_kv_heads, shape->k,
-                                   shape->max_len, dev, stream) == hipSuccess;
+                                   shape->max_len, shape->block_size == 64 ? 6 : 0, dev, stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(&host, dev, sizeof host, hipMemcpyDeviceToHost, stream) == hipSuccess;
     ok = ok && hipStreamSynchronize(stream) == hipSuccess;
     (void)hipFree(dev);

@@ -17,6 +17,7 @@ constexpr int kThreads = LYCHEE_THREADS;  // threads of every workgroup (256 or 
 constexpr int kWaves = kThreads / 64;
 constexpr int kTileRows = 16;            // rows one wavefront handles per iteration
 constexpr int kBlockRows = kWaves * kTileRows;  // cache rows per block of the pooled row space
+static_assert(kBlockRows == 64, "a pooled block is also the selection block of the block-granular variant");
 constexpr int kMaxWg = 1024;             // upper bound of the grid of one launch
 constexpr int kIdxChunk = 2048;          // set entries staged in LDS at a time
 constexpr int kSampleTilesMin = 128;     // the threshold sample: 128 to 256 tiles of 16 rows
@@ -36,6 +37,7 @@ struct Common {
     int32_t batch, n_q_heads, n_kv_heads, group;
     int32_t k, max_len, sel_stride;
     int32_t keep_ppm;     // > 0: the Ratio rule's share of a sequence, in parts per million
+    int32_t block_shift;  // 0: sets name positions; 6: blocks of 64 positions (App. C)
     int32_t list_row;     // capacity, in entries, of one score row's candidate list
     int32_t n_wg;         // grid size of this launch
     int32_t part_stride;  // partial slots per head
@@ -91,7 +93,7 @@ struct LaunchPlan {
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream);
 hipError_t launch_validate_idx(const int32_t *idx, const int32_t *lengths, int32_t batch,
-                               int32_t n_kv_heads, int32_t k, int32_t max_len,
+                               int32_t n_kv_heads, int32_t k, int32_t max_len, int32_t block_shift,
                                unsigned long long *n_bad, hipStream_t stream);
 hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
 hipError_t launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);

@@ -153,7 +153,14 @@ __device__ __forceinline__ uint32_t ordered_key(float x)
 
 __device__ __forceinline__ int clamp_len(int L, int max_len) { return L < 1 ? 1 : (L > max_len ? max_len : L); }
 
-// Positions selected for a sequence of L rows: Eq. 2's fixed budget, min(k, L), or under the
+// Selectable units of a sequence of L rows: its positions, or its blocks of 64 positions
+// (the last one may be short) in the block-granular variant (App. C).
+__device__ __forceinline__ int units_of(const Common &c, int L)
+{
+    return (L + (1 << c.block_shift) - 1) >> c.block_shift;
+}
+
+// Units selected for a sequence of L units: Eq. 2's fixed budget, min(k, L), or under the
 // Ratio rule (Sec. 4.4.1: a budget proportional to the sequence length) the rounded-up share
 // keep_ppm / 10^6 of L, at least 1 and at most the fixed budget.
 __device__ __forceinline__ int budget_of(const Common &c, int L)
@@ -351,6 +358,8 @@ struct Emit {
     int32_t *count;
     uint32_t thr;              // a row is a candidate when its ordered key reaches this
     int32_t cap;
+    int32_t direct;            // block-granular: entry b of the list is block b's best score,
+                               // written in place; no threshold, no counter
 };
 
 // Appends a wavefront's n buffered candidates to the row's list.  The counter keeps counting
@@ -387,12 +396,21 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
     const int rs = lane >> 4;  // row slot: which of the 4 rows of a load this lane is in
     const int ch = lane & 15;  // 16-byte chunk of the 256-byte row
     constexpr int kSpan = 32 * kWaves;
-    const int n_spans = (r1 - r0 + kSpan - 1) / kSpan;
     const float c_log2e = c.scale_log2e;
+    const int bshift = c.block_shift;
+    // A span is 32 rows per wavefront.  Normally the wavefronts' rows interleave (wavefront w:
+    // rows 32w .. 32w+31 of every 128).  When block scores are wanted a wavefront owns a whole
+    // block instead: rows 64w .. 64w+63 of every 256, as two consecutive spans.
+    const bool by_block = !GATHER && em.direct != 0;
+    const int n_spans = by_block ? 2 * ((r1 - r0 + 2 * kSpan - 1) / (2 * kSpan)) : (r1 - r0 + kSpan - 1) / kSpan;
+    auto span_base = [&](int span) {
+        return by_block ? r0 + (span >> 1) * (2 * kSpan) + 64 * wave + 32 * (span & 1) : r0 + span * kSpan + 32 * wave;
+    };
+    float block_best = 0.0f;
 
     // tile `half` (0 or 1) of span `span`: rows base .. base+15 of this wavefront
     auto issue = [&](Tile &t, int span, int half) {
-        const int base = r0 + span * kSpan + 32 * wave + 16 * half;
+        const int base = span_base(span) + 16 * half;
         t.valid = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -400,8 +418,10 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             int row;
             bool ok;
             if (GATHER) {
-                const int tpos = (r < r1) ? idx_s[r - r0] : -1;
-                ok = (tpos >= 0) && (tpos < L);
+                // set entry (r - r0) >> bshift names 2^bshift consecutive cache rows
+                const int e = (r < r1) ? idx_s[(r - r0) >> bshift] : -1;
+                const int tpos = (e << bshift) + (r & ((1 << bshift) - 1));
+                ok = (e >= 0) && (tpos < L);
                 row = ok ? tpos : 0;
             } else {
                 ok = r < r1;
@@ -437,7 +457,26 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
         __builtin_amdgcn_sched_barrier(0);
         issue(t1, span + 1, 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (!GATHER && em.list != nullptr) {
+        if (!GATHER && em.list != nullptr && em.direct != 0) {
+            // the best pooled score of this span's valid rows: every lane of a row slot holds
+            // its 8 rows' scores, the four row slots are merged by two exchanges
+            const int rb = span_base(span);
+            float m = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = rb + 4 * j + rs;
+                m = (r < r1) ? fmaxf(m, sel_value(sel0[j], sel_mul)) : m;
+                m = (r + 16 < r1) ? fmaxf(m, sel_value(sel1[j], sel_mul)) : m;
+            }
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            block_best = (span & 1) ? fmaxf(block_best, m) : m;
+            const int first = rb - 32;  // of the block, when this is its second span
+            if ((span & 1) && first < r1 && lane == 0) {
+                const uint32_t blk = (uint32_t)(first >> 6);
+                gstore(em.list + blk, (unsigned long long)ordered_key(block_best) | ((unsigned long long)blk << 32));
+            }
+        } else if (!GATHER && em.list != nullptr) {
             // lane ch (< 8) of each row slot holds the score of row 16*(ch/4) + 4*(ch%4) + rs
             const int j = ch & 3;
             float lo = sel0[0], hi = sel1[0];
@@ -464,7 +503,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             }
         }
     }
-    if (!GATHER && em.list != nullptr && cand_n > 0) flush_candidates(cand_buf, cand_n, em);
+    if (!GATHER && em.list != nullptr && em.direct == 0 && cand_n > 0) flush_candidates(cand_buf, cand_n, em);
 }
 
 // One (workgroup, segment) piece: rows/entries [r0, r1) of segment (b, g) for the heads in
@@ -511,10 +550,14 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     const float sel_mul = c.scale / (float)NH;
 
     if (GATHER) {
-        for (int e0 = r0; e0 < r1; e0 += kIdxChunk) {
-            const int e1 = e0 + kIdxChunk < r1 ? e0 + kIdxChunk : r1;
+        // rows r0 .. r1-1 of the gathered sequence are row (r mod 2^shift) of set entry r >> shift
+        const int shift = c.block_shift;
+        const int chunk_rows = kIdxChunk << shift;
+        for (int e0 = r0; e0 < r1; e0 += chunk_rows) {
+            const int e1 = e0 + chunk_rows < r1 ? e0 + chunk_rows : r1;
+            const int n_entries = (e1 - e0 + (1 << shift) - 1) >> shift;
             __syncthreads();  // the previous chunk's readers are done
-            for (int i = threadIdx.x; i < e1 - e0; i += kThreads) sh.idx_s[i] = gload(idx_src + e0 + i);
+            for (int i = threadIdx.x; i < n_entries; i += kThreads) sh.idx_s[i] = gload(idx_src + (e0 >> shift) + i);
             __syncthreads();
             stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr);
         }
@@ -1024,7 +1067,8 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
     const int rgi = p.rindex[g];
-    const int L = clamp_len(c.lengths[b], c.max_len);
+    const int len = clamp_len(c.lengths[b], c.max_len);
+    const int L = units_of(c, len);  // what is ranked: positions, or blocks of positions
     const int n = budget_of(c, L);
     if (n == L) {  // everything is selected
         for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
@@ -1032,7 +1076,8 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     }
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     const unsigned long long *list = p.list + row * (int64_t)c.list_row;
-    const int total = gload(p.list_count + row);
+    // block-granular: the streaming left every block's score at its place in the list
+    const int total = c.block_shift ? L : gload(p.list_count + row);
     TRACE(5);
     if (total >= n && total <= kThreads * kSelRegs && total <= c.list_row) {
         RegEntries E;
@@ -1044,16 +1089,17 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
         select_from(E, n, L, dst, sh, pool);
     } else {
         // too few candidates reached the threshold, or too many for the list: rank the row
+        // (token-granular only: a block list is always complete)
         float *sel = p.sel + row * c.sel_stride;
         switch (__builtin_popcount(p.rmask[g] & ((1u << c.group) - 1u))) {
-        case 1: score_row_unit<1>(c, p, b, g, L, sel); break;
-        case 2: score_row_unit<2>(c, p, b, g, L, sel); break;
-        case 3: score_row_unit<3>(c, p, b, g, L, sel); break;
-        default: score_row_unit<4>(c, p, b, g, L, sel); break;
+        case 1: score_row_unit<1>(c, p, b, g, len, sel); break;
+        case 2: score_row_unit<2>(c, p, b, g, len, sel); break;
+        case 3: score_row_unit<3>(c, p, b, g, len, sel); break;
+        default: score_row_unit<4>(c, p, b, g, len, sel); break;
         }
         __threadfence();
         __syncthreads();  // the scores are read back by other threads of the workgroup
-        const RowEntries E{sel, L};
+        const RowEntries E{sel, len};
         select_from(E, n, L, dst, sh, pool);
     }
     for (int i = n + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
@@ -1170,6 +1216,18 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
 
 // Launches that carry pooled R and G rows.  Two workgroups per CU must fit (the static shares
 // assume that every workgroup runs from the start): at most 256 registers per lane.
+// Rows a sparse KV head gathers for a sequence of L cache rows (set entries that are -1 or
+// name rows past L are skipped one by one), and how many of them make one pooled block.
+__device__ __forceinline__ int gather_rows(const Common &c, int L)
+{
+    const int units = units_of(c, L);
+    return (c.k < units ? c.k : units) << c.block_shift;
+}
+__device__ __forceinline__ int gather_block(const Common &c)
+{
+    return c.block_shift ? (1 << c.block_shift) : c.g_block_rows;  // whole blocks stream like R rows
+}
+
 // COLLECT = false is the dense baseline's streaming: no layer selects anything.
 template <bool HAS_R, bool HAS_G, bool COLLECT>
 __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPlan P)
@@ -1202,9 +1260,8 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                 if (li < P.r_count) {
                     blocks[i] = (uint32_t)(layers[P.r_first + li].n_rgroups * ((L + kBlockRows - 1) / kBlockRows));
                 } else {
-                    const int kk = c.k < L ? c.k : L;
                     blocks[i] = (uint32_t)(layers[P.g_first + li - P.r_count].n_sgroups *
-                                           ((kk + c.g_block_rows - 1) / c.g_block_rows));
+                                           ((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c)));
                 }
             }
             sum += blocks[i];
@@ -1279,8 +1336,8 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             }
             const uint32_t *dw = desc_s[cur];
             const int len_b = pool.len[b];
-            const int seg_rows = gather ? (c.k < len_b ? c.k : len_b) : len_b;
-            const int brows = gather ? c.g_block_rows : kBlockRows;
+            const int seg_rows = gather ? gather_rows(c, len_b) : len_b;
+            const int brows = gather ? gather_block(c) : kBlockRows;
             const int nb = (seg_rows + brows - 1) / brows;  // blocks per segment of this item
             const int xo = x - pool.ipre[it];
             const int gi = xo / nb;
@@ -1326,13 +1383,14 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             if (!gather) {
                 const int g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
                 const uint32_t hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
-                Emit em{nullptr, nullptr, 0u, 0};
+                Emit em{nullptr, nullptr, 0u, 0, 0};
                 if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
                     const int64_t row = (int64_t)b * (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) + gi;
                     em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
                     em.count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, list_count)) + row;
-                    em.thr = gload(desc_ptr<uint32_t>(dw, offsetof(LayerDesc, thr)) + row);
+                    em.thr = c.block_shift ? 0u : gload(desc_ptr<uint32_t>(dw, offsetof(LayerDesc, thr)) + row);
                     em.cap = c.list_row;
+                    em.direct = c.block_shift != 0;
                 }
                 dispatch_piece<false>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
                                       d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa, at_rows_done);
@@ -1341,7 +1399,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                 const uint32_t hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
                 const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)g) +
                                          ((int64_t)b * c.n_kv_heads + g) * c.k;
-                dispatch_piece<true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{nullptr, nullptr, 0u, 0},
+                dispatch_piece<true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{nullptr, nullptr, 0u, 0, 0},
                                      d_part_o, d_part_ml, d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa,
                                      at_rows_done);
             }
@@ -1393,12 +1451,13 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(uint4 *dst, const uint4
 }
 
 __global__ void validate_idx_kernel(const int32_t *idx, const int32_t *lengths, int32_t n_kv_heads,
-                                    int32_t k, int32_t max_len, unsigned long long *n_bad)
+                                    int32_t k, int32_t max_len, int32_t block_shift,
+                                    unsigned long long *n_bad)
 {
     // one workgroup per (sequence, KV head); quadratic duplicate check, debug use only
     const int bg = blockIdx.x;
     const int b = bg / n_kv_heads;
-    const int L = clamp_len(lengths[b], max_len);
+    const int L = (clamp_len(lengths[b], max_len) + (1 << block_shift) - 1) >> block_shift;
     const int32_t *row = idx + (int64_t)bg * k;
     unsigned long long bad = 0;
     for (int i = threadIdx.x; i < k; i += blockDim.x) {
@@ -1452,11 +1511,11 @@ hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
 }
 
 hipError_t launch_validate_idx(const int32_t *idx, const int32_t *lengths, int32_t batch,
-                               int32_t n_kv_heads, int32_t k, int32_t max_len,
+                               int32_t n_kv_heads, int32_t k, int32_t max_len, int32_t block_shift,
                                unsigned long long *n_bad, hipStream_t stream)
 {
     hipLaunchKernelGGL(validate_idx_kernel, dim3(batch * n_kv_heads), dim3(256), 0, stream, idx,
-                       lengths, n_kv_heads, k, max_len, n_bad);
+                       lengths, n_kv_heads, k, max_len, block_shift, n_bad);
     return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def previous_layer_sets(inp: wl.LayerInputs, k: int, seed: int = 99) -> np.ndarray:
+def previous_layer_sets(inp: wl.LayerInputs, k: int, seed: int = 99, block: int = 1) -> np.ndarray:
     """Realistic inherited sets: the oracle's top-k of an all-retrieval previous layer with
     an independently drawn query on the same cache."""
     w = inp.workload
@@ -34,7 +34,7 @@ def previous_layer_sets(inp: wl.LayerInputs, k: int, seed: int = 99) -> np.ndarr
     q_prev = torch.randn(inp.q.shape, generator=g, dtype=torch.float32).to(torch.bfloat16)
     _, idx, _ = lo.decode_attn(wl.bf16_bits(q_prev), wl.bf16_bits(inp.k_cache),
                                wl.bf16_bits(inp.v_cache), np.ones(w.n_q_heads, np.uint8), k, None,
-                               inp.lengths)
+                               inp.lengths, block=block)
     return idx
 
 
@@ -42,7 +42,7 @@ class DeviceLayer:
     """Device copies of one layer's inputs plus output buffers."""
 
     def __init__(self, inp: wl.LayerInputs, k: int, idx_in: Optional[np.ndarray], device="cuda",
-                 keep_ppm: int = 0):
+                 keep_ppm: int = 0, block: int = 1):
         lb = binding()
         w = inp.workload
         self.inp, self.k = inp, k
@@ -55,7 +55,7 @@ class DeviceLayer:
                               device=device)
         self.idx_out = torch.full((w.batch, w.n_kv_heads, k), -7, dtype=torch.int32, device=device)
         self.shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, self.k_cache.shape[2], k,
-                                   kv=self.k_cache, keep_ppm=keep_ppm)
+                                   kv=self.k_cache, keep_ppm=keep_ppm, block_size=block)
         self.workspace = lb.alloc_workspace(self.shape, device)
         # poison the workspace: results must not depend on what it held
         self.workspace.fill_(0xFF)
@@ -74,10 +74,17 @@ def run_dense(ctx, dl: DeviceLayer):
     return bf16_tensor_to_f64(dl.out)
 
 
-def oracle_layer(inp: wl.LayerInputs, mask, k, idx_in, keep_ppm: int = 0):
+def oracle_layer(inp: wl.LayerInputs, mask, k, idx_in, keep_ppm: int = 0, block: int = 1):
     return lo.decode_attn(wl.bf16_bits(inp.q), wl.bf16_bits(inp.k_cache), wl.bf16_bits(inp.v_cache),
                           np.asarray(mask, np.uint8), k, idx_in, inp.lengths, want_sel=True,
-                          keep_ppm=keep_ppm)
+                          keep_ppm=keep_ppm, block=block)
+
+
+def unit_scores(sel_row: np.ndarray, L: int, block: int) -> np.ndarray:
+    """What the sets rank: a position's pooled score, or a block's best one."""
+    if block == 1:
+        return sel_row[:L]
+    return np.maximum.reduceat(sel_row[:L], np.arange(0, L, block))
 
 
 def assert_outputs_close(got: np.ndarray, ref: np.ndarray, what=""):
@@ -91,7 +98,7 @@ def assert_outputs_close(got: np.ndarray, ref: np.ndarray, what=""):
 
 
 def assert_sets_match(idx_gpu, idx_ref, sel_ref, mask, inp: wl.LayerInputs, k, idx_in, what="",
-                      keep_ppm: int = 0):
+                      keep_ppm: int = 0, block: int = 1):
     """Per (sequence, KV head): retrieval groups match the oracle's set (differences only at
     oracle ties), are ascending and -1 padded; other groups are a verbatim copy of idx_in.
     Returns the number of positions that differed inside the tie allowance."""
@@ -99,7 +106,7 @@ def assert_sets_match(idx_gpu, idx_ref, sel_ref, mask, inp: wl.LayerInputs, k, i
     G = w.group
     n_diff = 0
     for b in range(w.batch):
-        L = int(inp.lengths[b])
+        L = -(-int(inp.lengths[b]) // block)       # units: positions, or blocks
         n = lo.ratio_budget(L, k, keep_ppm)
         for g in range(w.n_kv_heads):
             got = idx_gpu[b, g]
@@ -108,7 +115,8 @@ def assert_sets_match(idx_gpu, idx_ref, sel_ref, mask, inp: wl.LayerInputs, k, i
                 assert (got[n:] == -1).all(), "%s: padding b=%d g=%d" % (what, b, g)
                 assert (np.diff(valid) > 0).all(), "%s: not ascending b=%d g=%d" % (what, b, g)
                 assert valid.min() >= 0 and valid.max() < L
-                ok, nd, msg = index_sets_match(got, idx_ref[b, g], sel_ref[b, g, :L], n, TIE_REL)
+                ok, nd, msg = index_sets_match(got, idx_ref[b, g],
+                                               unit_scores(sel_ref[b, g], int(inp.lengths[b]), block), n, TIE_REL)
                 assert ok, "%s: b=%d g=%d: %s" % (what, b, g, msg)
                 n_diff += nd
             else:
@@ -116,13 +124,14 @@ def assert_sets_match(idx_gpu, idx_ref, sel_ref, mask, inp: wl.LayerInputs, k, i
     return n_diff
 
 
-def check_layer(ctx, inp: wl.LayerInputs, mask, k, idx_in, what="", exact_sets=False, keep_ppm: int = 0):
+def check_layer(ctx, inp: wl.LayerInputs, mask, k, idx_in, what="", exact_sets=False, keep_ppm: int = 0,
+                block: int = 1):
     """Run one hybrid layer call on the GPU and compare everything with the oracle."""
-    dl = DeviceLayer(inp, k, idx_in, keep_ppm=keep_ppm)
+    dl = DeviceLayer(inp, k, idx_in, keep_ppm=keep_ppm, block=block)
     out_gpu, idx_gpu = run_hybrid(ctx, dl, np.asarray(mask, np.uint8))
-    out_ref, idx_ref, sel_ref = oracle_layer(inp, mask, k, idx_in, keep_ppm)
+    out_ref, idx_ref, sel_ref = oracle_layer(inp, mask, k, idx_in, keep_ppm, block)
     assert_outputs_close(out_gpu, out_ref, what)
-    n_diff = assert_sets_match(idx_gpu, idx_ref, sel_ref, mask, inp, k, idx_in, what, keep_ppm)
+    n_diff = assert_sets_match(idx_gpu, idx_ref, sel_ref, mask, inp, k, idx_in, what, keep_ppm, block)
     if exact_sets:
         assert n_diff == 0, "%s: %d positions differ from the oracle's sets" % (what, n_diff)
     return dl, out_gpu, idx_gpu, out_ref, idx_ref, sel_ref

@@ -103,6 +103,6 @@ def test_ratio_rule_field_is_validated(lb):
     assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=1000000)) == lb.OK
     assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=1000001)) == lb.EINVAL
     assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, keep_ppm=-1)) == lb.EINVAL
-    s = lb.make_shape(1, 8, 2, 4096, 256)
-    s.reserved = 7
-    assert lb.check_shape(s) == lb.EINVAL
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, block_size=64)) == lb.OK
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, block_size=1)) == lb.OK
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, block_size=32)) == lb.EUNSUPPORTED

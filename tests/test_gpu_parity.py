@@ -536,3 +536,102 @@ def test_ratio_rule_decode_step(ctx):
             assert ok, msg
         else:
             assert (got[0, g] == refs[-1][1][0, g]).all()
+
+
+# ------------------------------------------------------------------ block-granular sets (App. C)
+BLOCK_CASES = [
+    # B, Hq, Hkv, L_cap, lens, k (blocks), mask kind
+    (1, 8, 2, 4096, [4096], 8, "c1"),
+    (1, 8, 2, 4096, [4096], 64, "all_r"),        # k = every block
+    (2, 8, 2, 3000, [3000, 1111], 10, "mixed"),  # ragged last blocks
+    (3, 12, 4, 900, [900, 64, 65], 3, "mixed"),  # one block exactly, one row into the second block
+    (1, 4, 1, 20000, [19999], 100, "one_r"),
+]
+
+
+@pytest.mark.parametrize("case", BLOCK_CASES, ids=lambda c: "B%d_Hq%d_Hkv%d_L%d_k%d_%s" % (c[0], c[1], c[2], c[3], c[5], c[6]))
+def test_block_granular_layers(ctx, case):
+    B, Hq, Hkv, L_cap, lens, k, kind = case
+    rng = np.random.default_rng(5)
+    w = wl.scaled(wl.WORKLOADS["c1"], batch=B, n_q_heads=Hq, n_kv_heads=Hkv, max_len=L_cap, k=k, planted=8)
+    mask = {"c1": None, "all_r": np.ones(Hq, np.uint8), "one_r": np.eye(1, Hq, 0, dtype=np.uint8)[0]}.get(kind)
+    if kind == "mixed":
+        mask = (rng.random(Hq) < 0.4).astype(np.uint8)
+        mask[0] = 1
+    if mask is None:
+        mask = wl.head_type_mask(w)
+    inp = wl.make_layer(w, mask=mask, lens=np.array(lens, np.int32), l_cap=L_cap)
+    _say("block-granular layer %s" % (case,))
+    idx_in = H.previous_layer_sets(inp, k, block=64)
+    H.check_layer(ctx, inp, mask, k, idx_in, "block %s" % kind, block=64)
+    H.check_layer(ctx, inp, np.ones(Hq, np.uint8), k, None, "block all-retrieval", block=64)
+
+
+def test_block_granular_sets_with_ties_and_scattered_entries(ctx):
+    """Tied best tokens in different blocks go to the lower block; inherited sets may come
+    in any order, with -1 anywhere and with blocks that lie past the sequence."""
+    w = wl.scaled(wl.WORKLOADS["c1"], max_len=8192, k=16, planted=0)
+    inp = wl.make_layer(w, l_cap=8192)
+    _, _, sel0 = H.oracle_layer(inp, np.ones(8, np.uint8), 16, None, block=64)
+    for g in range(2):
+        best = np.argsort(-sel0[0, g, :8192], kind="stable")[:40]
+        for t in best[:20]:                          # copies of strong rows into other blocks
+            inp.k_cache[0, g, (int(t) + 64 * 31) % 8192] = inp.k_cache[0, g, int(t)]
+    H.check_layer(ctx, inp, np.ones(8, np.uint8), 16, None, "block ties", exact_sets=True, block=64)
+    idx_in = H.previous_layer_sets(inp, 16, block=64)
+    rng = np.random.default_rng(3)
+    for g in range(2):
+        row = idx_in[0, g].copy()
+        gone = rng.choice(16, 5, replace=False)
+        row[gone] = -1
+        row[gone[0]] = 1000                          # a block past the 128 blocks of the sequence
+        rng.shuffle(row)
+        idx_in[0, g] = row
+    dl = H.DeviceLayer(inp, 16, idx_in, block=64)
+    out_gpu, idx_gpu = H.run_hybrid(ctx, dl, inp.mask)
+    # the oracle wants valid entries first: same sets, compacted
+    idx_ref_in = np.full_like(idx_in, -1)
+    for g in range(2):
+        v = idx_in[0, g][(idx_in[0, g] >= 0) & (idx_in[0, g] < 128)]
+        idx_ref_in[0, g, :v.size] = v
+    out_ref, _, _ = H.oracle_layer(inp, inp.mask, 16, idx_ref_in, block=64)
+    H.assert_outputs_close(out_gpu, out_ref, "block scattered sets")
+
+
+@pytest.mark.parametrize("mode", ["phased", "layerwise"])
+def test_block_granular_decode_step(ctx, mode):
+    lb = H.binding()
+    n_layers, k = 5, 12
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=6000, k=k, n_layers=n_layers, planted=32)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=6000) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx, block=64)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 6000, k, kv=layers[0].k_cache, block_size=64)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda")
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    _say("block-granular %s step" % mode)
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED if mode == "phased" else lb.STEP_LAYERWISE)
+    try:
+        ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                        [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "block step layer %d" % l)
+    got = idx_final.cpu().numpy()
+    G = w.group
+    for g in range(w.n_kv_heads):
+        if layers[-1].mask[g * G:(g + 1) * G].any():
+            ok, _, msg = H.index_sets_match(got[0, g], refs[-1][1][0, g],
+                                            H.unit_scores(refs[-1][2][0, g], 6000, 64), k, H.TIE_REL)
+            assert ok, msg
+        else:
+            assert (got[0, g] == refs[-1][1][0, g]).all()
