@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--k", type=int, default=0, help="override the budget (the c5 sweep)")
     ap.add_argument("--retrieval", type=int, default=0, help="override the retrieval heads per layer (the c5 sweep)")
+    ap.add_argument("--ks", default="", metavar="BATCH,CONTEXT,SPARSE_GROUPS",
+                    help="the kernel-study shape of Sec. 4.3.2 instead of a named workload "
+                         "(one layer, block size 64, 90 %% block sparsity), e.g. 8,131072,8")
     ap.add_argument("--block", action="store_true",
                     help="block-granular sets (App. C): the budget becomes k/64 blocks of 64 positions")
     ap.add_argument("--wg-per-cu", type=int, default=0)
@@ -69,7 +72,12 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    w = wl.WORKLOADS[args.workload]
+    if args.ks:
+        ks_batch, ks_ctx, ks_sparse = (int(x) for x in args.ks.split(","))
+        w = wl.kernel_study(ks_batch, ks_ctx, ks_sparse)
+        args.block = True
+    else:
+        w = wl.WORKLOADS[args.workload]
     if args.k:
         w = wl.scaled(w, k=args.k)
     if args.retrieval:
@@ -91,7 +99,7 @@ def main() -> int:
     lens_h = layers[0].lengths
     lens = torch.from_numpy(lens_h).to(dev)
     unit = 64 if args.block else 1          # positions one set entry names
-    k_set = max(1, w.k // unit)             # entries per set
+    k_set = w.k if args.ks else max(1, w.k // unit)   # entries per set (the study's k counts blocks)
     shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, k_set, kv=layers[0].k_cache,
                           block_size=unit)
     ws = lb.alloc_workspace(shape, dev, n_layers=n_layers)
@@ -102,6 +110,12 @@ def main() -> int:
         idx0_h = np.tile(np.arange(k_set, dtype=np.int32), (w.batch, w.n_kv_heads, 1))
         for b in range(w.batch):
             idx0_h[b] = np.minimum(idx0_h[b], (int(lens_h[b]) - 1) // unit)
+        if args.ks:             # a seeded tenth of the blocks per (sequence, KV head), ascending
+            rng = np.random.Generator(np.random.Philox(key=wl.BASE_SEED + 6))
+            n_units = (w.max_len + unit - 1) // unit
+            for b in range(w.batch):
+                for g in range(w.n_kv_heads):
+                    idx0_h[b, g] = np.sort(rng.choice(n_units, size=k_set, replace=False))
         idx0 = torch.from_numpy(idx0_h).to(dev)
     qs = [ly.q for ly in layers]
     ks = [ly.k_cache for ly in layers]
@@ -168,7 +182,8 @@ def main() -> int:
     # per step: every K+V row streamed or gathered (512 B), the index sets, q and out.  Not
     # counted, although the library moves them: the threshold sample's K rows (256 B each,
     # 2048 per score row) and the candidate lists (8 B per candidate, written and read once)
-    step_bytes = sum(wl.algorithmic_bytes(w, masks[l], lens_h) for l in range(n_layers))
+    w_rows = wl.scaled(w, k=w.k * 64) if args.ks else w   # the budget in cache rows, for the byte counts
+    step_bytes = sum(wl.algorithmic_bytes(w_rows, masks[l], lens_h) for l in range(n_layers))
     dense_bytes = n_layers * wl.dense_bytes(w, lens_h)
     # per streaming launch: 512 B of K+V per streamed row, plus q
     G = w.group
@@ -178,7 +193,7 @@ def main() -> int:
         n_r = sum(1 for g in range(w.n_kv_heads) if masks[l][g * G:(g + 1) * G].any())
         n_s = sum(1 for g in range(w.n_kv_heads) if (masks[l][g * G:(g + 1) * G] == 0).any())
         rows_streamed += sum(n_r * int(L) for L in lens_h)
-        rows_gathered += sum(n_s * min(w.k, int(L)) for L in lens_h)
+        rows_gathered += sum(n_s * min(w_rows.k, int(L)) for L in lens_h)
     n_stream_launches = max(1, launches_per_step["stream"])
     if args.layerwise:          # the streaming launch of a layer also carries its gathers
         stream_bytes = (rows_streamed + rows_gathered) * 512
@@ -187,7 +202,7 @@ def main() -> int:
     stream_bytes = (stream_bytes + n_layers * w.batch * w.n_q_heads * 256) / n_stream_launches
     achieved = stream_bytes / (stream_us * 1e-6) / 1e9 if stream_us > 0 else 0.0
     default_run = args.workload == "c3" and not (args.layerwise or args.layers or args.k or args.retrieval
-                                                 or args.block)
+                                                 or args.block or args.ks)
     traffic = measured_traffic() if default_run else None
 
     result = {
@@ -203,10 +218,11 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "%s: %d layers, B%d, %dq/%dkv heads, d128, context %d, k %d, "
-                               "layer 0 all-retrieval then %d retrieval heads per layer" % (
-                                   w.name, n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.max_len,
-                                   w.k, w.n_retrieval),
+        "config": {"workload": "%s: %d layers, B%d, %dq/%dkv heads, d128, context %d, k %d, %s" % (
+                                   w.name, n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, w.k,
+                                   "layer 0 all-retrieval then %d retrieval heads per layer" % w.n_retrieval
+                                   if w.first_layer_all_retrieval else
+                                   "%d retrieval heads" % int(masks[0].sum())),
                    "step_mode": "layerwise" if args.layerwise else "phased",
                    "sets": "blocks of 64 positions" if args.block else "positions"},
         "step_algorithmic_bytes": step_bytes,

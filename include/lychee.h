@@ -146,7 +146,8 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
  *   LYCHEE_STEP_LAYERWISE  layer after layer, each as lychee_decode_attn (three dependent
  *     launches); out[l] is complete before layer l+1 starts, as a model that computes
  *     q[l+1] from out[l] needs.
- * Fewer than 128 layers; PHASED falls back to LAYERWISE when n_layers * batch > 2048.
+ * Fewer than 128 layers; PHASED falls back to LAYERWISE when n_layers * batch > 2048, and a
+ * single layer always runs as lychee_decode_attn does.
  */
 int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
                        const void *const *q, const void *const *k_cache,

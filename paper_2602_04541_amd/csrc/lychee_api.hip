@@ -544,7 +544,9 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
 
-    const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && (int64_t)n_layers * shape->batch <= kMaxItems;
+    // (a single layer has nothing to pool across layers: its streaming and gather share a launch)
+    const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && n_layers > 1 &&
+                        (int64_t)n_layers * shape->batch <= kMaxItems;
     if (!phased) {
         for (int l = 0; l < n_layers; ++l)
             if ((rc = run_layer(L, l, l < n_select)) != LYCHEE_OK) return rc;
@@ -611,7 +613,7 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    if (ctx->step_mode != LYCHEE_STEP_PHASED || (int64_t)n_layers * shape->batch > kMaxItems) {
+    if (ctx->step_mode != LYCHEE_STEP_PHASED || n_layers == 1 || (int64_t)n_layers * shape->batch > kMaxItems) {
         for (int l = 0; l < n_layers; ++l)
             if ((rc = run_layer(L, l, false)) != LYCHEE_OK) return rc;
         return LYCHEE_OK;

@@ -77,6 +77,17 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+def kernel_study(batch: int, context: int, sparse_groups: int) -> Workload:
+    """The shape of the paper's kernel-level study (Sec. 4.3.2): one layer, 8 KV heads (4 query
+    heads each), `sparse_groups` of the 8 KV groups entirely sparse with 90 % block sparsity
+    (block size 64: a tenth of the blocks is attended), the other groups entirely dense.
+    `k` counts blocks.  Only the shape is the paper's; values and block choices are synthetic."""
+    n_blocks = (context + 63) // 64
+    heads = tuple(h for h in range(32) if h // 4 < 8 - sparse_groups)
+    return Workload("ks_b%d_L%d_s%d" % (batch, context, sparse_groups), 6, batch, 32, 8, context,
+                    max(1, n_blocks // 10), retrieval_heads=heads, planted=0)
+
+
 def scaled(w: Workload, **changes) -> Workload:
     """A copy of a workload with some fields replaced (smaller test variants)."""
     d = dict(w.__dict__)
