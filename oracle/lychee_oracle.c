@@ -304,6 +304,25 @@ int lo_decode_attn(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int
                                idx_in, lengths, out, idx_out, sel_out, 0);
 }
 
+/* Alg. 1, "C.append(k, v)": the new token's key and value rows ([B][Hkv][d] each) become row
+ * lengths[b] - 1 of every KV head's cache (lengths count the token being decoded). */
+int lo_append_kv(int32_t B, int32_t Hkv, int32_t d, const uint16_t *k_new, const uint16_t *v_new,
+                 uint16_t *K, uint16_t *V, int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                 const int32_t *lengths)
+{
+    for (int32_t b = 0; b < B; ++b) {
+        if (lengths[b] < 1) return -1;
+        for (int32_t g = 0; g < Hkv; ++g) {
+            const int64_t at = b * stride_b + g * stride_h + (int64_t)(lengths[b] - 1) * stride_t;
+            for (int32_t i = 0; i < d; ++i) {
+                K[at + i] = k_new[((int64_t)b * Hkv + g) * d + i];
+                V[at + i] = v_new[((int64_t)b * Hkv + g) * d + i];
+            }
+        }
+    }
+    return 0;
+}
+
 /* Number of threads the (sequence, KV head) loop above spreads over. */
 int32_t lo_num_threads(void)
 {

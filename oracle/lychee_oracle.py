@@ -57,6 +57,8 @@ def _load():
         lib.lo_decode_attn_rule.restype = ctypes.c_int
         lib.lo_decode_attn_block.argtypes = lib.lo_decode_attn.argtypes + [i32, i32]
         lib.lo_decode_attn_block.restype = ctypes.c_int
+        lib.lo_append_kv.argtypes = [i32, i32, i32, u16p, u16p, u16p, u16p, i64, i64, i64, i32p]
+        lib.lo_append_kv.restype = ctypes.c_int
         lib.lo_ratio_budget.argtypes = [i32, i32, i32]
         lib.lo_ratio_budget.restype = i32
         lib.lo_topk_n.argtypes = [f64p, i32, i32, i32, i32p]
@@ -119,6 +121,24 @@ def topk(sel: np.ndarray, k: int) -> np.ndarray:
     out = np.empty(k, dtype=np.int32)
     _load().lo_topk(_ptr(sel, ctypes.c_double), sel.size, k, _ptr(out, ctypes.c_int32))
     return out
+
+
+def append_kv(k_new: np.ndarray, v_new: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray,
+              lengths: np.ndarray) -> None:
+    """Alg. 1's cache append, in place: k_new / v_new [B,Hkv,d] become row lengths[b]-1 of the
+    caches k_bits / v_bits [B,Hkv,L_cap,d] (uint16 bf16 bit patterns, writable)."""
+    kn, vn = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    assert k_bits.dtype == np.uint16 and v_bits.dtype == np.uint16 and k_bits.flags.writeable
+    assert k_bits.strides == v_bits.strides
+    B, Hkv, d = kn.shape
+    sb, sh, st, sd = (x // 2 for x in k_bits.strides)
+    assert sd == 1
+    lengths = _c(lengths, np.int32)
+    rc = _load().lo_append_kv(B, Hkv, d, _ptr(kn, ctypes.c_uint16), _ptr(vn, ctypes.c_uint16),
+                              _ptr(k_bits, ctypes.c_uint16), _ptr(v_bits, ctypes.c_uint16), sb, sh, st,
+                              _ptr(lengths, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments (rc=%d)" % rc)
 
 
 def ratio_budget(L: int, k: int, keep_ppm: int) -> int:

@@ -374,3 +374,26 @@ def test_block_of_one_is_the_token_method_and_ratio_counts_blocks():
     _, idx, _ = lo.decode_attn(q, K, V, mask, 40, None, lens, keep_ppm=250000, block=8)
     assert ((idx[0] >= 0).sum(axis=1) == 10).all()            # 300 rows = 38 blocks of 8; a quarter, rounded up
     assert ((idx[1] >= 0).sum(axis=1) == 6).all()             # 170 rows = 22 blocks; ceil(5.5) = 6
+
+
+# ------------------------------------------------------------------ the cache append of Alg. 1
+def test_append_puts_the_new_rows_at_the_last_position_of_every_head_and_nowhere_else():
+    rng = np.random.default_rng(31)
+    B, Hkv, L_cap, d = 3, 2, 20, 128
+    lens = np.array([20, 1, 7], np.int32)
+    K = round_to_bf16_bits(rng.standard_normal((B, Hkv, L_cap, d)))
+    V = round_to_bf16_bits(rng.standard_normal((B, Hkv, L_cap, d)))
+    kn = round_to_bf16_bits(rng.standard_normal((B, Hkv, d)))
+    vn = round_to_bf16_bits(rng.standard_normal((B, Hkv, d)))
+    K2, V2 = K.copy(), V.copy()
+    lo.append_kv(kn, vn, K2, V2, lens)
+    want_k, want_v = K.copy(), V.copy()
+    for b in range(B):
+        want_k[b, :, lens[b] - 1] = kn[b]          # numpy indexing, not the oracle's loop
+        want_v[b, :, lens[b] - 1] = vn[b]
+    assert (K2 == want_k).all() and (V2 == want_v).all()
+    # token-major storage: same logical result through other strides
+    Kt = np.ascontiguousarray(K.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    Vt = np.ascontiguousarray(V.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    lo.append_kv(kn, vn, Kt, Vt, lens)
+    assert (Kt == want_k).all() and (Vt == want_v).all()
