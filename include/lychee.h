@@ -156,6 +156,27 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
                        const int32_t *lengths, void *workspace, size_t workspace_bytes,
                        void *hip_stream);
 
+/* Alg. 1, "C.append(k, v)": the decoded token's key and value rows
+ *   k_new, v_new   bf16 [B][H_kv][128], 16-byte aligned
+ * become row lengths[b] - 1 of every KV head of k_cache / v_cache (strided as in `shape`; lengths
+ * count the token being decoded).  One small launch on the stream; needs no workspace. */
+int lychee_append_kv(lychee_ctx *ctx, const lychee_shape *shape, const void *k_new,
+                     const void *v_new, void *k_cache, void *v_cache, const int32_t *lengths,
+                     void *hip_stream);
+
+/* lychee_decode_step with each layer's cache append inside the call (Alg. 1: append, then
+ * attend): k_new[l], v_new[l] (HOST arrays of n_layers device pointers, each bf16 [B][H_kv][128])
+ * are written to row lengths[b] - 1 of layer l's caches before any of the step's attention
+ * reads them.  The appends ride in the step's first launch (the selection thresholds, whose
+ * sample never touches the newest row), so they cost no launch of their own; with block-granular
+ * sets, which need no thresholds, they are one small launch. */
+int lychee_decode_step_append(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
+                              const void *const *q, const void *const *k_new,
+                              const void *const *v_new, void *const *k_cache, void *const *v_cache,
+                              const uint8_t *head_type_masks, const int32_t *idx_in,
+                              void *const *out, int32_t *idx_out, const int32_t *lengths,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Dense attention for all layers of a step (Eq. 1 and o = A V for every head, no selection), in
  * the order STEP_MODE names: PHASED = all layers' streaming pooled in one launch, then the
  * combines; LAYERWISE = layer after layer as lychee_dense_decode_attn.  The in-run baseline of

@@ -27,7 +27,7 @@ EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
     "lychee_step_workspace_bytes",
     "lychee_decode_attn", "lychee_dense_decode_attn", "lychee_decode_step",
-    "lychee_dense_decode_step",
+    "lychee_dense_decode_step", "lychee_decode_step_append", "lychee_append_kv",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
 ]
@@ -67,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.lychee_dense_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_dense_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lychee_decode_step_append.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lychee_append_kv.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp]
     lib.lychee_validate_idx.argtypes = [vp, shp, vp, vp, ctypes.POINTER(i64), vp]
     lib.lychee_set_option.argtypes = [vp, i32, i32]
     lib.lychee_timing_enable.argtypes = [vp, ctypes.c_int]
@@ -193,6 +195,24 @@ class Context:
                                        _ptr(lengths), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(),
                                        _stream(stream)), "lychee_decode_step")
+
+    def decode_step_append(self, shape: Shape, q: Sequence, k_new: Sequence, v_new: Sequence,
+                           k_cache: Sequence, v_cache: Sequence, head_type_masks: np.ndarray, idx_in,
+                           out: Sequence, idx_out, lengths, workspace, stream=None) -> None:
+        n = len(q)
+        arr = ctypes.c_void_p * n
+        masks = np.ascontiguousarray(head_type_masks, dtype=np.uint8)
+        assert masks.shape == (n, shape.n_q_heads)
+        _check(_lib.lychee_decode_step_append(
+            self._h, ctypes.byref(shape), n, arr(*[_ptr(t) for t in q]), arr(*[_ptr(t) for t in k_new]),
+            arr(*[_ptr(t) for t in v_new]), arr(*[_ptr(t) for t in k_cache]),
+            arr(*[_ptr(t) for t in v_cache]), masks.ctypes.data, _ptr(idx_in),
+            arr(*[_ptr(t) for t in out]), _ptr(idx_out), _ptr(lengths), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream)), "lychee_decode_step_append")
+
+    def append_kv(self, shape: Shape, k_new, v_new, k_cache, v_cache, lengths, stream=None) -> None:
+        _check(_lib.lychee_append_kv(self._h, ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                     _ptr(v_cache), _ptr(lengths), _stream(stream)), "lychee_append_kv")
 
     def dense_decode_step(self, shape: Shape, q: Sequence, k_cache: Sequence, v_cache: Sequence,
                           out: Sequence, lengths, workspace, stream=None) -> None:

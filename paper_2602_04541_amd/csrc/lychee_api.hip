@@ -225,7 +225,7 @@ const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &d
 
 struct Ranges {
     int r_first = 0, r_count = 0, g_first = 0, g_count = 0, c_first = 0, c_count = 0;
-    int t_first = 0, t_count = 0, s_first = 0, s_count = 0;
+    int t_first = 0, t_count = 0, s_first = 0, s_count = 0, a_first = 0, a_count = 0;
 };
 
 hipEvent_t take_event(lychee_ctx *ctx)
@@ -256,7 +256,7 @@ struct Launcher {
     }
     int go(const Ranges &r) const
     {
-        if (r.r_count + r.g_count + r.c_count + r.t_count + r.s_count == 0) return LYCHEE_OK;
+        if (r.r_count + r.g_count + r.c_count + r.t_count + r.s_count + r.a_count == 0) return LYCHEE_OK;
 #ifdef LYCHEE_TRACE
         {   // trace builds: LYCHEE_TRACE_STOP=n drops every launch after the n-th of a call
             static int budget = -1, left = 0;
@@ -302,12 +302,13 @@ struct Launcher {
         p.r_first = r.r_first, p.r_count = r.r_count;
         p.g_first = r.g_first, p.g_count = r.g_count;
         p.c_first = r.c_first, p.c_count = r.c_count;
+        p.a_first = r.a_first, p.a_count = r.a_count;
         p.t_first = r.t_first, p.t_count = r.t_count;
         p.s_first = r.s_first, p.s_count = r.s_count;
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.collect |= host_table[l].emit_sel;
         for (int l = r.s_first; l < r.s_first + r.s_count; ++l) p.selects |= host_table[l].n_rgroups > 0;
         const int cls = r.r_count ? LYCHEE_KERNEL_STREAM : r.g_count ? LYCHEE_KERNEL_GATHER
-                        : r.t_count ? LYCHEE_KERNEL_THRESHOLD : r.c_count ? LYCHEE_KERNEL_COMBINE
+                        : (r.t_count || r.a_count) ? LYCHEE_KERNEL_THRESHOLD : r.c_count ? LYCHEE_KERNEL_COMBINE
                         : LYCHEE_KERNEL_SELECT;
         if (!ctx->timing) return launch_units(p, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
         lychee_ctx::Rec rec{cls, take_event(ctx), take_event(ctx)};
@@ -320,16 +321,15 @@ struct Launcher {
     }
 };
 
-// Layer `l` of the table, dependent launches: T (only when the layer selects), then R+G,
-// then S+C.
+// Layer `l` of the table, dependent launches: T (only when the layer selects; the cache append,
+// if the layer has one, rides along or goes alone), then R+G, then S+C.
 int run_layer(const Launcher &L, int l, bool select)
 {
     int rc;
-    if (select && L.s.block_size != 64) {  // block scores need no threshold: every block is ranked
-        Ranges t;
-        t.t_first = l, t.t_count = 1;
-        if ((rc = L.go(t)) != LYCHEE_OK) return rc;
-    }
+    Ranges t;
+    if (select && L.s.block_size != 64) t.t_first = l, t.t_count = 1;  // block scores need no threshold
+    if (L.host_table[l].k_new != nullptr) t.a_first = l, t.a_count = 1;
+    if ((rc = L.go(t)) != LYCHEE_OK) return rc;
     Ranges a;
     a.r_first = a.g_first = l, a.r_count = a.g_count = 1;
     if ((rc = L.go(a)) != LYCHEE_OK) return rc;
@@ -337,6 +337,127 @@ int run_layer(const Launcher &L, int l, bool select)
     b.c_first = l, b.c_count = 1;
     if (select) b.s_first = l, b.s_count = 1;
     return L.go(b);
+}
+
+int check_step_pointers(int32_t n_layers, const void *const *q, const void *const *k_cache,
+                        const void *const *v_cache, void *const *out)
+{
+    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr) return LYCHEE_EINVAL;
+    for (int l = 0; l < n_layers; ++l) {
+        if (q[l] == nullptr || k_cache[l] == nullptr || v_cache[l] == nullptr || out[l] == nullptr)
+            return LYCHEE_EINVAL;
+        if (!aligned(q[l], 16) || !aligned(k_cache[l], 16) || !aligned(v_cache[l], 16) || !aligned(out[l], 16))
+            return LYCHEE_EINVAL;
+    }
+    return LYCHEE_OK;
+}
+
+// The hybrid decode step; k_new / v_new (both or neither) add each layer's cache append.
+int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, const void *const *q,
+                const void *const *k_new, const void *const *v_new, const void *const *k_cache,
+                const void *const *v_cache, const uint8_t *head_type_masks, const int32_t *idx_in,
+                void *const *out, int32_t *idx_out, const int32_t *lengths, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    if (n_layers < 1 || n_layers >= kMaxLayers) return n_layers < 1 ? LYCHEE_EINVAL : LYCHEE_EUNSUPPORTED;
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, n_layers);
+    if (rc != LYCHEE_OK) return rc;
+    if (head_type_masks == nullptr || lengths == nullptr) return LYCHEE_EINVAL;
+    if ((rc = check_step_pointers(n_layers, q, k_cache, v_cache, out)) != LYCHEE_OK) return rc;
+    if ((k_new == nullptr) != (v_new == nullptr)) return LYCHEE_EINVAL;
+    if (!aligned(idx_in, 4) || !aligned(idx_out, 4) || !aligned(lengths, 4)) return LYCHEE_EINVAL;
+    if (idx_in != nullptr && idx_in == idx_out) return LYCHEE_EINVAL;
+    for (int l = 0; l < n_layers; ++l) {
+        if (k_new != nullptr && (k_new[l] == nullptr || v_new[l] == nullptr || !aligned(k_new[l], 16) ||
+                                 !aligned(v_new[l], 16)))
+            return LYCHEE_EINVAL;
+        // only layer 0 can lack an inherited set: every later layer receives the previous one's
+        rc = check_mask(shape, head_type_masks + (size_t)l * shape->n_q_heads, l > 0 || idx_in != nullptr);
+        if (rc != LYCHEE_OK) return rc;
+    }
+    if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, n_layers);
+    char *ws = static_cast<char *>(workspace);
+
+    // Layer l writes the sets of its retrieval groups into its own array; a KV head whose
+    // group holds no retrieval head keeps reading the array of the last layer that selected
+    // for it (Sec. 3.1: the set is propagated unchanged), so nothing is copied between layers.
+    // Entry n_layers of the table only assembles the caller's idx_out from those arrays.
+    const bool assemble = idx_out != nullptr;
+    // the last layer's selection is only needed if the caller wants the final sets
+    const int n_select = assemble ? n_layers : n_layers - 1;
+    std::vector<LayerDesc> descs((size_t)n_layers + 1);
+    const int32_t *cur[kMaxKvHeads];
+    for (int g = 0; g < shape->n_kv_heads; ++g) cur[g] = idx_in;
+    for (int l = 0; l < n_layers; ++l) {
+        LayerDesc &d = descs[l];
+        memset(&d, 0, sizeof d);
+        d.q = static_cast<const uint16_t *>(q[l]);
+        d.k_cache = static_cast<const uint16_t *>(k_cache[l]);
+        d.v_cache = static_cast<const uint16_t *>(v_cache[l]);
+        if (k_new != nullptr) {
+            d.k_new = static_cast<const uint16_t *>(k_new[l]);
+            d.v_new = static_cast<const uint16_t *>(v_new[l]);
+        }
+        d.out = static_cast<uint16_t *>(out[l]);
+        set_groups(d, *shape, head_type_masks + (size_t)l * shape->n_q_heads);
+        set_scratch(d, w, ws, l);
+        d.idx_out = idx_set_of(w, ws, l);
+        for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = cur[g];
+        d.emit_sel = l < n_select;
+#ifdef LYCHEE_TRACE
+        if (getenv("LYCHEE_TRACE_NOSEL")) d.emit_sel = 0;  // trace builds: cost of collecting candidates
+#endif
+        d.copy_keep = 0;
+        for (int i = 0; i < d.n_rgroups; ++i) cur[d.rgroup[i]] = d.idx_out;
+    }
+    LayerDesc &fin = descs[n_layers];
+    memset(&fin, 0, sizeof fin);
+    for (int g = 0; g < shape->n_kv_heads; ++g) {
+        fin.rindex[g] = 0xFF;
+        fin.idx_src[g] = cur[g];
+    }
+    fin.idx_out = idx_out;
+    fin.copy_keep = 1;
+
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
+
+    // (a single layer has nothing to pool across layers: its streaming and gather share a launch)
+    const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && n_layers > 1 &&
+                        (int64_t)n_layers * shape->batch <= kMaxItems;
+    if (!phased) {
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = run_layer(L, l, l < n_select)) != LYCHEE_OK) return rc;
+    } else {
+        // All layers at once, one launch per phase; each phase needs only earlier phases:
+        //   A + T (appends, thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
+        Ranges t;
+        t.t_first = 0, t.t_count = shape->block_size == 64 ? 0 : n_select;
+        if (k_new != nullptr) t.a_first = 0, t.a_count = n_layers;
+        if ((rc = L.go(t)) != LYCHEE_OK) return rc;
+        Ranges r;
+        r.r_first = 0, r.r_count = n_layers;
+        if ((rc = L.go(r)) != LYCHEE_OK) return rc;
+        Ranges sl;
+        sl.s_first = 0, sl.s_count = n_select;
+        if ((rc = L.go(sl)) != LYCHEE_OK) return rc;
+        Ranges g;
+        g.g_first = 0, g.g_count = n_layers;
+        if ((rc = L.go(g)) != LYCHEE_OK) return rc;
+        Ranges c;
+        c.c_first = 0, c.c_count = n_layers;
+        if (assemble) c.s_first = n_layers, c.s_count = 1;  // the set copies ride along
+        if ((rc = L.go(c)) != LYCHEE_OK) return rc;
+    }
+    if (assemble && !phased) {
+        Ranges f;
+        f.s_first = n_layers, f.s_count = 1;
+        if ((rc = L.go(f)) != LYCHEE_OK) return rc;
+    }
+    return LYCHEE_OK;
 }
 
 }  // namespace
@@ -480,102 +601,49 @@ int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_lay
                        const int32_t *lengths, void *workspace, size_t workspace_bytes,
                        void *hip_stream)
 {
-    if (n_layers < 1 || n_layers >= kMaxLayers) return n_layers < 1 ? LYCHEE_EINVAL : LYCHEE_EUNSUPPORTED;
-    int rc = check_common(ctx, shape, workspace, workspace_bytes, n_layers);
+    return decode_step(ctx, shape, n_layers, q, nullptr, nullptr, k_cache, v_cache, head_type_masks, idx_in, out,
+                       idx_out, lengths, workspace, workspace_bytes, hip_stream);
+}
+
+int lychee_decode_step_append(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
+                              const void *const *q, const void *const *k_new,
+                              const void *const *v_new, void *const *k_cache, void *const *v_cache,
+                              const uint8_t *head_type_masks, const int32_t *idx_in,
+                              void *const *out, int32_t *idx_out, const int32_t *lengths,
+                              void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (k_new == nullptr || v_new == nullptr) return LYCHEE_EINVAL;
+    return decode_step(ctx, shape, n_layers, q, k_new, v_new, k_cache, v_cache, head_type_masks, idx_in, out,
+                       idx_out, lengths, workspace, workspace_bytes, hip_stream);
+}
+
+int lychee_append_kv(lychee_ctx *ctx, const lychee_shape *shape, const void *k_new, const void *v_new,
+                     void *k_cache, void *v_cache, const int32_t *lengths, void *hip_stream)
+{
+    if (ctx == nullptr) return LYCHEE_EINVAL;
+    int rc = check_shape(shape);
     if (rc != LYCHEE_OK) return rc;
-    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr ||
-        head_type_masks == nullptr || lengths == nullptr)
+    if (k_new == nullptr || v_new == nullptr || k_cache == nullptr || v_cache == nullptr || lengths == nullptr)
         return LYCHEE_EINVAL;
-    if (!aligned(idx_in, 4) || !aligned(idx_out, 4) || !aligned(lengths, 4)) return LYCHEE_EINVAL;
-    if (idx_in != nullptr && idx_in == idx_out) return LYCHEE_EINVAL;
-    for (int l = 0; l < n_layers; ++l) {
-        if (q[l] == nullptr || k_cache[l] == nullptr || v_cache[l] == nullptr || out[l] == nullptr)
-            return LYCHEE_EINVAL;
-        if (!aligned(q[l], 16) || !aligned(k_cache[l], 16) || !aligned(v_cache[l], 16) ||
-            !aligned(out[l], 16))
-            return LYCHEE_EINVAL;
-        // only layer 0 can lack an inherited set: every later layer receives the previous one's
-        rc = check_mask(shape, head_type_masks + (size_t)l * shape->n_q_heads, l > 0 || idx_in != nullptr);
-        if (rc != LYCHEE_OK) return rc;
-    }
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) ||
+        !aligned(lengths, 4))
+        return LYCHEE_EINVAL;
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const Workspace w = carve(*shape, n_layers);
-    char *ws = static_cast<char *>(workspace);
-
-    // Layer l writes the sets of its retrieval groups into its own array; a KV head whose
-    // group holds no retrieval head keeps reading the array of the last layer that selected
-    // for it (Sec. 3.1: the set is propagated unchanged), so nothing is copied between layers.
-    // Entry n_layers of the table only assembles the caller's idx_out from those arrays.
-    const bool assemble = idx_out != nullptr;
-    // the last layer's selection is only needed if the caller wants the final sets
-    const int n_select = assemble ? n_layers : n_layers - 1;
-    std::vector<LayerDesc> descs((size_t)n_layers + 1);
-    const int32_t *cur[kMaxKvHeads];
-    for (int g = 0; g < shape->n_kv_heads; ++g) cur[g] = idx_in;
-    for (int l = 0; l < n_layers; ++l) {
-        LayerDesc &d = descs[l];
-        memset(&d, 0, sizeof d);
-        d.q = static_cast<const uint16_t *>(q[l]);
-        d.k_cache = static_cast<const uint16_t *>(k_cache[l]);
-        d.v_cache = static_cast<const uint16_t *>(v_cache[l]);
-        d.out = static_cast<uint16_t *>(out[l]);
-        set_groups(d, *shape, head_type_masks + (size_t)l * shape->n_q_heads);
-        set_scratch(d, w, ws, l);
-        d.idx_out = idx_set_of(w, ws, l);
-        for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = cur[g];
-        d.emit_sel = l < n_select;
-#ifdef LYCHEE_TRACE
-        if (getenv("LYCHEE_TRACE_NOSEL")) d.emit_sel = 0;  // trace builds: cost of collecting candidates
-#endif
-        d.copy_keep = 0;
-        for (int i = 0; i < d.n_rgroups; ++i) cur[d.rgroup[i]] = d.idx_out;
-    }
-    LayerDesc &fin = descs[n_layers];
-    memset(&fin, 0, sizeof fin);
-    for (int g = 0; g < shape->n_kv_heads; ++g) {
-        fin.rindex[g] = 0xFF;
-        fin.idx_src[g] = cur[g];
-    }
-    fin.idx_out = idx_out;
-    fin.copy_keep = 1;
-
+    std::vector<LayerDesc> descs(1);
+    LayerDesc &d = descs[0];
+    memset(&d, 0, sizeof d);
+    d.k_cache = static_cast<const uint16_t *>(k_cache);
+    d.v_cache = static_cast<const uint16_t *>(v_cache);
+    d.k_new = static_cast<const uint16_t *>(k_new);
+    d.v_new = static_cast<const uint16_t *>(v_new);
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
+    const Workspace w = carve(*shape, 1);
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-
-    // (a single layer has nothing to pool across layers: its streaming and gather share a launch)
-    const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && n_layers > 1 &&
-                        (int64_t)n_layers * shape->batch <= kMaxItems;
-    if (!phased) {
-        for (int l = 0; l < n_layers; ++l)
-            if ((rc = run_layer(L, l, l < n_select)) != LYCHEE_OK) return rc;
-    } else {
-        // All layers at once, one launch per phase; each phase needs only earlier phases:
-        //   T (thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
-        Ranges t;
-        t.t_first = 0, t.t_count = shape->block_size == 64 ? 0 : n_select;
-        if ((rc = L.go(t)) != LYCHEE_OK) return rc;
-        Ranges r;
-        r.r_first = 0, r.r_count = n_layers;
-        if ((rc = L.go(r)) != LYCHEE_OK) return rc;
-        Ranges sl;
-        sl.s_first = 0, sl.s_count = n_select;
-        if ((rc = L.go(sl)) != LYCHEE_OK) return rc;
-        Ranges g;
-        g.g_first = 0, g.g_count = n_layers;
-        if ((rc = L.go(g)) != LYCHEE_OK) return rc;
-        Ranges c;
-        c.c_first = 0, c.c_count = n_layers;
-        if (assemble) c.s_first = n_layers, c.s_count = 1;  // the set copies ride along
-        if ((rc = L.go(c)) != LYCHEE_OK) return rc;
-    }
-    if (assemble && !phased) {
-        Ranges f;
-        f.s_first = n_layers, f.s_count = 1;
-        if ((rc = L.go(f)) != LYCHEE_OK) return rc;
-    }
-    return LYCHEE_OK;
+    Ranges a;
+    a.a_first = 0, a.a_count = 1;
+    return L.go(a);
 }
 
 int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,

@@ -56,6 +56,8 @@ struct Common {
 // memory; a launch names the layer ranges its unit kinds cover.
 struct LayerDesc {
     const uint16_t *q, *k_cache, *v_cache;
+    const uint16_t *k_new, *v_new;  // bf16 [B][H_kv][128]: the decoded token's rows, appended to the
+                                    // caches by an A unit (nullptr: the caller has appended them)
     uint16_t *out;         // bf16 [B][H_q][128]
     float *sel;            // [B][n_rgroups][sel_stride] pooled selection scores (scaled logits),
                            // written only for a row whose candidate list cannot be used
@@ -85,6 +87,7 @@ struct LaunchPlan {
     int32_t r_first, r_count;    // retrieval streaming
     int32_t g_first, g_count;    // sparse gather
     int32_t c_first, c_count;    // combine
+    int32_t a_first, a_count;    // cache append
     int32_t t_first, t_count;    // selection thresholds
     int32_t s_first, s_count;    // select (and set copies)
     int32_t collect;             // some R layer of the launch collects selection candidates

@@ -804,7 +804,8 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     __syncthreads();
 
     constexpr int kBatch = 8;  // tiles a wavefront has in flight
-    const int stratum = L / n_tiles;  // >= 32
+    // (strata cover rows 0 .. L-2: the newest row may be being appended in this very launch)
+    const int stratum = (L - 1) / n_tiles;  // >= 32
     for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
         uint4 kr[kBatch][4];
 #pragma unroll
@@ -1049,6 +1050,25 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
     TRACE(4);
 }
 
+// A unit of one layer (Alg. 1, "C.append(k, v)"): the decoded token's key and value rows become
+// row L_b - 1 of every KV head's cache.  16 lanes move one 256-byte row.
+__device__ __forceinline__ void append_unit(const Common &c, const LayerDesc &p)
+{
+    const int ch = threadIdx.x & 15;
+    const int n_rows = c.batch * c.n_kv_heads * 2;  // K rows, then V rows
+    for (int r = threadIdx.x >> 4; r < n_rows; r += kThreads >> 4) {
+        const int which = r / (c.batch * c.n_kv_heads);
+        const int bg = r % (c.batch * c.n_kv_heads);
+        const int b = bg / c.n_kv_heads, g = bg % c.n_kv_heads;
+        const int L = clamp_len(c.lengths[b], c.max_len);
+        const uint16_t *src = (which ? p.v_new : p.k_new) + (int64_t)bg * kHeadDim + ch * 8;
+        const uint16_t *dst = (which ? p.v_cache : p.k_cache) + (int64_t)b * c.stride_b +
+                              (int64_t)g * c.stride_h + (int64_t)(L - 1) * c.stride_t + ch * 8;
+        const uint4 v = gload_u4(src);
+        *(LYCHEE_GLOBAL u32x4_t *)const_cast<uint16_t *>(dst) = u32x4_t{v.x, v.y, v.z, v.w};
+    }
+}
+
 // The set of a KV head (b, g) whose group holds no retrieval head is handed on unchanged
 // (Sec. 3.1): a verbatim copy.
 __device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &p, int b, int g)
@@ -1152,10 +1172,10 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
     const int W = c.n_wg;
     TRACE(0);
 
-    // Kinds in a fixed order (S on retrieval groups, C, T, S set copies); within a kind layer
-    // by layer.
+    // Kinds in a fixed order (S on retrieval groups, C, T, S set copies, A); within a kind
+    // layer by layer.
     {
-        uint32_t cnt[4] = {0, 0, 0, 0};
+        uint32_t cnt[5] = {0, 0, 0, 0, 0};
         const int t = threadIdx.x;
         if (t < P.s_count) {
             const LayerDesc &L = layers[P.s_first + t];
@@ -1164,15 +1184,18 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
         }
         if (t < P.c_count) cnt[1] = (uint32_t)(c.batch * c.n_q_heads);
         if (t < P.t_count) cnt[2] = (uint32_t)(c.batch * layers[P.t_first + t].n_rgroups);
-        uint32_t tot[4];
+        if (t < P.a_count) cnt[4] = 1u;
+        uint32_t tot[5];
 #pragma unroll
-        for (int kd = 0; kd < 4; ++kd) {
+        for (int kd = 0; kd < 5; ++kd) {
             const uint32_t incl = block_scan(cnt[kd], pool.scan, tot[kd]);
-            if (t < kMaxLayers) pool.upre[kd][t + 1] = (int32_t)incl;
-            if (t == 0) pool.upre[kd][0] = 0;
+            if (kd < 4) {
+                if (t < kMaxLayers) pool.upre[kd][t + 1] = (int32_t)incl;
+                if (t == 0) pool.upre[kd][0] = 0;
+            }
         }
         __syncthreads();
-        const int n_small = (int)(tot[0] + tot[1] + tot[2] + tot[3]);
+        const int n_small = (int)(tot[0] + tot[1] + tot[2] + tot[3] + tot[4]);
         for (int j = w; j < n_small; j += W) {
             int u = j;
             if (u < (int)tot[0]) {
@@ -1196,8 +1219,9 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
                 case 3: threshold_unit<3>(c, L, b, rgi, su.sel, pool); break;
                 default: threshold_unit<4>(c, L, b, rgi, su.sel, pool); break;
                 }
+            } else if ((u -= (int)tot[2]) >= (int)tot[3]) {  // append: one unit per layer
+                append_unit(c, layers[P.a_first + u - (int)tot[3]]);
             } else {  // copy of the set of a KV head whose group holds no retrieval head
-                u -= (int)tot[2];
                 const int li = find_item(pool.upre[3], P.s_count, u);
                 const LayerDesc &L = layers[P.s_first + li];
                 u -= pool.upre[3][li];
@@ -1490,7 +1514,7 @@ hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
 {
     if (plan.c.n_wg < 1 || plan.c.n_wg > kMaxWg) return hipErrorInvalidValue;
     const bool pooled = plan.r_count + plan.g_count > 0;
-    const bool small = plan.t_count + plan.s_count + plan.c_count > 0;
+    const bool small = plan.t_count + plan.s_count + plan.c_count + plan.a_count > 0;
     if (pooled == small) return hipErrorInvalidValue;  // a launch carries one family of units
     const dim3 grid(plan.c.n_wg), block(kThreads);
     if (small && plan.selects)

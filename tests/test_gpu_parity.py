@@ -635,3 +635,71 @@ def test_block_granular_decode_step(ctx, mode):
             assert ok, msg
         else:
             assert (got[0, g] == refs[-1][1][0, g]).all()
+
+
+# ------------------------------------------------------------------ the cache append of Alg. 1
+@pytest.mark.parametrize("token_major", [False, True])
+def test_append_kv_writes_exactly_the_new_rows(ctx, token_major):
+    lb = H.binding()
+    B, Hkv, L_cap = 3, 4, 500
+    lens_h = np.array([500, 1, 263], np.int32)
+    g = torch.Generator().manual_seed(77)
+    def cache():
+        t = torch.randn((B, L_cap, Hkv, 128) if token_major else (B, Hkv, L_cap, 128), generator=g).to(torch.bfloat16)
+        return t.cuda().permute(0, 2, 1, 3) if token_major else t.cuda()
+    K, V = cache(), cache()
+    kn = torch.randn((B, Hkv, 128), generator=g).to(torch.bfloat16).cuda()
+    vn = torch.randn((B, Hkv, 128), generator=g).to(torch.bfloat16).cuda()
+    K_ref, V_ref = wl.bf16_bits(K).copy(), wl.bf16_bits(V).copy()
+    lo_mod = H.lo
+    lo_mod.append_kv(wl.bf16_bits(kn), wl.bf16_bits(vn), K_ref, V_ref, lens_h)
+    shape = lb.make_shape(B, 4 * Hkv, Hkv, L_cap, 16, kv=K)
+    _say("append_kv, token_major=%s" % token_major)
+    ctx.append_kv(shape, kn, vn, K, V, torch.from_numpy(lens_h).cuda())
+    torch.cuda.synchronize()
+    assert (wl.bf16_bits(K) == K_ref).all() and (wl.bf16_bits(V) == V_ref).all()
+
+
+@pytest.mark.parametrize("mode,block", [("phased", 1), ("layerwise", 1), ("phased", 64), ("layerwise", 64)])
+def test_decode_step_with_the_append_inside(ctx, mode, block):
+    lb = H.binding()
+    n_layers = 4
+    k = 8 if block == 64 else 300
+    w = wl.scaled(wl.WORKLOADS["c3"], batch=2, max_len=5000, k=k, n_layers=n_layers, planted=32,
+                  len_lo=4200, len_hi=5000)
+    lens_h = wl.lengths(w)
+    layers = [wl.make_layer(w, layer=l, device="cuda", lens=lens_h, l_cap=5000) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    # the new token's rows are taken out of the generated caches; the caches get stale rows there
+    k_new, v_new = [], []
+    for ly in layers:
+        kn = torch.stack([ly.k_cache[b, :, int(lens_h[b]) - 1] for b in range(w.batch)]).contiguous()
+        vn = torch.stack([ly.v_cache[b, :, int(lens_h[b]) - 1] for b in range(w.batch)]).contiguous()
+        k_new.append(kn)
+        v_new.append(vn)
+    idx = None
+    refs = []
+    for ly in layers:                       # the oracle sees the caches with the rows in place
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx, block=block)
+        refs.append((out_ref, idx, sel_ref))
+    want_k = [wl.bf16_bits(ly.k_cache).copy() for ly in layers]
+    for ly in layers:
+        for b in range(w.batch):
+            ly.k_cache[b, :, int(lens_h[b]) - 1] = 7.0       # what a missing append would leave behind
+            ly.v_cache[b, :, int(lens_h[b]) - 1] = -7.0
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 5000, k, kv=layers[0].k_cache, block_size=block)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    lens = torch.from_numpy(lens_h).cuda()
+    _say("decode step with append: %s, block %d" % (mode, block))
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED if mode == "phased" else lb.STEP_LAYERWISE)
+    try:
+        ctx.decode_step_append(shape, [ly.q for ly in layers], k_new, v_new, [ly.k_cache for ly in layers],
+                               [ly.v_cache for ly in layers], masks, None, outs, None, lens, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "append step layer %d" % l)
+        assert (wl.bf16_bits(layers[l].k_cache) == want_k[l]).all()
