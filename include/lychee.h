@@ -57,7 +57,11 @@ extern "C" {
 
 typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id, tuning and a small device
                                          arena for per-call descriptor tables; use one context
-                                         per stream */
+                                         per stream.  The attention calls only enqueue kernels (and
+                                         at most one host-to-device copy of a descriptor table from
+                                         the context's pinned memory), so a stream that is being
+                                         captured into a HIP graph can take them, and the graph can be
+                                         replayed while the context lives and timing is off. */
 
 /* Problem shape of one layer call (the inputs of Alg. 1 that are not tensors). */
 typedef struct lychee_shape {

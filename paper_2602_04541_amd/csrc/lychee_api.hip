@@ -28,6 +28,7 @@ struct lychee_ctx {
     int32_t tail_permille = 250;
     int32_t select_margin = 60;  // tenths of a standard deviation, see LYCHEE_OPT_SELECT_MARGIN
     uint32_t launch_seq = 0;   // pooled launches so far: picks the chunk counter
+    std::vector<int32_t> used_slots;  // counters of pooled launches that no later launch has reset yet
     bool timing = false;
     struct Rec {
         int cls;
@@ -294,7 +295,18 @@ struct Launcher {
         const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
         c.chunk_blocks = (int32_t)((seg_blocks + 191) / 192);
         if (c.chunk_blocks < 2) c.chunk_blocks = 2;
-        if (r.r_count || r.g_count) c.ticket_slot = (int32_t)(ctx->launch_seq++ % kTicketRing);
+        if (r.r_count || r.g_count) {
+            c.ticket_slot = (int32_t)(ctx->launch_seq++ % kTicketRing);
+            ctx->used_slots.push_back(c.ticket_slot);
+        } else {
+            // every call ends with a small-unit launch: it resets what the call's pooled
+            // launches counted (a pooled launch is never followed by more than this many)
+            while (c.n_clear < 4 && !ctx->used_slots.empty()) {
+                c.clear_slot[c.n_clear++] = ctx->used_slots.back();
+                ctx->used_slots.pop_back();
+            }
+            ctx->used_slots.clear();
+        }
         c.sel_margin = 0.1f * (float)ctx->select_margin;
         c.scale = (float)(1.0 / sqrt((double)kHeadDim));
         c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));

@@ -43,6 +43,9 @@ struct Common {
     int32_t part_stride;  // partial slots per head
     uint32_t *tickets;    // ring of kTicketRing chunk counters, zero except the ones in use
     int32_t ticket_slot;  // the counter of this launch; the launch also clears the opposite one
+    int32_t n_clear;      // a small-unit launch puts back to zero the counters that the pooled
+    int32_t clear_slot[4];//   launches before it used: a call leaves every counter as it found it,
+                          //   which is what lets a captured sequence of launches be replayed
     int32_t tail_permille;// share of the pooled blocks handed out dynamically, in chunks of
     int32_t chunk_blocks; //   chunk_blocks blocks, to whichever workgroup asks next
     int32_t g_block_rows; // set entries per pooled block of gather work (fewer than kBlockRows:

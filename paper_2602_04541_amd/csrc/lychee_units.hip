@@ -1171,6 +1171,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
     const int w = blockIdx.x;
     const int W = c.n_wg;
     TRACE(0);
+    if (w == 0 && (int)threadIdx.x < c.n_clear) c.tickets[c.clear_slot[threadIdx.x]] = 0u;
 
     // Kinds in a fixed order (S on retrieval groups, C, T, S set copies, A); within a kind
     // layer by layer.

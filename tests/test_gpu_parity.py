@@ -703,3 +703,60 @@ def test_decode_step_with_the_append_inside(ctx, mode, block):
     for l in range(n_layers):
         H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "append step layer %d" % l)
         assert (wl.bf16_bits(layers[l].k_cache) == want_k[l]).all()
+
+
+# ------------------------------------------------------------------ HIP graph capture and replay
+@pytest.mark.parametrize("block", [1, 64])
+def test_a_captured_decode_step_replays_correctly(ctx, block):
+    """The step's launches (and its one table upload) are captured into a graph and replayed
+    with new queries in the same buffers; every replay must equal the eager step."""
+    lb = H.binding()
+    n_layers = 10
+    k = 30 if block == 64 else 1500
+    # many layers of a medium length: the pooled streaming launch then hands out dynamic chunks,
+    # i.e. it uses a chunk counter, which a replay must find at zero again
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=20000, k=k, n_layers=n_layers, planted=64)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=20000) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 20000, k, kv=layers[0].k_cache, block_size=block)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    qs = [ly.q.clone() for ly in layers]
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda")
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+
+    def step():
+        ctx.decode_step(shape, qs, [ly.k_cache for ly in layers], [ly.v_cache for ly in layers], masks,
+                        None, outs, idx_final, lens, ws)
+
+    step()                                   # eager once: uploads the table, warms everything
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for rep in range(3):
+        _say("graph replay %d, block %d" % (rep, block))
+        for qt in qs:                        # new queries in the captured buffers
+            qt.copy_(torch.randn(qt.shape, generator=gen, device="cuda").to(torch.bfloat16))
+        for o in outs:
+            o.zero_()
+        idx_final.fill_(-9)
+        graph.replay()
+        torch.cuda.synchronize()
+        got_out = [o.clone() for o in outs]
+        got_idx = idx_final.clone()
+        step()                               # the program's own eager work between replays
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            assert torch.equal(got_out[l], outs[l]), "replay %d layer %d differs from the eager step" % (rep, l)
+        assert torch.equal(got_idx, idx_final)
+    # and the eager result is the oracle's (last queries)
+    idx = None
+    for l, ly in enumerate(layers):
+        ly.q.copy_(qs[l])
+        out_ref, idx, _ = H.oracle_layer(ly, ly.mask, k, idx, block=block)
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), out_ref, "graph step layer %d" % l)
