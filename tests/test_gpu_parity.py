@@ -760,3 +760,17 @@ def test_a_captured_decode_step_replays_correctly(ctx, block):
         ly.q.copy_(qs[l])
         out_ref, idx, _ = H.oracle_layer(ly, ly.mask, k, idx, block=block)
         H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), out_ref, "graph step layer %d" % l)
+
+
+def test_ratio_rule_counts_blocks_with_block_granular_sets(ctx):
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=2, max_len=12000, k=100, planted=16, len_lo=3000, len_hi=12000)
+    lens_h = wl.lengths(w)
+    inp = wl.make_layer(w, lens=lens_h, l_cap=12000)
+    mask = np.ones(w.n_q_heads, np.uint8)
+    _say("ratio rule on blocks: a quarter of the blocks of lengths %s" % lens_h.tolist())
+    _, _, idx_gpu, _, _, _ = H.check_layer(ctx, inp, mask, w.k, None, "ratio blocks", keep_ppm=250000, block=64)
+    for b in range(w.batch):
+        units = -(-int(lens_h[b]) // 64)
+        assert ((idx_gpu[b] >= 0).sum(axis=1) == min(w.k, -(-units * 250000 // 1000000))).all()
+    _, idx_prev, _ = H.oracle_layer(inp, mask, w.k, None, 250000, 64)
+    H.check_layer(ctx, inp, inp.mask, w.k, idx_prev, "ratio blocks hybrid", keep_ppm=250000, block=64)
