@@ -241,6 +241,9 @@ def main() -> int:
                      "avg_launch_us": round(stream_us, 2),
                      "algorithmic_bytes_per_launch": int(stream_bytes)},
         "gen_seconds": round(t_gen, 1),
+        # score rows that the select had to rank from all of their scores (threshold too high,
+        # candidate list full) in everything this process ran: time lost, not correctness
+        "select_fallbacks": list(ctx.select_stats()),
     }
     if other_sec is not None:
         # the dense kernel on identical buffers, in the same step order as `value` and in the other

@@ -195,6 +195,12 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
 int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,
                         const int32_t *lengths, int64_t *n_bad, void *hip_stream);
 
+/* Debug helper (synchronous): how many score rows, since the context was created, the select had
+ * to rank from all of their scores because the sampled threshold let fewer than the budget
+ * through (*too_few) or more than the candidate list holds (*too_many).  Both cost time, never
+ * correctness; on smooth score distributions both stay 0. */
+int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, void *hip_stream);
+
 /* Options of a context.  Results never depend on them beyond fp32 rounding order of the
  * split merge (index sets do not depend on them at all).
  *   WG_PER_CU     workgroups per compute unit in every launch (1..3, default 2)

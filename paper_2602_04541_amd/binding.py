@@ -27,7 +27,7 @@ EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
     "lychee_step_workspace_bytes",
     "lychee_decode_attn", "lychee_dense_decode_attn", "lychee_decode_step",
-    "lychee_dense_decode_step", "lychee_decode_step_append", "lychee_append_kv",
+    "lychee_dense_decode_step", "lychee_decode_step_append", "lychee_append_kv", "lychee_select_stats",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
 ]
@@ -69,6 +69,7 @@ def _load() -> ctypes.CDLL:
     lib.lychee_dense_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step_append.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_append_kv.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp]
+    lib.lychee_select_stats.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), vp]
     lib.lychee_validate_idx.argtypes = [vp, shp, vp, vp, ctypes.POINTER(i64), vp]
     lib.lychee_set_option.argtypes = [vp, i32, i32]
     lib.lychee_timing_enable.argtypes = [vp, ctypes.c_int]
@@ -226,6 +227,13 @@ class Context:
                                              _stream(stream)), "lychee_dense_decode_step")
 
     # -- helpers ------------------------------------------------------------------------
+    def select_stats(self, stream=None):
+        """(too_few, too_many): score rows the select ranked whole since the context was created."""
+        a, b = ctypes.c_int64(-1), ctypes.c_int64(-1)
+        _check(_lib.lychee_select_stats(self._h, ctypes.byref(a), ctypes.byref(b), _stream(stream)),
+               "lychee_select_stats")
+        return int(a.value), int(b.value)
+
     def validate_idx(self, shape: Shape, idx, lengths, stream=None) -> int:
         n_bad = ctypes.c_int64(-1)
         _check(_lib.lychee_validate_idx(self._h, ctypes.byref(shape), _ptr(idx), _ptr(lengths),

@@ -15,7 +15,8 @@ using namespace lychee;
 
 namespace {
 constexpr size_t kArenaBytes = 4u << 20;  // device memory for descriptor tables, per context
-constexpr size_t kArenaReserved = 256;    // its first bytes hold the ring of chunk counters
+constexpr size_t kArenaReserved = 512;    // its first bytes hold the ring of chunk counters (256 B)
+constexpr size_t kArenaStats = 256;       // and, from here, the select's fall-back counters
 }
 
 struct lychee_ctx {
@@ -289,6 +290,7 @@ struct Launcher {
         c.part_stride = kPartSlots;
         c.g_block_rows = ctx->g_block_rows;
         c.tickets = reinterpret_cast<uint32_t *>(ctx->arena_dev);
+        c.stats = reinterpret_cast<uint32_t *>(ctx->arena_dev + kArenaStats);
         c.tail_permille = ctx->tail_permille;
         // chunks small enough to level the finish times, large enough that a segment
         // never has more than ~192 of them (partial slots per head are limited)
@@ -725,6 +727,20 @@ int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_
     (void)hipFree(dev);
     if (!ok) return LYCHEE_EHIP;
     *n_bad = (int64_t)host;
+    return LYCHEE_OK;
+}
+
+int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, void *hip_stream)
+{
+    if (ctx == nullptr || too_few == nullptr || too_many == nullptr) return LYCHEE_EINVAL;
+    if (make_current(ctx) != LYCHEE_OK) return LYCHEE_EHIP;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint32_t host[2] = {0, 0};
+    if (hipMemcpyAsync(host, ctx->arena_dev + kArenaStats, sizeof host, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return LYCHEE_EHIP;
+    *too_few = host[0];
+    *too_many = host[1];
     return LYCHEE_OK;
 }
 

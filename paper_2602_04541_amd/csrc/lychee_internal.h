@@ -42,6 +42,7 @@ struct Common {
     int32_t n_wg;         // grid size of this launch
     int32_t part_stride;  // partial slots per head
     uint32_t *tickets;    // ring of kTicketRing chunk counters, zero except the ones in use
+    uint32_t *stats;      // [0] score rows ranked whole for want of candidates, [1] for a full list
     int32_t ticket_slot;  // the counter of this launch; the launch also clears the opposite one
     int32_t n_clear;      // a small-unit launch puts back to zero the counters that the pooled
     int32_t clear_slot[4];//   launches before it used: a call leaves every counter as it found it,

@@ -773,7 +773,7 @@ __device__ __forceinline__ float tile_pooled_score(const uint4 (&kr)[4], const u
 // plus sel_margin (six, unless the caller changes it) standard deviations; the streamed rows
 // that reach it are then very likely at least n and a few thousand more at most.  Whatever the sample yields, the select unit
 // checks the candidate count and ranks the whole row itself when the list cannot be used.
-// The sample is one 16-row tile at a hashed offset inside each of n_tiles equal strata.
+// The sample is one row at a hashed offset inside each of 2048 to 4096 equal strata.
 template <int NH>
 __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc &p, int b, int rgi,
                                                SharedSelect &sh, SharedPool &pool)
@@ -803,19 +803,24 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
     __syncthreads();
 
-    constexpr int kBatch = 8;  // tiles a wavefront has in flight
-    // (strata cover rows 0 .. L-2: the newest row may be being appended in this very launch)
-    const int stratum = (L - 1) / n_tiles;  // >= 32
+    constexpr int kBatch = 8;  // groups of 16 sampled rows a wavefront has in flight
+    // One row at a hashed offset in each of n_sample equal strata of rows 0 .. L-2 (the newest
+    // row may be being appended in this very launch).  Row by row, not tile by tile: scores
+    // come in runs (a passage that matters is hundreds of consecutive rows), and a sample of
+    // contiguous tiles would over- or under-count such runs far beyond its nominal deviation.
+    const int stratum = (L - 1) / n_sample;  // >= 2
     for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
         uint4 kr[kBatch][4];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const int t = t0 + u < n_tiles ? t0 + u : n_tiles - 1;
-            const uint32_t hsh = ((uint32_t)t * 2654435761u + (uint32_t)row * 40503u) >> 12;
-            const int base = t * stratum + (int)(hsh % (uint32_t)(stratum - 15));
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                kr[u][j] = gload_u4(kbase + (int64_t)(base + 4 * j + rs) * c.stride_t + ch * 8);
+            for (int j = 0; j < 4; ++j) {
+                const int i = t * 16 + 4 * j + rs;  // sample number
+                const uint32_t hsh = ((uint32_t)i * 2654435761u + (uint32_t)row * 40503u) >> 12;
+                const int pos = i * stratum + (int)(hsh % (uint32_t)stratum);
+                kr[u][j] = gload_u4(kbase + (int64_t)pos * c.stride_t + ch * 8);
+            }
         }
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
@@ -1110,6 +1115,7 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     } else {
         // too few candidates reached the threshold, or too many for the list: rank the row
         // (token-granular only: a block list is always complete)
+        if (threadIdx.x == 0) atomicAdd(c.stats + (total < n ? 0 : 1), 1u);
         float *sel = p.sel + row * c.sel_stride;
         switch (__builtin_popcount(p.rmask[g] & ((1u << c.group) - 1u))) {
         case 1: score_row_unit<1>(c, p, b, g, len, sel); break;

@@ -468,12 +468,17 @@ def test_select_routes_give_the_same_sets(ctx, margin, route):
         src[0, g] = order[w.k - 4:w.k + 4]     # duplicates of rows around the k-th score
     wl.plant_ties(inp, 3000, src)
     _say("select route: %s (margin %d)" % (route, margin))
+    few0, many0 = ctx.select_stats()
     ctx.set_option(lb.OPT_SELECT_MARGIN, margin)
     try:
         H.check_layer(ctx, inp, np.ones(w.n_q_heads, np.uint8), w.k, None, route, exact_sets=True)
         H.check_layer(ctx, inp, inp.mask, w.k, H.previous_layer_sets(inp, w.k), route, exact_sets=True)
     finally:
         ctx.set_option(lb.OPT_SELECT_MARGIN, 60)
+    few, many = ctx.select_stats()
+    # 2 score rows in the all-retrieval call, those of the masked call on top
+    n_rows = 2 + sum(1 for g in range(w.n_kv_heads) if inp.mask[g * w.group:(g + 1) * w.group].any())
+    assert (few - few0, many - many0) == {60: (0, 0), 1250: (0, 0), -1000: (n_rows, 0), 100000: (0, n_rows)}[margin]
 
 
 def test_sequence_longer_than_one_bitmap_window(ctx):
@@ -774,3 +779,22 @@ def test_ratio_rule_counts_blocks_with_block_granular_sets(ctx):
         assert ((idx_gpu[b] >= 0).sum(axis=1) == min(w.k, -(-units * 250000 // 1000000))).all()
     _, idx_prev, _ = H.oracle_layer(inp, mask, w.k, None, 250000, 64)
     H.check_layer(ctx, inp, inp.mask, w.k, idx_prev, "ratio blocks hybrid", keep_ppm=250000, block=64)
+
+
+
+def test_scores_that_come_in_runs_do_not_mislead_the_threshold(ctx):
+    """Rows that matter are consecutive in real contexts.  All the best rows sit in a few runs of
+    hundreds of rows here; the sets must be exact and no score row may need the whole-row ranking."""
+    w = wl.scaled(wl.WORKLOADS["c5"], n_q_heads=8, n_kv_heads=2, n_retrieval=0, retrieval_heads=(0, 5), k=4096)
+    inp = wl.make_layer(w, mask=np.ones(8, np.uint8))
+    rng = np.random.default_rng(17)
+    for g in range(2):
+        src = inp.planted_pos[0, g]                       # 1024 strong rows, all different
+        starts = rng.choice(np.arange(2048, 131072 - 1024, 1024), size=8, replace=False)
+        for c, s0 in enumerate(starts):                   # 8 runs of 500 consecutive strong rows
+            rows = src[(np.arange(500) + 125 * c) % src.size]
+            inp.k_cache[0, g, int(s0) + 13:int(s0) + 513] = inp.k_cache[0, g, rows]
+    few0, many0 = ctx.select_stats()
+    _say("scores in runs: 8 runs of 500 strong rows per KV head at 128K, k 4096")
+    H.check_layer(ctx, inp, np.ones(8, np.uint8), w.k, None, "runs", exact_sets=True)
+    assert ctx.select_stats() == (few0, many0)
