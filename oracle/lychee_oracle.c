@@ -33,7 +33,14 @@
  *     is the largest pooled token score inside it (so the block holding the best token is
  *     always kept), blocks are ranked like tokens (ties to the lower block), a set entry e
  *     names the positions [e*block, (e+1)*block) below the sequence length, and the budget
- *     counts blocks.  block = 1 is the token-granular method itself.
+ *     counts blocks.  block = 1 is the token-granular method itself;
+ *   - the Top-p and Threshold rules of Sec. 4.4.1 speak of attention probabilities.  Under
+ *     grouped-query attention the set is scored by the pooled query (App. F), so the
+ *     probabilities here are the softmax of the pooled logits over the whole sequence.
+ *     Threshold keeps the tokens whose probability exceeds tau; Top-p keeps the shortest
+ *     prefix of the descending order whose probabilities sum to at least p.  Both keep at
+ *     least the best token and at most k (the capacity of a set) - the k best, if the rule
+ *     would keep more - and both break ties like Eq. 2 does.
  *
  * Every function is a direct loop nest: no blocking, no fusion, no reordering.
  * OpenMP only spreads the independent (sequence, KV head) pairs over cores.
@@ -159,6 +166,36 @@ void lo_topk_n(const double *sel, int32_t L, int32_t n, int32_t k, int32_t *idx_
     free(all);
 }
 
+/* How many positions the Threshold rule (rule 1: probability > param) or the Top-p rule (rule 2:
+ * shortest descending prefix with probability mass >= param) keeps among L pooled logits, before
+ * the clamp to [1, min(k, L)].  Probabilities are softmax(sel) over all L positions. */
+int32_t lo_rule_count(const double *sel, int32_t L, int32_t rule, double param)
+{
+    double m = sel[0];
+    for (int32_t t = 1; t < L; ++t)
+        if (sel[t] > m) m = sel[t];
+    double z = 0.0;
+    for (int32_t t = 0; t < L; ++t) z += exp(sel[t] - m);
+    if (rule == 1) {
+        int32_t n = 0;
+        for (int32_t t = 0; t < L; ++t)
+            if (exp(sel[t] - m) / z > param) ++n;
+        return n;
+    }
+    /* rule 2: walk down the sorted order */
+    scored_pos *all = malloc((size_t)L * sizeof *all);
+    for (int32_t t = 0; t < L; ++t) {
+        all[t].s = sel[t];
+        all[t].t = t;
+    }
+    qsort(all, (size_t)L, sizeof *all, by_score_desc_then_pos);
+    double cum = 0.0;
+    int32_t n = 0;
+    while (n < L && cum < param) cum += exp(all[n++].s - m) / z;
+    free(all);
+    return n;
+}
+
 /* Eq. 2 with the fixed budget k. */
 void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
 {
@@ -182,16 +219,21 @@ void lo_topk(const double *sel, int32_t L, int32_t k, int32_t *idx_out)
  *              per sequence, in sets of capacity k
  *   block      positions one set entry stands for (1: tokens; 64: the blocks of App. C).  The
  *              entries of idx_in / idx_out are then block numbers and k counts blocks.
+ *   rule       0: the budget above.  1: Threshold, 2: Top-p (Sec. 4.4.1) with parameter
+ *              rule_param (tau, p); token-granular only, without the Ratio rule
  * Returns 0, or -1 on an argument it cannot serve.
  */
 int lo_decode_attn_block(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k, int32_t max_len,
                          const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t stride_b,
                          int64_t stride_h, int64_t stride_t, const uint8_t *mask,
                          const int32_t *idx_in, const int32_t *lengths, double *out,
-                         int32_t *idx_out, double *sel_out, int32_t keep_ppm, int32_t block)
+                         int32_t *idx_out, double *sel_out, int32_t keep_ppm, int32_t block,
+                         int32_t rule, double rule_param)
 {
     if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || d < 1 || k < 1 || block < 1) return -1;
     if (keep_ppm < 0 || keep_ppm > 1000000) return -1;
+    if (rule < 0 || rule > 2 || (rule != 0 && (block != 1 || keep_ppm != 0))) return -1;
+    if (rule != 0 && !(rule_param > 0.0 && rule_param <= 1.0)) return -1;
     const int32_t G = Hq / Hkv;
     int any_sparse = 0;
     for (int32_t h = 0; h < Hq; ++h)
@@ -261,7 +303,13 @@ int lo_decode_attn_block(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t 
                             if (sel[t] > best) best = sel[t];
                         unit_score[u] = best;
                     }
-                    lo_topk_n(unit_score, n_units, lo_ratio_budget(n_units, k, keep_ppm), k, dst);
+                    int32_t n_keep = lo_ratio_budget(n_units, k, keep_ppm);
+                    if (rule != 0) {
+                        int32_t want = lo_rule_count(sel, L, rule, rule_param);
+                        if (want < 1) want = 1;
+                        if (want < n_keep) n_keep = want;
+                    }
+                    lo_topk_n(unit_score, n_units, n_keep, k, dst);
                 }
                 else
                     memcpy(dst, idx_in + ((int64_t)b * Hkv + g) * k, (size_t)k * sizeof *dst);
@@ -290,7 +338,7 @@ int lo_decode_attn_rule(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t k
                         int32_t *idx_out, double *sel_out, int32_t keep_ppm)
 {
     return lo_decode_attn_block(B, Hq, Hkv, d, k, max_len, q, K, V, stride_b, stride_h, stride_t, mask,
-                                idx_in, lengths, out, idx_out, sel_out, keep_ppm, 1);
+                                idx_in, lengths, out, idx_out, sel_out, keep_ppm, 1, 0, 0.0);
 }
 
 /* The same with Eq. 2's fixed budget. */

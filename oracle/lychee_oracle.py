@@ -55,7 +55,9 @@ def _load():
         lib.lo_decode_attn.restype = ctypes.c_int
         lib.lo_decode_attn_rule.argtypes = lib.lo_decode_attn.argtypes + [i32]
         lib.lo_decode_attn_rule.restype = ctypes.c_int
-        lib.lo_decode_attn_block.argtypes = lib.lo_decode_attn.argtypes + [i32, i32]
+        lib.lo_decode_attn_block.argtypes = lib.lo_decode_attn.argtypes + [i32, i32, i32, ctypes.c_double]
+        lib.lo_rule_count.argtypes = [f64p, i32, i32, ctypes.c_double]
+        lib.lo_rule_count.restype = i32
         lib.lo_decode_attn_block.restype = ctypes.c_int
         lib.lo_append_kv.argtypes = [i32, i32, i32, u16p, u16p, u16p, u16p, i64, i64, i64, i32p]
         lib.lo_append_kv.restype = ctypes.c_int
@@ -141,6 +143,16 @@ def append_kv(k_new: np.ndarray, v_new: np.ndarray, k_bits: np.ndarray, v_bits: 
         raise ValueError("oracle rejected its arguments (rc=%d)" % rc)
 
 
+RULE_TOPK, RULE_THRESHOLD, RULE_TOP_P = 0, 1, 2
+
+
+def rule_count(sel: np.ndarray, rule: int, param: float) -> int:
+    """Positions the Threshold (rule 1) or Top-p (rule 2) rule keeps among these pooled logits,
+    before the clamp to [1, min(k, L)]."""
+    sel = _c(sel, np.float64)
+    return int(_load().lo_rule_count(_ptr(sel, ctypes.c_double), sel.size, int(rule), float(param)))
+
+
 def ratio_budget(L: int, k: int, keep_ppm: int) -> int:
     """Positions the Ratio rule (Sec. 4.4.1) keeps for a sequence of L rows: ceil(L * keep_ppm /
     10^6), at least 1, at most L and the set capacity k; keep_ppm = 0 gives min(k, L)."""
@@ -149,12 +161,13 @@ def ratio_budget(L: int, k: int, keep_ppm: int) -> int:
 
 def decode_attn(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, mask: np.ndarray,
                 k: int, idx_in: Optional[np.ndarray], lengths: np.ndarray,
-                want_sel: bool = False, keep_ppm: int = 0, block: int = 1
-                ) -> Tuple[np.ndarray, np.ndarray, Optional[np.ndarray]]:
+                want_sel: bool = False, keep_ppm: int = 0, block: int = 1, rule: int = 0,
+                rule_param: float = 0.0) -> Tuple[np.ndarray, np.ndarray, Optional[np.ndarray]]:
     """One layer of Alg. 1's per-head loop.  keep_ppm > 0: the Ratio rule of Sec. 4.4.1
     (ratio_budget() entries per sequence, in sets of capacity k) instead of the fixed budget.
     block > 1: the block-granular variant (App. C): set entries are block numbers, k counts
-    blocks, a block is scored by its best token.
+    blocks, a block is scored by its best token.  rule 1 / 2: the Threshold / Top-p rule of
+    Sec. 4.4.1 with parameter rule_param, on the softmax of the pooled logits, capped at k.
 
     q_bits [B,Hq,d], k_bits / v_bits [B,Hkv,L_cap,d] (uint16 bf16 bit patterns, any
     strides numpy can express with a contiguous last axis), mask [Hq] uint8, idx_in
@@ -181,7 +194,8 @@ def decode_attn(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, mask
                                      sb, sh, st, _ptr(mask, ctypes.c_uint8),
                                      _ptr(idx_in, ctypes.c_int32), _ptr(lengths, ctypes.c_int32),
                                      _ptr(out, ctypes.c_double), _ptr(idx_out, ctypes.c_int32),
-                                     _ptr(sel, ctypes.c_double), int(keep_ppm), int(block))
+                                     _ptr(sel, ctypes.c_double), int(keep_ppm), int(block), int(rule),
+                                     float(rule_param))
     if rc != 0:
         raise ValueError("oracle rejected its arguments (rc=%d)" % rc)
     return out, idx_out, sel

@@ -397,3 +397,58 @@ def test_append_puts_the_new_rows_at_the_last_position_of_every_head_and_nowhere
     Vt = np.ascontiguousarray(V.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
     lo.append_kv(kn, vn, Kt, Vt, lens)
     assert (Kt == want_k).all() and (Vt == want_v).all()
+
+
+# ------------------------------------------------------------------ Top-p and Threshold (Sec. 4.4.1)
+def test_threshold_and_top_p_counts_against_a_library_softmax():
+    from scipy.special import softmax
+    rng = np.random.default_rng(41)
+    for L in (1, 5, 64, 1000):
+        sel = rng.standard_normal(L) * 3.0
+        if L > 10:
+            sel[7] = sel[3]                                   # a tie
+        p = softmax(sel)                                      # library routine
+        order = sorted(range(L), key=lambda t: (-sel[t], t))
+        for tau in (1e-1, 1e-2, 1e-3, 1e-6):
+            assert lo.rule_count(sel, lo.RULE_THRESHOLD, tau) == int((p > tau).sum())
+        for pp in (0.2, 0.5, 0.9, 0.99, 0.999):
+            cum, n = 0.0, 0
+            while n < L and cum < pp:
+                cum += p[order[n]]
+                n += 1
+            assert lo.rule_count(sel, lo.RULE_TOP_P, pp) == n
+    # closed forms: L equal logits have probability 1/L each
+    flat = np.zeros(10)
+    assert lo.rule_count(flat, lo.RULE_THRESHOLD, 0.09) == 10 and lo.rule_count(flat, lo.RULE_THRESHOLD, 0.11) == 0
+    assert lo.rule_count(flat, lo.RULE_TOP_P, 0.25) == 3 and lo.rule_count(flat, lo.RULE_TOP_P, 1.0) == 10
+    # one dominant logit: probability ~ 1 - 9 e^-30
+    spike = np.zeros(10)
+    spike[4] = 30.0
+    assert lo.rule_count(spike, lo.RULE_TOP_P, 0.999) == 1 and lo.rule_count(spike, lo.RULE_THRESHOLD, 0.5) == 1
+
+
+def test_threshold_and_top_p_sets_are_top_sets_capped_at_k_and_never_empty():
+    rng = np.random.default_rng(42)
+    q = round_to_bf16_bits(rng.standard_normal((2, 4, 128)) * 2.0)
+    K = round_to_bf16_bits(rng.standard_normal((2, 2, 300, 128)))
+    V = round_to_bf16_bits(rng.standard_normal((2, 2, 300, 128)))
+    lens = np.array([300, 120], np.int32)
+    mask = np.ones(4, np.uint8)
+    for rule, params in ((lo.RULE_THRESHOLD, (0.5, 1e-2, 1e-3, 1e-9)), (lo.RULE_TOP_P, (0.01, 0.5, 0.9, 1.0))):
+        sizes = []
+        for param in params:
+            _, idx, sel = lo.decode_attn(q, K, V, mask, 64, None, lens, want_sel=True, rule=rule, rule_param=param)
+            for b in range(2):
+                L = int(lens[b])
+                for g in range(2):
+                    n = int((idx[b, g] >= 0).sum())
+                    want = min(64, L, max(1, lo.rule_count(sel[b, g, :L], rule, param)))
+                    assert n == want
+                    order = sorted(range(L), key=lambda t: (-sel[b, g, t], t))
+                    assert list(idx[b, g][:n]) == sorted(order[:n]) and (idx[b, g][n:] == -1).all()
+            sizes.append((idx >= 0).sum())
+        # looser parameters keep more: tau falls / p rises along params
+        assert sizes == sorted(sizes)
+    _, idx_cap, _ = lo.decode_attn(q, K, V, mask, 64, None, lens, rule=lo.RULE_TOP_P, rule_param=1.0)
+    _, idx_k, _ = lo.decode_attn(q, K, V, mask, 64, None, lens)
+    assert (idx_cap == idx_k).all()                          # p = 1 wants everything: the cap is Top-k
