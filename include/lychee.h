@@ -84,7 +84,21 @@ typedef struct lychee_shape {
                             App. C / Sec. 4.3.2: a set entry e names the positions [64e, 64e+63]
                             below L_b, a block is ranked by the best pooled score inside it, and k,
                             idx_in / idx_out and the Ratio rule all count blocks.               */
+    int32_t prob_rule;   /* 0: none.  LYCHEE_RULE_THRESHOLD (1), LYCHEE_RULE_TOP_P (2): the rules of
+                            Sec. 4.4.1 on attention probabilities, here the softmax over the whole
+                            sequence of the pooled selection logits (App. F's pooled query).
+                            Threshold keeps the positions whose probability exceeds prob_param;
+                            Top-p keeps the shortest prefix of the descending order whose
+                            probabilities sum to at least prob_param.  Both keep at least the best
+                            position and at most min(k, L_b) - the best ones, if the rule wants
+                            more -, break ties like Eq. 2, and pad the set with -1.  Positions
+                            only (block_size <= 1), and not together with keep_ppm.  Decisions are
+                            taken in fp32: a position whose probability (cumulative probability)
+                            lies within rounding of the parameter may fall on either side.     */
+    float prob_param;    /* tau or p, in (0, 1]                                                  */
 } lychee_shape;
+#define LYCHEE_RULE_THRESHOLD 1
+#define LYCHEE_RULE_TOP_P     2
 
 /* Create / destroy a context bound to HIP device `device`.  Needs a GPU. */
 int lychee_create(lychee_ctx **ctx, int device);

@@ -22,6 +22,7 @@ KERNEL_STREAM, KERNEL_GATHER, KERNEL_THRESHOLD, KERNEL_SELECT, KERNEL_COMBINE = 
 N_KERNEL_CLASSES = 5
 OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE, OPT_SELECT_MARGIN = 1, 2, 6, 7, 8, 9
 STEP_PHASED, STEP_LAYERWISE = 1, 0
+RULE_THRESHOLD, RULE_TOP_P = 1, 2
 
 EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
@@ -40,7 +41,8 @@ class Shape(ctypes.Structure):
                 ("max_len", ctypes.c_int32), ("k", ctypes.c_int32),
                 ("kv_stride_batch", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
                 ("kv_stride_tok", ctypes.c_int64), ("keep_ppm", ctypes.c_int32),
-                ("block_size", ctypes.c_int32)]
+                ("block_size", ctypes.c_int32), ("prob_rule", ctypes.c_int32),
+                ("prob_param", ctypes.c_float)]
 
 
 class LycheeError(RuntimeError):
@@ -115,7 +117,7 @@ def _stream(stream) -> Optional[int]:
 def make_shape(batch: int, n_q_heads: int, n_kv_heads: int, max_len: int, k: int,
                kv: Optional[torch.Tensor] = None, head_dim: int = 128,
                strides: Optional[Sequence[int]] = None, keep_ppm: int = 0,
-               block_size: int = 0) -> Shape:
+               block_size: int = 0, prob_rule: int = 0, prob_param: float = 0.0) -> Shape:
     """A `lychee_shape`; KV strides (elements) come from a [B,H_kv,L_cap,128] tensor or `strides`."""
     if strides is None:
         if kv is not None:
@@ -123,7 +125,7 @@ def make_shape(batch: int, n_q_heads: int, n_kv_heads: int, max_len: int, k: int
         else:
             strides = (n_kv_heads * max_len * head_dim, max_len * head_dim, head_dim)
     return Shape(batch, n_q_heads, n_kv_heads, head_dim, max_len, k, *[int(s) for s in strides],
-                 int(keep_ppm), int(block_size))
+                 int(keep_ppm), int(block_size), int(prob_rule), float(prob_param))
 
 
 def check_shape(shape: Shape, head_type_mask: Optional[np.ndarray] = None,

@@ -73,7 +73,7 @@ int32_t list_row_entries(int32_t max_len, int32_t k)
 
 // Per-layer scratch, laid out layer after layer.
 struct Workspace {
-    size_t sel, part_o, part_ml, part_count, list, list_count, thr, idx_set;  // offsets inside a layer
+    size_t sel, part_o, part_ml, part_count, part_pool, list, list_count, thr, idx_set;  // offsets inside a layer
     size_t layer_bytes, total;
     int32_t sel_stride, list_row;
 };
@@ -95,6 +95,7 @@ Workspace carve(const lychee_shape &s, int n_layers)
     w.part_o = take(heads * kPartSlots * kHeadDim * sizeof(float));
     w.part_ml = take(heads * kPartSlots * 2 * sizeof(float));
     w.part_count = take(heads * sizeof(int32_t));
+    w.part_pool = take(groups * kPartSlots * 2 * sizeof(float));
     w.list = take(groups * (size_t)w.list_row * sizeof(unsigned long long));
     w.list_count = take(groups * sizeof(int32_t));
     w.thr = take(groups * sizeof(uint32_t));
@@ -116,6 +117,11 @@ int check_shape(const lychee_shape *s)
     if (s->max_len > (1 << 24) || s->batch > kMaxBatch) return LYCHEE_EUNSUPPORTED;
     if (s->keep_ppm < 0 || s->keep_ppm > 1000000) return LYCHEE_EINVAL;
     if (s->block_size != 0 && s->block_size != 1 && s->block_size != 64) return LYCHEE_EUNSUPPORTED;
+    if (s->prob_rule < 0 || s->prob_rule > 2) return LYCHEE_EINVAL;
+    if (s->prob_rule != 0) {
+        if (!(s->prob_param > 0.0f && s->prob_param <= 1.0f)) return LYCHEE_EINVAL;
+        if (s->keep_ppm != 0 || s->block_size == 64) return LYCHEE_EUNSUPPORTED;  // one rule at a time, on tokens
+    }
     if (s->kv_stride_tok < kHeadDim || s->kv_stride_batch < 0 || s->kv_stride_head < 0)
         return LYCHEE_EINVAL;
     if (s->kv_stride_tok % 8 || s->kv_stride_head % 8 || s->kv_stride_batch % 8) return LYCHEE_EINVAL;
@@ -181,6 +187,7 @@ void set_scratch(LayerDesc &d, const Workspace &w, char *ws, int layer_slot)
     d.part_o = reinterpret_cast<float *>(base + w.part_o);
     d.part_ml = reinterpret_cast<float *>(base + w.part_ml);
     d.part_count = reinterpret_cast<int32_t *>(base + w.part_count);
+    d.part_pool = reinterpret_cast<float *>(base + w.part_pool);
     d.list = reinterpret_cast<unsigned long long *>(base + w.list);
     d.list_count = reinterpret_cast<int32_t *>(base + w.list_count);
     d.thr = reinterpret_cast<uint32_t *>(base + w.thr);
@@ -283,6 +290,8 @@ struct Launcher {
         c.k = s.k;
         c.keep_ppm = s.keep_ppm;
         c.block_shift = s.block_size == 64 ? 6 : 0;
+        c.prob_rule = s.prob_rule;
+        c.prob_param = s.prob_param;
         c.max_len = s.max_len;
         c.sel_stride = w.sel_stride;
         c.list_row = w.list_row;

@@ -38,6 +38,8 @@ struct Common {
     int32_t k, max_len, sel_stride;
     int32_t keep_ppm;     // > 0: the Ratio rule's share of a sequence, in parts per million
     int32_t block_shift;  // 0: sets name positions; 6: blocks of 64 positions (App. C)
+    int32_t prob_rule;    // 0: budget only; 1: Threshold, 2: Top-p (Sec. 4.4.1) with parameter
+    float prob_param;     //   prob_param, on the softmax of the pooled logits
     int32_t list_row;     // capacity, in entries, of one score row's candidate list
     int32_t n_wg;         // grid size of this launch
     int32_t part_stride;  // partial slots per head
@@ -68,6 +70,8 @@ struct LayerDesc {
     float *part_o;         // [B*H_q][part_stride][128] un-normalised partial outputs
     float *part_ml;        // [B*H_q][part_stride][2]   running maximum (raw dot units) and sum
     int32_t *part_count;   // [B*H_q] partial slots in use
+    float *part_pool;      // [B*n_rgroups][part_stride][2] running maximum and sum of exp of the
+                           // pooled selection logits, per piece (Threshold / Top-p rules only)
     unsigned long long *list;  // [B*n_rgroups][list_row] candidates in no particular order:
                                // ordered key in the low 32 bits, position in the high 32 bits
     int32_t *list_count;   // [B*n_rgroups] candidates found (may exceed list_row: list unusable)

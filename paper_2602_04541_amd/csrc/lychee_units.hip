@@ -48,6 +48,7 @@ struct SharedAttn {
     int32_t idx_s[kIdxChunk];
     float red_o[kWaves * kMaxGroup * kHeadDim];
     float red_ml[kWaves * kMaxGroup * 2];
+    float pool_ml[kWaves * 2];
     unsigned long long cand[kWaves][kCandBuf];  // per wavefront: candidates not yet flushed
 };
 struct SharedSelect {
@@ -100,6 +101,7 @@ __device__ __forceinline__ float row16_sum(float x)
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kLog2e = 1.4426950408889634f;
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xFFFF0000u); }
 
@@ -360,6 +362,8 @@ struct Emit {
     int32_t cap;
     int32_t direct;            // block-granular: entry b of the list is block b's best score,
                                // written in place; no threshold, no counter
+    float *pool_ml;            // Threshold / Top-p rules: this score row's per-piece (maximum,
+                               // sum of exp) of the pooled logits; nullptr otherwise
 };
 
 // Appends a wavefront's n buffered candidates to the row's list.  The counter keeps counting
@@ -389,7 +393,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
                                             const uint16_t *vbase, const uint4 (&qf)[NH],
                                             Acc<NH> &acc, int L, int r0, int r1,
                                             const int32_t *idx_s, const Emit &em, float sel_mul,
-                                            unsigned long long *cand_buf)
+                                            unsigned long long *cand_buf, float &pool_m, float &pool_l)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -488,7 +492,14 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             hi = (j == 3) ? sel1[3] : hi;
             const float mine = (ch & 4) ? hi : lo;
             const int r = r0 + span * kSpan + 32 * wave + 16 * ((ch >> 2) & 1) + 4 * j + rs;
-            const uint32_t key = ordered_key(sel_value(mine, sel_mul));
+            const float score = sel_value(mine, sel_mul);
+            const uint32_t key = ordered_key(score);
+            if (em.pool_ml != nullptr && ch < 8 && r < r1) {
+                // online log-sum-exp of the pooled logits, one row per lane and span
+                const float m_new = fmaxf(pool_m, score);
+                pool_l = pool_l * fast_exp2((pool_m - m_new) * kLog2e) + fast_exp2((score - m_new) * kLog2e);
+                pool_m = m_new;
+            }
             const bool hit = ch < 8 && r < r1 && key >= em.thr;
             const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
             if (hits != 0) {  // wave-uniform
@@ -548,6 +559,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     const uint16_t *kbase = k_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
     const uint16_t *vbase = v_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
     const float sel_mul = c.scale / (float)NH;
+    float pool_m = kMinusBig, pool_l = 0.0f;  // per lane: log-sum-exp state of the pooled logits
 
     if (GATHER) {
         // rows r0 .. r1-1 of the gathered sequence are row (r mod 2^shift) of set entry r >> shift
@@ -559,10 +571,10 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             __syncthreads();  // the previous chunk's readers are done
             for (int i = threadIdx.x; i < n_entries; i += kThreads) sh.idx_s[i] = gload(idx_src + (e0 >> shift) + i);
             __syncthreads();
-            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr);
+            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr, pool_m, pool_l);
         }
     } else {
-        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave]);
+        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave], pool_m, pool_l);
     }
 
     TRACE(7);
@@ -587,8 +599,23 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             acc.o[h][e] = ow;
         }
     }
+    const bool pooled_lse = !GATHER && em.pool_ml != nullptr;
+    if (pooled_lse) {  // wave-uniform: merge the lanes' pooled log-sum-exp states
+        float mw = pool_m;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) mw = fmaxf(mw, __shfl_xor(mw, d));
+        float lw = pool_l * fast_exp2((pool_m - mw) * kLog2e);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) lw += __shfl_xor(lw, d);
+        pool_m = mw;
+        pool_l = lw;
+    }
     // Merge the 4 wavefronts through LDS and write the piece's partial.
     __syncthreads();  // red_o / idx_s readers of the previous piece are done
+    if (pooled_lse && lane == 0) {
+        sh.pool_ml[2 * wave] = pool_m;
+        sh.pool_ml[2 * wave + 1] = pool_l;
+    }
     if (rs == 0) {
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
@@ -624,6 +651,15 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
                 if (ends_segment) gstore(part_count + bh, (int32_t)(slot + 1));
             }
         }
+    }
+    if (pooled_lse && threadIdx.x == 0) {  // the piece's pooled log-sum-exp state, same slot
+        float M = kMinusBig, l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sh.pool_ml[2 * w]);
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) l = fmaf(fast_exp2((sh.pool_ml[2 * w] - M) * kLog2e), sh.pool_ml[2 * w + 1], l);
+        gstore(em.pool_ml + 2 * slot, M);
+        gstore(em.pool_ml + 2 * slot + 1, l);
     }
 }
 
@@ -788,7 +824,8 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
     if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
         // everything is selected anyway (no candidates wanted), or every row is a candidate
-        if (threadIdx.x == 0) gstore(p.thr + row, n == L ? 0xFFFFFFFFu : 0u);
+        // (a probability rule may keep fewer than everything: it still needs the candidates)
+        if (threadIdx.x == 0) gstore(p.thr + row, n == L && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u);
         return;
     }
     int n_tiles = L / 1024;
@@ -1074,6 +1111,133 @@ __device__ __forceinline__ void append_unit(const Common &c, const LayerDesc &p)
     }
 }
 
+// ---- the probability rules of Sec. 4.4.1 (Threshold, Top-p): how many entries to keep
+// The pooled logit an ordered key stands for.
+__device__ __forceinline__ float key_score(uint32_t key)
+{
+    return __builtin_bit_cast(float, (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+// Probability of a pooled logit under the softmax over the whole sequence, as a 40-bit
+// fixed-point number: sums of these are integer sums, the same in any order.
+constexpr float kMassOne = 1099511627776.0f;  // 2^40
+__device__ __forceinline__ unsigned long long mass_of(uint32_t key, float lse)
+{
+    const float p = fast_exp2((key_score(key) - lse) * kLog2e);  // <= 1 up to rounding
+    return (unsigned long long)(fminf(p, 1.0f) * kMassOne);
+}
+
+// In a histogram of probability mass per digit, finds the highest digit d at which the mass
+// of the digits >= d reaches `need`; returns d and what is still needed inside d, or digit
+// 0xFFFFFFFF when all the mass together does not reach it.
+template <int kBins>
+__device__ __forceinline__ void find_digit_mass(const unsigned long long *hist, unsigned long long need,
+                                                SharedPool &pool, uint32_t &digit, unsigned long long &rest)
+{
+    constexpr int per = kBins / kThreads;
+    unsigned long long mine[per], sum = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        mine[j] = hist[kBins - 1 - (threadIdx.x * per + j)];  // bins taken from the top
+        sum += mine[j];
+    }
+    unsigned long long total;
+    unsigned long long above = block_scan64(sum, pool.scan64, total) - sum;
+    if (threadIdx.x == 0) {
+        pool.scan64[kWaves] = 0xFFFFFFFFull << 32;  // "not reached"
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        if (above < need && need <= above + mine[j]) {
+            // digit in the high word, the remaining need (< 2^41) cannot be packed with it: two words
+            pool.scan64[kWaves] = (unsigned long long)(uint32_t)(kBins - 1 - (threadIdx.x * per + j)) << 32;
+            pool.scan64[kWaves - 1] = need - above;
+        }
+        above += mine[j];
+    }
+    __syncthreads();
+    digit = (uint32_t)(pool.scan64[kWaves] >> 32);
+    rest = pool.scan64[kWaves - 1];
+    __syncthreads();
+}
+
+// Entries the rule keeps, before the clamp to [1, n]: Threshold counts the entries whose
+// probability exceeds the parameter; Top-p finds, digit by digit, the key at which the
+// probability mass of the descending order reaches the parameter (all entries with that key
+// have the same mass, so a division says how many of them are needed).  `lse` is the
+// log-sum-exp of the pooled logits of the whole sequence.  The entries hold at least the n best
+// positions, and a rule that would go beyond them is capped at n anyway.
+template <typename Entries>
+__device__ __forceinline__ int rule_keeps(const Common &c, const Entries &E, int n, float lse, SharedSelect &sh,
+                                          SharedPool &pool)
+{
+    uint32_t want;
+    if (c.prob_rule == 1) {
+        const uint32_t cut = ordered_key(lse + __logf(c.prob_param));
+        uint32_t mine = 0;
+        E.for_each([&](uint32_t key, uint32_t pos) { mine += (uint32_t)((pos != kNoEntry) & (key > cut)); });
+        (void)block_scan(mine, pool.scan, want);
+    } else {
+        if (c.prob_param >= 1.0f) return n;  // all of the mass: everything, i.e. the cap
+        unsigned long long *mh = reinterpret_cast<unsigned long long *>(sh.hist);  // 4096 x 8 bytes: hist + samp
+        unsigned long long need = (unsigned long long)((double)c.prob_param * (double)kMassOne);
+        need = need < 1 ? 1 : need;
+        uint32_t prefix = 0, prefix_mask = 0;
+        bool reached = true;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int n_bins = pass == 0 ? 4096 : 1024;
+            const uint32_t digit_mask = (uint32_t)n_bins - 1u;
+            for (int i = threadIdx.x; i < n_bins; i += kThreads) mh[i] = 0;
+            __syncthreads();
+            E.for_each([&](uint32_t key, uint32_t pos) {
+                const bool in = (pos != kNoEntry) & ((key & prefix_mask) == prefix);
+                if (in) atomicAdd(&mh[(key >> shift) & digit_mask], mass_of(key, lse));
+            });
+            __syncthreads();
+            uint32_t digit;
+            unsigned long long left;
+            if (pass == 0)
+                find_digit_mass<4096>(mh, need, pool, digit, left);
+            else
+                find_digit_mass<1024>(mh, need, pool, digit, left);
+            if (digit == 0xFFFFFFFFu) {  // (uniform) not even all entries reach the mass: the cap decides
+                reached = false;
+                break;
+            }
+            prefix |= digit << shift;
+            prefix_mask |= digit_mask << shift;
+            need = left;
+        }
+        if (!reached) return n;
+        const unsigned long long each = mass_of(prefix, lse);  // > 0: its digit held mass
+        const uint32_t of_last = (uint32_t)((need + each - 1) / each);
+        uint32_t mine = 0;
+        E.for_each([&](uint32_t key, uint32_t pos) { mine += (uint32_t)((pos != kNoEntry) & (key > prefix)); });
+        uint32_t above;
+        (void)block_scan(mine, pool.scan, above);
+        want = above + of_last;
+    }
+    return want < 1u ? 1 : (want > (uint32_t)n ? n : (int)want);
+}
+
+// Log-sum-exp of the pooled logits of score row `row`: the pieces' states, merged.
+__device__ __forceinline__ float pooled_lse(const Common &c, const LayerDesc &p, int64_t row, int count,
+                                            SharedPool &pool)
+{
+    const float *ml = p.part_pool + row * (2 * (int64_t)c.part_stride);
+    float m_loc = kMinusBig;
+    for (int s = threadIdx.x; s < count; s += kThreads) m_loc = fmaxf(m_loc, gload(ml + 2 * s));
+    const float M = block_max(m_loc, pool.fred);
+    float l_loc = 0.0f;
+    for (int s = threadIdx.x; s < count; s += kThreads)
+        l_loc = fmaf(fast_exp2((gload(ml + 2 * s) - M) * kLog2e), gload(ml + 2 * s + 1), l_loc);
+    const float l = block_sum(l_loc, pool.fred);
+    return M + __logf(l);
+}
+
 // The set of a KV head (b, g) whose group holds no retrieval head is handed on unchanged
 // (Sec. 3.1): a verbatim copy.
 __device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &p, int b, int g)
@@ -1085,7 +1249,9 @@ __device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &
 }
 
 // S unit of KV head (b, g), whose group holds a retrieval head: the set the next layer's
-// sparse heads of the group inherit.
+// sparse heads of the group inherit.  PROB: the build that knows the probability rules (their
+// 64-bit mass arithmetic over register-resident entries would cost the plain build registers).
+template <bool PROB>
 __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p, int b, int g,
                                             SharedSelect &sh, SharedPool &pool)
 {
@@ -1095,7 +1261,8 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     const int len = clamp_len(c.lengths[b], c.max_len);
     const int L = units_of(c, len);  // what is ranked: positions, or blocks of positions
     const int n = budget_of(c, L);
-    if (n == L) {  // everything is selected
+    const bool by_prob = PROB && c.prob_rule != 0;
+    if (n == L && !by_prob) {  // everything is selected
         for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
         return;
     }
@@ -1104,14 +1271,25 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     // block-granular: the streaming left every block's score at its place in the list
     const int total = c.block_shift ? L : gload(p.list_count + row);
     TRACE(5);
+    float lse = 0.0f;
+    if (by_prob) {
+        // the pieces of this KV head's segment, counted by its first retrieval head
+        const int h = g * c.group + __builtin_ctz((uint32_t)p.rmask[g]);
+        int count = gload(p.part_count + (int64_t)b * c.n_q_heads + h);
+        count = count < 0 ? 0 : (count > c.part_stride ? c.part_stride : count);
+        lse = pooled_lse(c, p, row, count, pool);
+    }
+    int keep = n;  // what is selected in the end: n, or fewer under a probability rule
     if (total >= n && total <= kThreads * kSelRegs && total <= c.list_row) {
         RegEntries E;
         E.load(list, total);
         TRACE(6);
-        select_from(E, n, L, dst, sh, pool);
+        if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
+        select_from(E, keep, L, dst, sh, pool);
     } else if (total >= n && total <= c.list_row) {
         const ListEntries E{list, total};
-        select_from(E, n, L, dst, sh, pool);
+        if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
+        select_from(E, keep, L, dst, sh, pool);
     } else {
         // too few candidates reached the threshold, or too many for the list: rank the row
         // (token-granular only: a block list is always complete)
@@ -1126,9 +1304,10 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
         __threadfence();
         __syncthreads();  // the scores are read back by other threads of the workgroup
         const RowEntries E{sel, len};
-        select_from(E, n, L, dst, sh, pool);
+        if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
+        select_from(E, keep, L, dst, sh, pool);
     }
-    for (int i = n + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
+    for (int i = keep + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
 }
 
 // ------------------------------------------------------------------------------ the kernels
@@ -1164,10 +1343,11 @@ __device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
     return lo;
 }
 
-// Launches that carry T, S and C units: unit j runs on workgroup j mod W.  SELECTS = false
-// is the lighter build for launches without S units on retrieval groups (their candidates held
-// in registers set this kernel's register budget, and spill code with it).
-template <bool SELECTS>
+// Launches that carry T, S and C units: unit j runs on workgroup j mod W.  SELECTS = 0 is
+// the lighter build for launches without S units on retrieval groups (their candidates held
+// in registers set this kernel's register budget, and spill code with it), 1 the build with
+// them, 2 the one whose S units also know the probability rules.
+template <int SELECTS>
 __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchPlan P)
 {
     __shared__ SharedUnit su;
@@ -1210,7 +1390,8 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
                 const LayerDesc &L = layers[P.s_first + li];
                 u -= pool.upre[0][li];
                 const int b = u / L.n_rgroups;
-                if (SELECTS) select_unit(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
+                if (SELECTS == 1) select_unit<false>(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
+                if (SELECTS == 2) select_unit<true>(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
             } else if ((u -= (int)tot[0]) < (int)tot[1]) {
                 const int li = u / (c.batch * c.n_q_heads);
                 combine_unit(c, layers[P.c_first + li], u % (c.batch * c.n_q_heads), su.comb, pool);
@@ -1414,7 +1595,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             if (!gather) {
                 const int g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
                 const uint32_t hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
-                Emit em{nullptr, nullptr, 0u, 0, 0};
+                Emit em{nullptr, nullptr, 0u, 0, 0, nullptr};
                 if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
                     const int64_t row = (int64_t)b * (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) + gi;
                     em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
@@ -1422,6 +1603,8 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                     em.thr = c.block_shift ? 0u : gload(desc_ptr<uint32_t>(dw, offsetof(LayerDesc, thr)) + row);
                     em.cap = c.list_row;
                     em.direct = c.block_shift != 0;
+                    if (c.prob_rule != 0)
+                        em.pool_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_pool)) + row * (2 * (int64_t)c.part_stride);
                 }
                 dispatch_piece<false>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
                                       d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa, at_rows_done);
@@ -1430,7 +1613,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                 const uint32_t hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
                 const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)g) +
                                          ((int64_t)b * c.n_kv_heads + g) * c.k;
-                dispatch_piece<true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{nullptr, nullptr, 0u, 0, 0},
+                dispatch_piece<true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{nullptr, nullptr, 0u, 0, 0, nullptr},
                                      d_part_o, d_part_ml, d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa,
                                      at_rows_done);
             }
@@ -1524,10 +1707,12 @@ hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
     const bool small = plan.t_count + plan.s_count + plan.c_count + plan.a_count > 0;
     if (pooled == small) return hipErrorInvalidValue;  // a launch carries one family of units
     const dim3 grid(plan.c.n_wg), block(kThreads);
-    if (small && plan.selects)
-        hipLaunchKernelGGL((lychee_small_kernel<true>), grid, block, 0, stream, plan);
+    if (small && plan.selects && plan.c.prob_rule != 0)
+        hipLaunchKernelGGL((lychee_small_kernel<2>), grid, block, 0, stream, plan);
+    else if (small && plan.selects)
+        hipLaunchKernelGGL((lychee_small_kernel<1>), grid, block, 0, stream, plan);
     else if (small)
-        hipLaunchKernelGGL((lychee_small_kernel<false>), grid, block, 0, stream, plan);
+        hipLaunchKernelGGL((lychee_small_kernel<0>), grid, block, 0, stream, plan);
     else if (plan.r_count == 0)
         hipLaunchKernelGGL((lychee_pool_kernel<false, true, false>), grid, block, 0, stream, plan);
     else if (plan.g_count == 0 && plan.collect)

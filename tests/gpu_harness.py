@@ -135,3 +135,53 @@ def check_layer(ctx, inp: wl.LayerInputs, mask, k, idx_in, what="", exact_sets=F
     if exact_sets:
         assert n_diff == 0, "%s: %d positions differ from the oracle's sets" % (what, n_diff)
     return dl, out_gpu, idx_gpu, out_ref, idx_ref, sel_ref
+
+
+def check_prob_rule_layer(ctx, inp: wl.LayerInputs, mask, k, rule, param, what="", idx_in=None):
+    """One all-in-one check of a Threshold (rule 1) / Top-p (rule 2) layer call: outputs as usual;
+    every selected set must be the oracle's top set of its own size, and its size must be the
+    oracle's, or differ only by positions whose probability (cumulative probability) lies within
+    fp32 rounding of the parameter.  Returns the sizes [B][H_kv] (0 for groups that keep theirs)."""
+    lb = binding()
+    w = inp.workload
+    dl = DeviceLayer(inp, k, idx_in)
+    dl.shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, dl.k_cache.shape[2], k, kv=dl.k_cache,
+                             prob_rule=rule, prob_param=param)
+    out_gpu, idx_gpu = run_hybrid(ctx, dl, np.asarray(mask, np.uint8))
+    out_ref, idx_ref, sel_ref = lo.decode_attn(wl.bf16_bits(inp.q), wl.bf16_bits(inp.k_cache),
+                                               wl.bf16_bits(inp.v_cache), np.asarray(mask, np.uint8), k, idx_in,
+                                               inp.lengths, want_sel=True, rule=rule, rule_param=param)
+    assert_outputs_close(out_gpu, out_ref, what)
+    sizes = np.zeros((w.batch, w.n_kv_heads), np.int64)
+    G = w.group
+    for b in range(w.batch):
+        L = int(inp.lengths[b])
+        for g in range(w.n_kv_heads):
+            if not np.asarray(mask[g * G:(g + 1) * G]).any():
+                continue
+            got = idx_gpu[b, g]
+            n_g = int((got >= 0).sum())
+            n_o = int((idx_ref[b, g] >= 0).sum())
+            sizes[b, g] = n_g
+            assert 1 <= n_g <= min(k, L) and (got[n_g:] == -1).all() and (np.diff(got[:n_g]) > 0).all()
+            sel = sel_ref[b, g, :L]
+            ref_same_size = lo.topk(sel, n_g)                    # the oracle's top set of the GPU's size
+            ok, _, msg = index_sets_match(got[:n_g], ref_same_size, sel, n_g, TIE_REL)
+            assert ok, "%s: b=%d g=%d: %s" % (what, b, g, msg)
+            if n_g == n_o:
+                continue
+            # sizes differ: only by positions at the very edge of the rule
+            order = np.array(sorted(range(L), key=lambda t: (-sel[t], t)))
+            m = sel.max()
+            prob = np.exp(sel - m) / np.exp(sel - m).sum()
+            lo_n, hi_n = min(n_g, n_o), max(n_g, n_o)
+            between = order[lo_n:hi_n]
+            if rule == 1:
+                assert (np.abs(np.log(prob[between]) - np.log(param)) <= 1e-3).all(), \
+                    "%s: b=%d g=%d: sizes %d / %d differ away from the threshold" % (what, b, g, n_g, n_o)
+            else:
+                cum = np.cumsum(prob[order])
+                # the smaller set already holds the mass, to within fp32 rounding of it
+                assert abs(cum[lo_n - 1] - param) <= 1e-4 * param, \
+                    "%s: b=%d g=%d: sizes %d / %d differ away from the mass %r" % (what, b, g, n_g, n_o, param)
+    return sizes

@@ -106,3 +106,14 @@ def test_ratio_rule_field_is_validated(lb):
     assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, block_size=64)) == lb.OK
     assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, block_size=1)) == lb.OK
     assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, block_size=32)) == lb.EUNSUPPORTED
+
+
+def test_probability_rule_fields_are_validated(lb):
+    ok = lb.make_shape(1, 8, 2, 4096, 256, prob_rule=lb.RULE_TOP_P, prob_param=0.9)
+    assert lb.check_shape(ok) == lb.OK
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, prob_rule=lb.RULE_THRESHOLD, prob_param=1e-4)) == lb.OK
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, prob_rule=3, prob_param=0.5)) == lb.EINVAL
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, prob_rule=1, prob_param=0.0)) == lb.EINVAL
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, prob_rule=2, prob_param=1.5)) == lb.EINVAL
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, prob_rule=2, prob_param=0.5, block_size=64)) == lb.EUNSUPPORTED
+    assert lb.check_shape(lb.make_shape(1, 8, 2, 4096, 256, prob_rule=2, prob_param=0.5, keep_ppm=1000)) == lb.EUNSUPPORTED

@@ -798,3 +798,59 @@ def test_scores_that_come_in_runs_do_not_mislead_the_threshold(ctx):
     _say("scores in runs: 8 runs of 500 strong rows per KV head at 128K, k 4096")
     H.check_layer(ctx, inp, np.ones(8, np.uint8), w.k, None, "runs", exact_sets=True)
     assert ctx.select_stats() == (few0, many0)
+
+
+# ------------------------------------------------------------------ Threshold and Top-p (Sec. 4.4.1)
+@pytest.mark.parametrize("rule,param", [(1, 1e-2), (1, 1e-4), (1, 1e-6), (1, 0.9), (2, 0.5), (2, 0.9), (2, 0.999), (2, 1.0)])
+def test_probability_rules_on_a_long_sequence(ctx, rule, param):
+    w = wl.scaled(wl.WORKLOADS["c5"], n_q_heads=8, n_kv_heads=2, n_retrieval=0, retrieval_heads=(0, 4, 5), k=3000,
+                  max_len=50000, planted=64)
+    inp = wl.make_layer(w, l_cap=50000)
+    _say("probability rule %d, parameter %g, L 50000, k 3000" % (rule, param))
+    idx_in = H.previous_layer_sets(inp, w.k)
+    sizes = H.check_prob_rule_layer(ctx, inp, inp.mask, w.k, rule, param, "rule %d %g" % (rule, param), idx_in)
+    assert (sizes >= 0).all()
+    sizes_all = H.check_prob_rule_layer(ctx, inp, np.ones(8, np.uint8), w.k, rule, param, "rule %d %g all" % (rule, param))
+    if (rule, param) in ((1, 0.9), ):
+        assert (sizes_all <= 1).all()          # nothing holds 90 % of the mass here: only the best position is kept
+    if (rule, param) == (2, 1.0):
+        assert (sizes_all == 3000).all()       # all of the mass: capped at k
+
+
+@pytest.mark.parametrize("rule,param", [(1, 1e-3), (2, 0.8)])
+def test_probability_rules_on_short_and_ragged_sequences(ctx, rule, param):
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=3, max_len=6000, k=500, planted=8, len_lo=40, len_hi=6000)
+    lens_h = np.array([6000, 40, 333], np.int32)
+    inp = wl.make_layer(w, lens=lens_h, l_cap=6000)
+    _say("probability rule %d on ragged lengths %s (k larger than two of them)" % (rule, lens_h.tolist()))
+    H.check_prob_rule_layer(ctx, inp, np.ones(w.n_q_heads, np.uint8), w.k, rule, param, "ragged rule %d" % rule)
+
+
+def test_probability_rule_step_feeds_variable_sets_to_the_next_layers(ctx):
+    lb = H.binding()
+    n_layers, k = 4, 1500
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=30000, k=k, n_layers=n_layers, planted=64)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=30000) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, _ = H.lo.decode_attn(wl.bf16_bits(ly.q), wl.bf16_bits(ly.k_cache), wl.bf16_bits(ly.v_cache),
+                                           ly.mask, k, idx, ly.lengths, rule=2, rule_param=0.95)
+        refs.append(out_ref)
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 30000, k, kv=layers[0].k_cache, prob_rule=lb.RULE_TOP_P,
+                          prob_param=0.95)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda")
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    _say("Top-p 0.95: 4-layer phased step")
+    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers], [ly.v_cache for ly in layers],
+                    masks, None, outs, idx_final, lens, ws)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l], "top-p step layer %d" % l)
+    got = idx_final.cpu().numpy()
+    sizes = (got >= 0).sum(axis=2)
+    assert (sizes >= 1).all() and (sizes <= k).all()
