@@ -1,17 +1,21 @@
-// The work-unit kernel of liblychee for gfx950 (CDNA4).
+// The work-unit kernels of liblychee for gfx950 (CDNA4).
 //
 // One launch runs a pooled list of work for a fixed grid of workgroups (about two per CU):
+//   A  cache append          Alg. 1's C.append(k, v): the decoded token's rows enter the caches
 //   T  selection threshold   a score that somewhat more than k rows reach, read off a sample
 //                            of the row's pooled scores (Eq. 2's ranking needs only those)
 //   R  retrieval streaming   Eq. 1, o = A V; rows whose pooled score reaches the threshold
-//                            are collected as candidates of Eq. 2's top-k
+//                            are collected as candidates of Eq. 2's top-k (block-granular
+//                            sets, App. C: every block's best score is written in place)
 //   S  select                exact radix select over the candidates (ties to the lower
 //                            position), ascending write of the set; verbatim copy for groups
-//                            that keep theirs
+//                            that keep theirs; the Ratio, Threshold and Top-p rules of
+//                            Sec. 4.4.1 decide here how many are kept
 //   G  sparse gather         Eq. 3 on the inherited set
 //   C  combine               log-sum-exp merge of a head's partials into its bf16 output
-// A launch names, for each kind, the range of layers it covers in a table of layer
-// descriptors in device memory.  The units of one launch are mutually independent;
+// R and G rows run in lychee_pool_kernel, the other kinds in lychee_small_kernel.  A launch
+// names, for each kind, the range of layers it covers in a table of layer descriptors in
+// device memory.  The units of one launch are mutually independent;
 // everything that depends on another unit's result runs in a later launch, so there are no
 // device-side waits or fences; the only atomics on global memory are counters whose final
 // value, not the order of the additions, is what later launches use.
