@@ -345,20 +345,24 @@ struct Launcher {
 };
 
 // Layer `l` of the table, dependent launches: T (only when the layer selects; the cache append,
-// if the layer has one, rides along or goes alone), then R+G, then S+C.
-int run_layer(const Launcher &L, int l, bool select)
+// if the layer has one, rides along or goes alone), then R+G, then C.  The layer's own S units
+// go with C when `select_now`; `select_prev` >= 0 names an earlier layer whose S units ride in
+// the first launch instead: nothing of layer l before its gather needs them, and a select next
+// to the thresholds costs no launch of its own.
+int run_layer(const Launcher &L, int l, bool select, bool select_now, int select_prev = -1)
 {
     int rc;
     Ranges t;
     if (select && L.s.block_size != 64) t.t_first = l, t.t_count = 1;  // block scores need no threshold
     if (L.host_table[l].k_new != nullptr) t.a_first = l, t.a_count = 1;
+    if (select_prev >= 0) t.s_first = select_prev, t.s_count = 1;
     if ((rc = L.go(t)) != LYCHEE_OK) return rc;
     Ranges a;
     a.r_first = a.g_first = l, a.r_count = a.g_count = 1;
     if ((rc = L.go(a)) != LYCHEE_OK) return rc;
     Ranges b;
     b.c_first = l, b.c_count = 1;
-    if (select) b.s_first = l, b.s_count = 1;
+    if (select && select_now) b.s_first = l, b.s_count = 1;
     return L.go(b);
 }
 
@@ -452,8 +456,17 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && n_layers > 1 &&
                         (int64_t)n_layers * shape->batch <= kMaxItems;
     if (!phased) {
+        // Layer l's output needs its partials combined, not its sets selected: the select
+        // waits for the first launch of layer l + 1, where it runs beside that layer's
+        // thresholds; the last selecting layer's gets a launch of its own.
         for (int l = 0; l < n_layers; ++l)
-            if ((rc = run_layer(L, l, l < n_select)) != LYCHEE_OK) return rc;
+            if ((rc = run_layer(L, l, l < n_select, false, l > 0 && l - 1 < n_select ? l - 1 : -1)) != LYCHEE_OK)
+                return rc;
+        if (n_select == n_layers) {
+            Ranges last;
+            last.s_first = n_layers - 1, last.s_count = 1;
+            if ((rc = L.go(last)) != LYCHEE_OK) return rc;
+        }
     } else {
         // All layers at once, one launch per phase; each phase needs only earlier phases:
         //   A + T (appends, thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
@@ -584,7 +597,7 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    return run_layer(L, 0, true);
+    return run_layer(L, 0, true, true);
 }
 
 int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
@@ -614,7 +627,7 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
     const LayerDesc *table = resident_table(ctx, descs, stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    return run_layer(L, 0, false);
+    return run_layer(L, 0, false, false);
 }
 
 int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
@@ -706,7 +719,7 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     if (ctx->step_mode != LYCHEE_STEP_PHASED || n_layers == 1 || (int64_t)n_layers * shape->batch > kMaxItems) {
         for (int l = 0; l < n_layers; ++l)
-            if ((rc = run_layer(L, l, false)) != LYCHEE_OK) return rc;
+            if ((rc = run_layer(L, l, false, false)) != LYCHEE_OK) return rc;
         return LYCHEE_OK;
     }
     Ranges r;

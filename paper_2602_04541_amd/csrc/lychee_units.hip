@@ -54,6 +54,8 @@ struct SharedAttn {
     float red_ml[kWaves * kMaxGroup * 2];
     float pool_ml[kWaves * 2];
     unsigned long long cand[kWaves][kCandBuf];  // per wavefront: candidates not yet flushed
+    int32_t cand_left[kWaves];                  // what each wavefront still holds when a piece ends
+    int32_t cand_base;                          // where the workgroup's last candidates go
 };
 struct SharedSelect {
     uint32_t hist[4096];                   // radix histograms; position bitmap of the ordered write
@@ -261,8 +263,24 @@ __device__ __forceinline__ float block_sum(float v, float *scratch)
 __device__ unsigned long long g_trace[kMaxWg * 8];
 __device__ int g_trace_on = 1;
 #define TRACE(slot) do { if (threadIdx.x == 0 && g_trace_on) g_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+// Lap timer of a workgroup: adds the time since the previous lap to accumulator `which` (0..3);
+// which < 0 only restarts it, which == -2 also clears the accumulators.
+__device__ unsigned long long g_lap[kMaxWg * 4];
+__device__ __forceinline__ void trace_lap(int which)
+{
+    __shared__ unsigned long long mark;
+    if (threadIdx.x == 0) {
+        const unsigned long long now = wall_clock64();
+        if (which == -2)
+            for (int i = 0; i < 4; ++i) g_lap[blockIdx.x * 4 + i] = 0;
+        if (which >= 0) g_lap[blockIdx.x * 4 + which] += now - mark;
+        mark = now;
+    }
+}
+#define TRACE_LAP(which) trace_lap(which)
 #else
 #define TRACE(slot) do { } while (0)
+#define TRACE_LAP(which) do { } while (0)
 #endif
 
 // ------------------------------------------------------------------------------ R and G
@@ -372,6 +390,10 @@ struct Emit {
 
 // Appends a wavefront's n buffered candidates to the row's list.  The counter keeps counting
 // past the capacity, which is how the select unit learns that the list is incomplete.
+// (Only a full buffer comes here.  What a wavefront holds when its piece ends is written by
+// run_piece with one reservation per workgroup: a short launch has hundreds of workgroups
+// per score row that all end at the same time, and their reservations on the row's one
+// counter are served one after the other.)
 __device__ __forceinline__ void flush_candidates(const unsigned long long *buf, int n, const Emit &em)
 {
     const int lane = threadIdx.x & 63;
@@ -397,7 +419,8 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
                                             const uint16_t *vbase, const uint4 (&qf)[NH],
                                             Acc<NH> &acc, int L, int r0, int r1,
                                             const int32_t *idx_s, const Emit &em, float sel_mul,
-                                            unsigned long long *cand_buf, float &pool_m, float &pool_l)
+                                            unsigned long long *cand_buf, int &cand_left,
+                                            float &pool_m, float &pool_l)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -454,10 +477,14 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
     issue(t0, 0, 0);
     issue(t1, 0, 1);
     TRACE(5);
+    TRACE_LAP(0);  // piece set-up, until its first loads are issued
     for (int span = 0; span < n_spans; ++span) {
         float sel0[4], sel1[4];
         consume(t0, sel0);
-        if (span == 0) TRACE(6);
+        if (span == 0) {
+            TRACE(6);
+            TRACE_LAP(1);  // until the first tile has arrived and is consumed
+        }
         __builtin_amdgcn_sched_barrier(0);
         issue(t0, span + 1, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -518,7 +545,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             }
         }
     }
-    if (!GATHER && em.list != nullptr && em.direct == 0 && cand_n > 0) flush_candidates(cand_buf, cand_n, em);
+    cand_left = cand_n;  // the caller writes these out, one reservation for the whole workgroup
 }
 
 // One (workgroup, segment) piece: rows/entries [r0, r1) of segment (b, g) for the heads in
@@ -564,6 +591,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     const uint16_t *vbase = v_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
     const float sel_mul = c.scale / (float)NH;
     float pool_m = kMinusBig, pool_l = 0.0f;  // per lane: log-sum-exp state of the pooled logits
+    int cand_left = 0;                        // candidates still in this wavefront's LDS buffer
 
     if (GATHER) {
         // rows r0 .. r1-1 of the gathered sequence are row (r mod 2^shift) of set entry r >> shift
@@ -575,13 +603,15 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             __syncthreads();  // the previous chunk's readers are done
             for (int i = threadIdx.x; i < n_entries; i += kThreads) sh.idx_s[i] = gload(idx_src + (e0 >> shift) + i);
             __syncthreads();
-            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr, pool_m, pool_l);
+            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr, cand_left, pool_m, pool_l);
         }
     } else {
-        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave], pool_m, pool_l);
+        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave], cand_left, pool_m, pool_l);
     }
+    const bool collects = !GATHER && em.list != nullptr && em.direct == 0;  // the same in every wavefront
 
     TRACE(7);
+    TRACE_LAP(2);  // streaming
     at_rows_done();  // what the caller wants in flight while the partial is merged and written
     // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).
     const float c_log2e = c.scale_log2e;
@@ -620,6 +650,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         sh.pool_ml[2 * wave] = pool_m;
         sh.pool_ml[2 * wave + 1] = pool_l;
     }
+    if (collects && lane == 0) sh.cand_left[wave] = cand_left;
     if (rs == 0) {
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
@@ -633,6 +664,18 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         }
     }
     __syncthreads();
+    if (collects && threadIdx.x == kThreads - 1) {
+        // room for the workgroup's last candidates, asked for by a thread that writes no
+        // partial: the answer is on its way while the others merge
+        int n = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) n += sh.cand_left[w];
+        int base = 0;
+        if (n > 0)
+            base = __hip_atomic_fetch_add((LYCHEE_GLOBAL int32_t *)em.count, (int32_t)n, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
+        sh.cand_base = base;
+    }
     if (threadIdx.x < kHeadDim) {
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
@@ -664,6 +707,14 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         for (int w = 0; w < kWaves; ++w) l = fmaf(fast_exp2((sh.pool_ml[2 * w] - M) * kLog2e), sh.pool_ml[2 * w + 1], l);
         gstore(em.pool_ml + 2 * slot, M);
         gstore(em.pool_ml + 2 * slot + 1, l);
+    }
+    if (collects) {
+        __syncthreads();
+        int base = sh.cand_base;
+        for (int w = 0; w < wave; ++w) base += sh.cand_left[w];
+        const unsigned long long *buf = sh.cand[wave];
+        for (int i = lane; i < cand_left; i += 64)
+            if (base + i < em.cap) gstore(em.list + base + i, buf[i]);
     }
 }
 
@@ -1463,58 +1514,91 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
     // one segment per retrieval (sparse) KV head of the layer
     if (threadIdx.x < c.batch) pool.len[threadIdx.x] = clamp_len(c.lengths[threadIdx.x], c.max_len);
     __syncthreads();
-    {
-        constexpr int kPer = kMaxItems / kThreads;
-        uint32_t blocks[kPer], sum = 0;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            const int it = threadIdx.x * kPer + i;
-            blocks[i] = 0;
-            if (it < n_items) {
-                const int li = it / c.batch;
-                const int L = pool.len[it % c.batch];
-                if (li < P.r_count) {
-                    blocks[i] = (uint32_t)(layers[P.r_first + li].n_rgroups * ((L + kBlockRows - 1) / kBlockRows));
-                } else {
-                    blocks[i] = (uint32_t)(layers[P.g_first + li - P.r_count].n_sgroups *
-                                           ((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c)));
-                }
-            }
-            sum += blocks[i];
-        }
-        uint32_t total;
-        uint32_t at = block_scan(sum, pool.scan, total) - sum;
-        if (threadIdx.x == 0) pool.ipre[0] = 0;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            at += blocks[i];
-            pool.ipre[threadIdx.x * kPer + i + 1] = (int32_t)at;
-        }
-    }
-    __syncthreads();
-    const int T = pool.ipre[n_items];
     // Most of the pooled blocks are dealt statically, an equal contiguous run per workgroup;
     // the last tail_permille/1000 of them are cut into chunks that workgroups claim through
     // a counter as they finish, which evens out CUs that stream at different speeds.  Runs
     // and chunks in ascending block order are the launch's *work items*; the pieces of a
     // segment sit in consecutive items, and a piece's partial slot is its item's distance to
     // the first item of the segment, whoever ran it.
-    // (a launch too short to hold several chunks per workgroup is dealt statically: the
-    // chunks' start-up cost would outweigh what they level out)
-    const int tail = (int64_t)T >= 8ll * c.chunk_blocks * W ? c.tail_permille : 0;
-    const int share = (int)((int64_t)T * (1000 - tail) / (1000ll * W));
-    const int T_static = share * W;
+    // A launch too short to hold several chunks per workgroup is dealt statically (the chunks'
+    // start-up cost would outweigh what they level out), and then nothing evens out a
+    // workgroup whose run crosses from one segment into the next and pays a second piece's
+    // start-up and merge: such a launch pads every segment to a whole number of runs (`pad`),
+    // so that each workgroup has one piece, when that lengthens the runs by little.
+    int share, pad = 0;
+    {
+        constexpr int kPer = kMaxItems / kThreads;
+        uint32_t nseg[kPer], nb[kPer];  // per item: segments, blocks per segment
+        unsigned long long sum = 0;      // segments << 32 | blocks
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int it = threadIdx.x * kPer + i;
+            nseg[i] = nb[i] = 0;
+            if (it < n_items) {
+                const int li = it / c.batch;
+                const int L = pool.len[it % c.batch];
+                if (li < P.r_count) {
+                    nseg[i] = (uint32_t)layers[P.r_first + li].n_rgroups;
+                    nb[i] = (uint32_t)((L + kBlockRows - 1) / kBlockRows);
+                } else {
+                    nseg[i] = (uint32_t)layers[P.g_first + li - P.r_count].n_sgroups;
+                    nb[i] = (uint32_t)((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c));
+                }
+                if (nb[i] == 0) nseg[i] = 0;
+            }
+            sum += ((unsigned long long)nseg[i] << 32) | (unsigned long long)(nseg[i] * nb[i]);
+        }
+        unsigned long long total64;
+        uint32_t at = (uint32_t)(block_scan64(sum, pool.scan64, total64) - sum);
+        const int T_real = (int)(uint32_t)total64;
+        const int n_segs = (int)(total64 >> 32);
+        const int tail = (int64_t)T_real >= 8ll * c.chunk_blocks * W ? c.tail_permille : 0;
+        share = (int)((int64_t)T_real * (1000 - tail) / (1000ll * W));
+        if (tail == 0 && n_segs < W && T_real > 0) {
+            // the smallest run length whose padded segments fit the W workgroups, unless it is
+            // much longer than the unpadded run: with many short segments the padding would
+            // idle more than the second pieces cost
+            const int s0 = (T_real + W - 1) / W;
+            const int s_last = s0 + (s0 / 8 > 1 ? s0 / 8 : 1);
+            int s = s0;
+            for (; s <= s_last; ++s) {
+                uint32_t runs = 0, all;
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) runs += nseg[i] * ((nb[i] + s - 1) / s);
+                (void)block_scan(runs, pool.scan, all);
+                if ((int)all <= W) break;
+            }
+            if (s <= s_last) {
+                share = s;
+                pad = 1;
+                uint32_t vsum = 0, vtot;
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) vsum += nseg[i] * ((nb[i] + s - 1) / s) * s;
+                at = block_scan(vsum, pool.scan, vtot) - vsum;
+            }
+        }
+        if (threadIdx.x == 0) pool.ipre[0] = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            at += pad ? nseg[i] * ((nb[i] + share - 1) / share) * share : nseg[i] * nb[i];
+            pool.ipre[threadIdx.x * kPer + i + 1] = (int32_t)at;
+        }
+    }
+    __syncthreads();
+    const int T = pool.ipre[n_items];  // padded blocks included
+    const int T_static = pad ? T : share * W;
     const int n_static = share > 0 ? W : 0;
     const int chunk = c.chunk_blocks;
-    const int n_chunks = (T - T_static + chunk - 1) / chunk;
+    const int n_chunks = pad ? 0 : (T - T_static + chunk - 1) / chunk;
     auto item_of = [&](int blk) { return blk < T_static ? blk / share : n_static + (blk - T_static) / chunk; };
     uint32_t *counter = c.tickets + c.ticket_slot;
     uint32_t next_ticket = 0;
     if (threadIdx.x == 0) {
-        next_ticket = atomicAdd(counter, 1u);  // asked for early, looked at after the static run
+        if (n_chunks > 0) next_ticket = atomicAdd(counter, 1u);  // asked for early, looked at after the static run
         if (w == 0) c.tickets[(c.ticket_slot + kTicketRing / 2) % kTicketRing] = 0u;
     }
     TRACE(2);
+    TRACE_LAP(-2);
 
     // A piece needs its layer's descriptor before it can issue its first load.  Read through
     // the table pointer that is a chain of dependent loads; instead the descriptor is staged
@@ -1532,6 +1616,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
     int item = w;
     int x = w * share;
     int x1 = x + share;
+    x1 = x1 < T_static ? x1 : T_static;
     for (;;) {
         while (x < x1) {
             const int it = find_item(pool.ipre, n_items, x);
@@ -1555,10 +1640,12 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             const int seg_rows = gather ? gather_rows(c, len_b) : len_b;
             const int brows = gather ? gather_block(c) : kBlockRows;
             const int nb = (seg_rows + brows - 1) / brows;  // blocks per segment of this item
+            const int nbv = pad ? (nb + share - 1) / share * share : nb;  // and with its padding
             const int xo = x - pool.ipre[it];
-            const int gi = xo / nb;
-            const int blk = xo % nb;
-            const int seg_start = pool.ipre[it] + gi * nb;
+            const int gi = xo / nbv;
+            const int blk = xo % nbv;
+            if (blk >= nb) break;  // the run lies in a segment's padding (the last run of a segment ends in it)
+            const int seg_start = pool.ipre[it] + gi * nbv;
             int len = x1 - x;
             len = len < nb - blk ? len : nb - blk;
             const int r0 = blk * brows;
@@ -1627,6 +1714,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             }
             x += len;
             TRACE(3);
+            TRACE_LAP(3);  // merging and writing the partial
         }
         // next chunk: every workgroup asks until it is told that none is left
         __syncthreads();
@@ -1698,6 +1786,10 @@ __global__ void validate_idx_kernel(const int32_t *idx, const int32_t *lengths, 
 }  // namespace
 
 #ifdef LYCHEE_TRACE
+extern "C" int lychee_trace_laps(unsigned long long *host, int n_wg)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(lychee::g_lap), sizeof(unsigned long long) * 4 * n_wg) == hipSuccess ? 0 : -4;
+}
 extern "C" int lychee_trace_read(unsigned long long *host, int n_wg)
 {
     return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * n_wg) == hipSuccess ? 0 : -4;
