@@ -329,6 +329,8 @@ struct Launcher {
         p.t_first = r.t_first, p.t_count = r.t_count;
         p.s_first = r.s_first, p.s_count = r.s_count;
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.collect |= host_table[l].emit_sel;
+        for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
+        for (int l = r.g_first; l < r.g_first + r.g_count; ++l) p.n_gseg[l] = (uint8_t)host_table[l].n_sgroups;
         for (int l = r.s_first; l < r.s_first + r.s_count; ++l) p.selects |= host_table[l].n_rgroups > 0;
         const int cls = r.r_count ? LYCHEE_KERNEL_STREAM : r.g_count ? LYCHEE_KERNEL_GATHER
                         : (r.t_count || r.a_count) ? LYCHEE_KERNEL_THRESHOLD : r.c_count ? LYCHEE_KERNEL_COMBINE

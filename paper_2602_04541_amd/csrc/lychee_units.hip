@@ -1512,8 +1512,9 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
 
     // ---- the pooled row space: R items (layer, sequence) then G items, each item holding
     // one segment per retrieval (sparse) KV head of the layer
+    // (the sequence lengths go to LDS for the pieces; the item sizes below read them from memory
+    // themselves, so that those loads are not behind a barrier)
     if (threadIdx.x < c.batch) pool.len[threadIdx.x] = clamp_len(c.lengths[threadIdx.x], c.max_len);
-    __syncthreads();
     // Most of the pooled blocks are dealt statically, an equal contiguous run per workgroup;
     // the last tail_permille/1000 of them are cut into chunks that workgroups claim through
     // a counter as they finish, which evens out CUs that stream at different speeds.  Runs
@@ -1536,12 +1537,12 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             nseg[i] = nb[i] = 0;
             if (it < n_items) {
                 const int li = it / c.batch;
-                const int L = pool.len[it % c.batch];
+                const int L = clamp_len(c.lengths[it % c.batch], c.max_len);
                 if (li < P.r_count) {
-                    nseg[i] = (uint32_t)layers[P.r_first + li].n_rgroups;
+                    nseg[i] = (uint32_t)P.n_rseg[P.r_first + li];
                     nb[i] = (uint32_t)((L + kBlockRows - 1) / kBlockRows);
                 } else {
-                    nseg[i] = (uint32_t)layers[P.g_first + li - P.r_count].n_sgroups;
+                    nseg[i] = (uint32_t)P.n_gseg[P.g_first + li - P.r_count];
                     nb[i] = (uint32_t)((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c));
                 }
                 if (nb[i] == 0) nseg[i] = 0;
@@ -1554,7 +1555,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
         const int n_segs = (int)(total64 >> 32);
         const int tail = (int64_t)T_real >= 8ll * c.chunk_blocks * W ? c.tail_permille : 0;
         share = (int)((int64_t)T_real * (1000 - tail) / (1000ll * W));
-        if (tail == 0 && n_segs < W && T_real > 0) {
+        if (tail == 0 && 8 * n_segs <= W && T_real > 0) {  // (few segments: else the padding would not pay)
             // the smallest run length whose padded segments fit the W workgroups, unless it is
             // much longer than the unpadded run: with many short segments the padding would
             // idle more than the second pieces cost
