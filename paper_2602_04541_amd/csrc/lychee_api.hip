@@ -458,16 +458,17 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && n_layers > 1 &&
                         (int64_t)n_layers * shape->batch <= kMaxItems;
     if (!phased) {
-        // Layer l's output needs its partials combined, not its sets selected: the select
-        // waits for the first launch of layer l + 1, where it runs beside that layer's
-        // thresholds; the last selecting layer's gets a launch of its own.
-        for (int l = 0; l < n_layers; ++l)
-            if ((rc = run_layer(L, l, l < n_select, false, l > 0 && l - 1 < n_select ? l - 1 : -1)) != LYCHEE_OK)
-                return rc;
-        if (n_select == n_layers) {
-            Ranges last;
-            last.s_first = n_layers - 1, last.s_count = 1;
-            if ((rc = L.go(last)) != LYCHEE_OK) return rc;
+        // Layer l's output needs its partials combined, not its sets selected: where layer
+        // l + 1 starts with a launch of small units anyway (thresholds, an append), the select
+        // of layer l waits for that launch and runs beside them; otherwise it goes with the
+        // combine of its own layer.
+        auto has_first_launch = [&](int l) {
+            return l < n_layers && ((l < n_select && shape->block_size != 64) || k_new != nullptr);
+        };
+        for (int l = 0; l < n_layers; ++l) {
+            const bool prev_waits = l > 0 && l - 1 < n_select && has_first_launch(l);
+            rc = run_layer(L, l, l < n_select, !has_first_launch(l + 1), prev_waits ? l - 1 : -1);
+            if (rc != LYCHEE_OK) return rc;
         }
     } else {
         // All layers at once, one launch per phase; each phase needs only earlier phases:
