@@ -137,6 +137,34 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
                        const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The same layer (Alg. 1's per-head loop), for a caller that runs layer after layer: in Alg. 1
+ * the set S a retrieval head updates is read again only by the next layer's sparse heads, so
+ * `out` does not have to wait for it.  This call enqueues everything that `out` needs and
+ * leaves the selection (Eq. 2) of its layer PENDING; the next lychee_decode_attn_deferred call
+ * on the same context runs the pending selection in its first launch, beside its own
+ * preparations and before its sparse heads read their sets, and lychee_select_flush runs it
+ * alone.  Arguments and errors as for lychee_decode_attn, except:
+ *   workspace   lychee_step_workspace_bytes(shape, 2) bytes: the pending layer's selection
+ *               candidates live in one half while the next layer fills the other
+ *   idx_out     complete (in stream order) only after the call that runs the pending
+ *               selection; nothing else may write it in between
+ *   q           may be reused as soon as this call's work is done (the library keeps a copy of
+ *               what a selection can still need)
+ *   idx_in, k_cache, lengths (pointer AND contents), the workspace: unchanged until the
+ *               pending selection has run.  In particular flush before the lengths grow for
+ *               the next token, and before the workspace serves any other call.
+ * While a selection is pending, the next deferred call must pass the same shape, lengths
+ * pointer and workspace (else EINVAL: flush first).  With block_size 64 nothing is left
+ * pending (the selection has no later launch to join and is enqueued with this call).
+ * lychee_select_flush: enqueues a pending selection, if there is one; EINVAL for a NULL ctx.
+ */
+int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
+                                const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
+                                const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+int lychee_select_flush(lychee_ctx *ctx, void *hip_stream);
+
 /* Dense decode attention on the same buffers: every head runs Eq. 1 and o = A V, nothing
  * is selected.  The in-run speed baseline; `shape->k` is ignored (any value >= 1). */
 int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,

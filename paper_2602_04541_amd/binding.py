@@ -27,7 +27,8 @@ RULE_THRESHOLD, RULE_TOP_P = 1, 2
 EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
     "lychee_step_workspace_bytes",
-    "lychee_decode_attn", "lychee_dense_decode_attn", "lychee_decode_step",
+    "lychee_decode_attn", "lychee_decode_attn_deferred", "lychee_select_flush",
+    "lychee_dense_decode_attn", "lychee_decode_step",
     "lychee_dense_decode_step", "lychee_decode_step_append", "lychee_append_kv", "lychee_select_stats",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
@@ -66,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.lychee_step_workspace_bytes.argtypes = [shp, i32]
     lib.lychee_step_workspace_bytes.restype = sz
     lib.lychee_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lychee_decode_attn_deferred.argtypes = lib.lychee_decode_attn.argtypes
+    lib.lychee_select_flush.argtypes = [vp, vp]
     lib.lychee_dense_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_dense_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -175,6 +178,20 @@ class Context:
                                        _ptr(idx_out), _ptr(lengths), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(),
                                        _stream(stream)), "lychee_decode_attn")
+
+    def decode_attn_deferred(self, shape: Shape, q, k_cache, v_cache, head_type_mask: np.ndarray,
+                             idx_in, out, idx_out, lengths, workspace, stream=None) -> None:
+        """The layer call that leaves its selection for the next such call (or select_flush);
+        `workspace` holds two layers (alloc_workspace(..., n_layers=2))."""
+        mask = np.ascontiguousarray(head_type_mask, dtype=np.uint8)
+        _check(_lib.lychee_decode_attn_deferred(self._h, ctypes.byref(shape), _ptr(q), _ptr(k_cache),
+                                                _ptr(v_cache), mask.ctypes.data, _ptr(idx_in), _ptr(out),
+                                                _ptr(idx_out), _ptr(lengths), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(),
+                                                _stream(stream)), "lychee_decode_attn_deferred")
+
+    def select_flush(self, stream=None) -> None:
+        _check(_lib.lychee_select_flush(self._h, _stream(stream)), "lychee_select_flush")
 
     def dense_decode_attn(self, shape: Shape, q, k_cache, v_cache, out, lengths, workspace,
                           stream=None) -> None:

@@ -48,6 +48,15 @@ struct lychee_ctx {
         size_t offset, bytes;
     };
     std::vector<Cached> cache;
+    // A layer call whose select has been left for the next call (lychee_decode_attn_deferred).
+    struct Pending {
+        bool active = false;
+        LayerDesc desc;              // the layer, its queries redirected to the workspace's copy
+        lychee_shape shape;
+        const int32_t *lengths = nullptr;
+        void *workspace = nullptr;
+        int slot = 0;                // which of the workspace's two layer slots holds its scratch
+    } pending;
 };
 
 namespace {
@@ -73,7 +82,7 @@ int32_t list_row_entries(int32_t max_len, int32_t k)
 
 // Per-layer scratch, laid out layer after layer.
 struct Workspace {
-    size_t sel, part_o, part_ml, part_count, part_pool, list, list_count, thr, idx_set;  // offsets inside a layer
+    size_t sel, part_o, part_ml, part_count, part_pool, list, list_count, thr, idx_set, q_keep;  // offsets inside a layer
     size_t layer_bytes, total;
     int32_t sel_stride, list_row;
 };
@@ -100,6 +109,7 @@ Workspace carve(const lychee_shape &s, int n_layers)
     w.list_count = take(groups * sizeof(int32_t));
     w.thr = take(groups * sizeof(uint32_t));
     w.idx_set = take(groups * s.k * sizeof(int32_t));
+    w.q_keep = take(heads * kHeadDim * sizeof(uint16_t));
     w.layer_bytes = off;
     w.total = off * (size_t)n_layers;
     return w;
@@ -601,6 +611,97 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     return run_layer(L, 0, true, true);
+}
+
+int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
+                                const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
+                                const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, 2);
+    if (rc != LYCHEE_OK) return rc;
+    rc = check_mask(shape, head_type_mask, idx_in != nullptr);
+    if (rc != LYCHEE_OK) return rc;
+    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr ||
+        idx_out == nullptr || lengths == nullptr)
+        return LYCHEE_EINVAL;
+    if (!aligned(q, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 16) ||
+        !aligned(idx_out, 4) || !aligned(idx_in, 4) || !aligned(lengths, 4))
+        return LYCHEE_EINVAL;
+    if (idx_in == idx_out) return LYCHEE_EINVAL;
+    lychee_ctx::Pending &pd = ctx->pending;
+    // a pending select reads its layer's half of this workspace with this shape and these lengths
+    if (pd.active && (pd.workspace != workspace || pd.lengths != lengths || memcmp(&pd.shape, shape, sizeof *shape) != 0))
+        return LYCHEE_EINVAL;
+    if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, 2);
+    char *ws = static_cast<char *>(workspace);
+    const int slot = pd.active ? 1 - pd.slot : 0;
+    // With block-granular sets a layer has no threshold launch for the next layer's call to
+    // carry a select in: the select stays with the layer's combine and nothing is left pending.
+    const bool defer = shape->block_size != 64;
+    std::vector<LayerDesc> descs(pd.active ? 2 : 1);
+    LayerDesc &d = descs[0];
+    memset(&d, 0, sizeof d);
+    d.q = static_cast<const uint16_t *>(q);
+    d.k_cache = static_cast<const uint16_t *>(k_cache);
+    d.v_cache = static_cast<const uint16_t *>(v_cache);
+    d.out = static_cast<uint16_t *>(out);
+    set_groups(d, *shape, head_type_mask);
+    set_scratch(d, w, ws, slot);
+    if (defer) d.q_keep = reinterpret_cast<uint16_t *>(ws + (size_t)slot * w.layer_bytes + w.q_keep);
+    d.idx_out = idx_out;
+    for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = idx_in;
+    d.emit_sel = 1;
+    d.copy_keep = 1;
+    if (pd.active) descs[1] = pd.desc;
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
+    Ranges t;
+    if (defer) t.t_first = 0, t.t_count = 1;
+    if (pd.active) t.s_first = 1, t.s_count = 1;
+    if ((rc = L.go(t)) != LYCHEE_OK) return rc;
+    pd.active = false;
+    Ranges a;
+    a.r_first = a.g_first = 0, a.r_count = a.g_count = 1;
+    if ((rc = L.go(a)) != LYCHEE_OK) return rc;
+    Ranges b;
+    b.c_first = 0, b.c_count = 1;
+    if (!defer) b.s_first = 0, b.s_count = 1;
+    if ((rc = L.go(b)) != LYCHEE_OK) return rc;
+    if (defer) {
+        pd.active = true;
+        pd.desc = d;
+        pd.desc.q = d.q_keep;  // the caller's q may hold the next layer's queries by then
+        pd.desc.q_keep = nullptr;
+        pd.shape = *shape;
+        pd.lengths = lengths;
+        pd.workspace = workspace;
+        pd.slot = slot;
+    }
+    return LYCHEE_OK;
+}
+
+int lychee_select_flush(lychee_ctx *ctx, void *hip_stream)
+{
+    if (ctx == nullptr) return LYCHEE_EINVAL;
+    lychee_ctx::Pending &pd = ctx->pending;
+    if (!pd.active) return LYCHEE_OK;
+    int rc = make_current(ctx);
+    if (rc != LYCHEE_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(pd.shape, 2);
+    std::vector<LayerDesc> descs(1, pd.desc);
+    const LayerDesc *table = resident_table(ctx, descs, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    const Launcher L{ctx, pd.shape, w, pd.lengths, table, descs.data(), stream};
+    Ranges sl;
+    sl.s_first = 0, sl.s_count = 1;
+    if ((rc = L.go(sl)) != LYCHEE_OK) return rc;
+    pd.active = false;
+    return LYCHEE_OK;
 }
 
 int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,

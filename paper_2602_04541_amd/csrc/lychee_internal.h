@@ -65,6 +65,8 @@ struct LayerDesc {
     const uint16_t *k_new, *v_new;  // bf16 [B][H_kv][128]: the decoded token's rows, appended to the
                                     // caches by an A unit (nullptr: the caller has appended them)
     uint16_t *out;         // bf16 [B][H_q][128]
+    uint16_t *q_keep;      // bf16 [B][H_q][128] or nullptr: where T units leave a copy of their group's
+                           // queries, for a select that runs after the caller has reused q
     float *sel;            // [B][n_rgroups][sel_stride] pooled selection scores (scaled logits),
                            // written only for a row whose candidate list cannot be used
     float *part_o;         // [B*H_q][part_stride][128] un-normalised partial outputs

@@ -877,6 +877,11 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     const int n = budget_of(c, L);
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
+    if (p.q_keep != nullptr && (int)threadIdx.x < c.group * (kHeadDim / 8)) {
+        // the group's query rows (consecutive heads, 16 chunks of 16 bytes each)
+        const int64_t at = ((int64_t)b * c.n_q_heads + p.rgroup[rgi] * c.group) * kHeadDim + threadIdx.x * 8;
+        *(LYCHEE_GLOBAL u32x4_t *)(p.q_keep + at) = *(const LYCHEE_GLOBAL u32x4_t *)(p.q + at);
+    }
     if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
         // everything is selected anyway (no candidates wanted), or every row is a candidate
         // (a probability rule may keep fewer than everything: it still needs the candidates)

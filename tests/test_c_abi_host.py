@@ -87,6 +87,11 @@ def test_calls_reject_null_context_without_touching_a_gpu(lb):
     assert lib.lychee_set_option(None, lb.OPT_WG_PER_CU, 2) == lb.EINVAL
     lib.lychee_dense_decode_attn.argtypes = lb._lib.lychee_dense_decode_attn.argtypes
     assert lib.lychee_dense_decode_attn(None, ctypes.byref(s), None, None, None, None, None, None, 0, None) == lb.EINVAL
+    lib.lychee_decode_attn_deferred.argtypes = lb._lib.lychee_decode_attn_deferred.argtypes
+    assert lib.lychee_decode_attn_deferred(None, ctypes.byref(s), None, None, None, None, None, None, None, None,
+                                           None, 0, None) == lb.EINVAL
+    lib.lychee_select_flush.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.lychee_select_flush(None, None) == lb.EINVAL
 
 
 def test_create_fails_cleanly_without_a_gpu(lb):

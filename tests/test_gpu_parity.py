@@ -854,3 +854,86 @@ def test_probability_rule_step_feeds_variable_sets_to_the_next_layers(ctx):
     got = idx_final.cpu().numpy()
     sizes = (got >= 0).sum(axis=2)
     assert (sizes >= 1).all() and (sizes <= k).all()
+
+
+# ------------------------------------------------------------------ layer calls with a pending select
+@pytest.mark.parametrize("margin,block", [(60, 1), (-1000, 1), (60, 64)])
+def test_layer_calls_that_leave_their_select_pending(ctx, margin, block):
+    """Layer after layer through lychee_decode_attn_deferred, the way a model would call it: one
+    query buffer, overwritten with the next layer's queries as soon as a call is enqueued.  Each
+    layer's selection runs inside the next call (or the flush) and must still see its own layer's
+    queries - also on the route that recomputes the whole score row (margin -1000).  Outputs and
+    every layer's sets against the oracle chain."""
+    lb = H.binding()
+    n_layers = 5
+    k = 24 if block == 64 else 700
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=12000, k=k, n_layers=n_layers, planted=48)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=12000) for l in range(n_layers)]
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx, block=block)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 12000, k, kv=layers[0].k_cache, block_size=block)
+    ws = lb.alloc_workspace(shape, n_layers=2)
+    ws.fill_(0xFF)
+    q_buf = torch.empty_like(layers[0].q)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    sets = [torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda") for _ in layers]
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    few0, many0 = ctx.select_stats()
+    ctx.set_option(lb.OPT_SELECT_MARGIN, margin)
+    try:
+        for rep in range(2):        # the second pass finds both halves of the workspace used
+            for l, ly in enumerate(layers):
+                _say("deferred layer call %d (margin %d, block %d, pass %d)" % (l, margin, block, rep))
+                q_buf.copy_(ly.q)   # stream order: after the previous call's work, before its select has run
+                ctx.decode_attn_deferred(shape, q_buf, ly.k_cache, ly.v_cache, ly.mask,
+                                         sets[l - 1] if l else None, outs[l], sets[l], lens, ws)
+            q_buf.zero_()
+            ctx.select_flush()
+            ctx.select_flush()      # nothing pending any more: a no-op
+            torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_SELECT_MARGIN, 60)
+    few, many = ctx.select_stats()
+    if margin == -1000:
+        assert few - few0 > 0, "the recomputing route did not run"
+    G = w.group
+    for l, ly in enumerate(layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "deferred layer %d" % l)
+        got = sets[l].cpu().numpy()
+        for g in range(w.n_kv_heads):
+            if ly.mask[g * G:(g + 1) * G].any():
+                sc = H.unit_scores(refs[l][2][0, g], int(ly.lengths[0]), block)
+                ok, _, msg = H.index_sets_match(got[0, g], refs[l][1][0, g], sc, k, H.TIE_REL)
+                assert ok, "layer %d head %d: %s" % (l, g, msg)
+            else:
+                assert (got[0, g] == refs[l][1][0, g]).all(), "layer %d head %d: inherited set not copied" % (l, g)
+
+
+def test_a_pending_select_pins_its_workspace_and_shape(ctx):
+    lb = H.binding()
+    w = wl.scaled(wl.WORKLOADS["c1"], max_len=6000, k=100)
+    inp = wl.make_layer(w, device="cuda", l_cap=6000)
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 6000, w.k, kv=inp.k_cache)
+    ws2 = lb.alloc_workspace(shape, n_layers=2)
+    other = lb.alloc_workspace(shape, n_layers=2)
+    out = torch.zeros_like(inp.q)
+    idx_a = torch.zeros((w.batch, w.n_kv_heads, w.k), dtype=torch.int32, device="cuda")
+    idx_b = torch.zeros_like(idx_a)
+    lens = torch.from_numpy(inp.lengths).cuda()
+    ones = np.ones(w.n_q_heads, np.uint8)
+    with pytest.raises(lb.LycheeError) as e:      # a one-layer workspace is too small
+        ctx.decode_attn_deferred(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_a, lens,
+                                 lb.alloc_workspace(shape))
+    assert e.value.code == lb.EWORKSPACE
+    ctx.decode_attn_deferred(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_a, lens, ws2)
+    with pytest.raises(lb.LycheeError) as e:      # another workspace while a select is pending
+        ctx.decode_attn_deferred(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_b, lens, other)
+    assert e.value.code == lb.EINVAL
+    ctx.select_flush()
+    ctx.decode_attn_deferred(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_b, lens, other)
+    ctx.select_flush()
+    torch.cuda.synchronize()
+    assert torch.equal(idx_a, idx_b)
