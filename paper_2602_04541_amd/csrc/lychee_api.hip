@@ -340,6 +340,11 @@ struct Launcher {
         p.s_first = r.s_first, p.s_count = r.s_count;
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.collect |= host_table[l].emit_sel;
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
+        for (int l = r.t_first; l < r.t_first + r.t_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
+        for (int l = r.s_first; l < r.s_first + r.s_count; ++l) {
+            p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
+            p.keeps[l] = (uint8_t)(host_table[l].copy_keep != 0);
+        }
         for (int l = r.g_first; l < r.g_first + r.g_count; ++l) p.n_gseg[l] = (uint8_t)host_table[l].n_sgroups;
         for (int l = r.s_first; l < r.s_first + r.s_count; ++l) p.selects |= host_table[l].n_rgroups > 0;
         const int cls = r.r_count ? LYCHEE_KERNEL_STREAM : r.g_count ? LYCHEE_KERNEL_GATHER

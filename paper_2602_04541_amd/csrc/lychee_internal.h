@@ -102,10 +102,10 @@ struct LaunchPlan {
     int32_t s_first, s_count;    // select (and set copies)
     int32_t collect;             // some R layer of the launch collects selection candidates
     int32_t selects;             // some S layer of the launch has a retrieval group to select for
-    // segments per (layer, sequence) item of the pooled launches, by table index: what
-    // LayerDesc::n_rgroups / n_sgroups say, here so that every workgroup's prologue reads
-    // them from the kernel arguments instead of all of them loading the same table lines
-    uint8_t n_rseg[kMaxLayers], n_gseg[kMaxLayers];
+    // Per layer of the launch's ranges, by table index: what LayerDesc::n_rgroups / n_sgroups /
+    // copy_keep say, here so that every workgroup's prologue reads them from the kernel
+    // arguments instead of all of them loading the same table lines
+    uint8_t n_rseg[kMaxLayers], n_gseg[kMaxLayers], keeps[kMaxLayers];
 };
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream);

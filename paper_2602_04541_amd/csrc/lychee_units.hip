@@ -873,7 +873,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     const int wave = threadIdx.x >> 6;
     const int rs = lane >> 4;
     const int ch = lane & 15;
-    const int L = clamp_len(c.lengths[b], c.max_len);
+    const int L = pool.len[b];  // staged by the kernel, clamped
     const int n = budget_of(c, L);
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
@@ -1318,7 +1318,7 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
     const int rgi = p.rindex[g];
-    const int len = clamp_len(c.lengths[b], c.max_len);
+    const int len = pool.len[b];  // staged by the kernel, clamped
     const int L = units_of(c, len);  // what is ranked: positions, or blocks of positions
     const int n = budget_of(c, L);
     const bool by_prob = PROB && c.prob_rule != 0;
@@ -1412,52 +1412,76 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
 {
     __shared__ SharedUnit su;
     __shared__ SharedPool pool;
+    __shared__ __align__(16) uint32_t small_desc[kDescWords];  // the current unit's layer descriptor
     const Common &c = P.c;
     const LayerDesc *layers = P.layers;
     const int w = blockIdx.x;
     const int W = c.n_wg;
     TRACE(0);
     if (w == 0 && (int)threadIdx.x < c.n_clear) c.tickets[c.clear_slot[threadIdx.x]] = 0u;
+    // the sequence lengths: asked for now, in LDS by the time the unit tables below are built
+    if ((int)threadIdx.x < c.batch) pool.len[threadIdx.x] = clamp_len(c.lengths[threadIdx.x], c.max_len);
 
     // Kinds in a fixed order (S on retrieval groups, C, T, S set copies, A); within a kind
     // layer by layer.
     {
-        uint32_t cnt[5] = {0, 0, 0, 0, 0};
+        // (C and A units are the same number per layer: their tables are arithmetic.  The three
+        // other kinds take two scans: S units and set copies range over the same layers.)
         const int t = threadIdx.x;
+        unsigned long long cnt_s = 0;  // S units | set copies << 32
+        uint32_t cnt_t = 0;
         if (t < P.s_count) {
-            const LayerDesc &L = layers[P.s_first + t];
-            cnt[0] = (uint32_t)(c.batch * L.n_rgroups);
-            cnt[3] = L.copy_keep ? (uint32_t)(c.batch * (c.n_kv_heads - L.n_rgroups)) : 0u;
+            const int n_r = P.n_rseg[P.s_first + t];
+            cnt_s = (unsigned long long)(c.batch * n_r);
+            if (P.keeps[P.s_first + t]) cnt_s |= (unsigned long long)(c.batch * (c.n_kv_heads - n_r)) << 32;
         }
-        if (t < P.c_count) cnt[1] = (uint32_t)(c.batch * c.n_q_heads);
-        if (t < P.t_count) cnt[2] = (uint32_t)(c.batch * layers[P.t_first + t].n_rgroups);
-        if (t < P.a_count) cnt[4] = 1u;
+        if (t < P.t_count) cnt_t = (uint32_t)(c.batch * P.n_rseg[P.t_first + t]);
         uint32_t tot[5];
-#pragma unroll
-        for (int kd = 0; kd < 5; ++kd) {
-            const uint32_t incl = block_scan(cnt[kd], pool.scan, tot[kd]);
-            if (kd < 4) {
-                if (t < kMaxLayers) pool.upre[kd][t + 1] = (int32_t)incl;
-                if (t == 0) pool.upre[kd][0] = 0;
-            }
+        unsigned long long tot_s;
+        const unsigned long long incl_s = block_scan64(cnt_s, pool.scan64, tot_s);
+        const uint32_t incl_t = block_scan(cnt_t, pool.scan, tot[2]);
+        tot[0] = (uint32_t)tot_s;
+        tot[3] = (uint32_t)(tot_s >> 32);
+        tot[1] = (uint32_t)(P.c_count * c.batch * c.n_q_heads);
+        tot[4] = (uint32_t)P.a_count;
+        if (t < kMaxLayers) {
+            pool.upre[0][t + 1] = (int32_t)(uint32_t)incl_s;
+            pool.upre[3][t + 1] = (int32_t)(uint32_t)(incl_s >> 32);
+            pool.upre[2][t + 1] = (int32_t)incl_t;
         }
+        if (t == 0) pool.upre[0][0] = pool.upre[2][0] = pool.upre[3][0] = 0;
         __syncthreads();
         const int n_small = (int)(tot[0] + tot[1] + tot[2] + tot[3] + tot[4]);
+        // A unit reads a dozen fields of its layer's descriptor, several of them pointers it
+        // then loads through: read from the table that is a chain of dependent loads (4 to 5 us
+        // before a select unit had its candidate count).  The workgroup fetches the whole
+        // descriptor into LDS at once instead; which layer a unit belongs to follows from the
+        // kernel arguments alone.
+        int held = -1;
+        auto stage = [&](int layer) -> const LayerDesc & {
+            if (layer != held) {  // (the previous unit's readers are behind the barrier that ends a unit)
+                if (threadIdx.x < kDescWords)
+                    small_desc[threadIdx.x] = gload(reinterpret_cast<const uint32_t *>(layers + layer) + threadIdx.x);
+                held = layer;
+                __syncthreads();
+            }
+            return *reinterpret_cast<const LayerDesc *>(small_desc);
+        };
         for (int j = w; j < n_small; j += W) {
             int u = j;
             if (u < (int)tot[0]) {
                 const int li = find_item(pool.upre[0], P.s_count, u);
-                const LayerDesc &L = layers[P.s_first + li];
+                const LayerDesc &L = stage(P.s_first + li);
                 u -= pool.upre[0][li];
                 const int b = u / L.n_rgroups;
                 if (SELECTS == 1) select_unit<false>(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
                 if (SELECTS == 2) select_unit<true>(c, L, b, L.rgroup[u % L.n_rgroups], su.sel, pool);
             } else if ((u -= (int)tot[0]) < (int)tot[1]) {
                 const int li = u / (c.batch * c.n_q_heads);
-                combine_unit(c, layers[P.c_first + li], u % (c.batch * c.n_q_heads), su.comb, pool);
+                combine_unit(c, stage(P.c_first + li), u % (c.batch * c.n_q_heads), su.comb, pool);
             } else if ((u -= (int)tot[1]) < (int)tot[2]) {
                 const int li = find_item(pool.upre[2], P.t_count, u);
-                const LayerDesc &L = layers[P.t_first + li];
+                const LayerDesc &L = stage(P.t_first + li);
                 u -= pool.upre[2][li];
                 const int rgi = u % L.n_rgroups;
                 const int b = u / L.n_rgroups;
@@ -1468,10 +1492,10 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
                 default: threshold_unit<4>(c, L, b, rgi, su.sel, pool); break;
                 }
             } else if ((u -= (int)tot[2]) >= (int)tot[3]) {  // append: one unit per layer
-                append_unit(c, layers[P.a_first + u - (int)tot[3]]);
+                append_unit(c, stage(P.a_first + u - (int)tot[3]));
             } else {  // copy of the set of a KV head whose group holds no retrieval head
                 const int li = find_item(pool.upre[3], P.s_count, u);
-                const LayerDesc &L = layers[P.s_first + li];
+                const LayerDesc &L = stage(P.s_first + li);
                 u -= pool.upre[3][li];
                 const int n_keep = c.n_kv_heads - L.n_rgroups;
                 const int b = u / n_keep;
