@@ -1,0 +1,248 @@
+// Device-side building blocks of the work-unit kernels (included by lychee_units.hip only):
+// the LDS layout of a workgroup, global-memory accessors, the bf16 dot product, wavefront and
+// workgroup reductions and scans, and the trace hooks of probe builds.
+#pragma once
+#include "lychee_internal.h"
+
+namespace lychee {
+namespace {
+
+// ------------------------------------------------------------------------------ LDS layout
+struct SharedAttn {
+    int32_t idx_s[kIdxChunk];
+    float red_o[kWaves * kMaxGroup * kHeadDim];
+    float red_ml[kWaves * kMaxGroup * 2];
+    float pool_ml[kWaves * 2];
+    unsigned long long cand[kWaves][kCandBuf];  // per wavefront: candidates not yet flushed
+    int32_t cand_left[kWaves];                  // what each wavefront still holds when a piece ends
+    int32_t cand_base;                          // where the workgroup's last candidates go
+};
+struct SharedSelect {
+    uint32_t hist[4096];                   // radix histograms; position bitmap of the ordered write
+    uint32_t samp[kSampleTilesMax * 16];   // ordered keys of the threshold sample
+    uint32_t found[2];
+};
+struct SharedCombine {
+    float w[kMaxWg];
+    float red[(kThreads / 32) * kHeadDim];
+};
+union SharedUnit {
+    SharedSelect sel;
+    SharedCombine comb;
+};
+struct SharedPool {
+    int32_t ipre[kMaxItems + 1];         // first pooled block of every (layer, sequence) item
+    int32_t upre[4][kMaxLayers + 1];     // first small unit of every layer, per unit kind
+    int32_t len[kMaxBatch];
+    uint32_t scan[kWaves + 1];
+    unsigned long long scan64[kWaves + 1];
+    float fred[kWaves + 1];
+};
+
+// ------------------------------------------------------------------------------ primitives
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float x)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kCtrl, 0xF, 0xF, false));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the same bits.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_f32<0xB1>(x);   // quad_perm [1,0,3,2]  : lane ^ 1
+    x += dpp_f32<0x4E>(x);   // quad_perm [2,3,0,1]  : lane ^ 2
+    x += dpp_f32<0x141>(x);  // row_half_mirror      : the other quad of the 8-lane half
+    x += dpp_f32<0x140>(x);  // row_mirror           : the other half of the 16-lane row
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xFFFF0000u); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Every buffer the units touch is device global memory, but most pointers reach the kernel
+// through the descriptor table, where the compiler can no longer see that.  Generic-address
+// ("flat") accesses make it wait for *all* outstanding loads before each use, which breaks the
+// load pipeline of the streaming loop; so every access goes through these casts.
+#define LYCHEE_GLOBAL __attribute__((address_space(1)))
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename T>
+__device__ __forceinline__ T gload(const T *p)
+{
+    return *(const LYCHEE_GLOBAL T *)p;
+}
+template <typename T>
+__device__ __forceinline__ void gstore(T *p, T v)
+{
+    *(LYCHEE_GLOBAL T *)p = v;
+}
+__device__ __forceinline__ float4 gload_f4(const float *p)
+{
+    const f32x4_t r = *(const LYCHEE_GLOBAL f32x4_t *)p;
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ uint4 gload_u4(const void *p)
+{
+    const u32x4_t r = *(const LYCHEE_GLOBAL u32x4_t *)p;
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+// 16-byte streaming load: cache rows are read once per step and never again.
+__device__ __forceinline__ uint4 load_stream16(const uint16_t *p)
+{
+    const u32x4_t r = __builtin_nontemporal_load((const LYCHEE_GLOBAL u32x4_t *)p);
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+__device__ __forceinline__ uint32_t ordered_key(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int clamp_len(int L, int max_len) { return L < 1 ? 1 : (L > max_len ? max_len : L); }
+
+// Selectable units of a sequence of L rows: its positions, or its blocks of 64 positions
+// (the last one may be short) in the block-granular variant (App. C).
+__device__ __forceinline__ int units_of(const Common &c, int L)
+{
+    return (L + (1 << c.block_shift) - 1) >> c.block_shift;
+}
+
+// Units selected for a sequence of L units: Eq. 2's fixed budget, min(k, L), or under the
+// Ratio rule (Sec. 4.4.1: a budget proportional to the sequence length) the rounded-up share
+// keep_ppm / 10^6 of L, at least 1 and at most the fixed budget.
+__device__ __forceinline__ int budget_of(const Common &c, int L)
+{
+    int n = c.k < L ? c.k : L;
+    if (c.keep_ppm > 0) {
+        long long r = ((long long)L * c.keep_ppm + 999999) / 1000000;
+        r = r < 1 ? 1 : r;
+        n = r < n ? (int)r : n;
+    }
+    return n;
+}
+
+// Inclusive prefix sum over the 256 threads of the workgroup; `total` = sum of all.
+__device__ __forceinline__ uint32_t block_scan(uint32_t v, uint32_t *wave_tot, uint32_t &total)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();  // wave_tot may still be read by the previous call
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = wave_tot[w];
+        before += (w < wave) ? t : 0u;
+        all += t;
+    }
+    total = all;
+    return x + before;
+}
+
+// The same for four 16-bit counts packed in 64 bits (no field may overflow).
+__device__ __forceinline__ unsigned long long block_scan64(unsigned long long v, unsigned long long *wave_tot,
+                                                           unsigned long long &total)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    unsigned long long x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    unsigned long long before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const unsigned long long t = wave_tot[w];
+        before += (w < wave) ? t : 0ull;
+        all += t;
+    }
+    total = all;
+    return x + before;
+}
+
+__device__ __forceinline__ float block_max(float v, float *scratch)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, scratch[w]);
+    return r;
+}
+
+__device__ __forceinline__ float block_sum(float v, float *scratch)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r += scratch[w];
+    return r;
+}
+
+#ifdef LYCHEE_TRACE
+__device__ unsigned long long g_trace[kMaxWg * 8];
+__device__ int g_trace_on = 1;
+#define TRACE(slot) do { if (threadIdx.x == 0 && g_trace_on) g_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+// Lap timer of a workgroup: adds the time since the previous lap to accumulator `which` (0..3);
+// which < 0 only restarts it, which == -2 also clears the accumulators.
+__device__ unsigned long long g_lap[kMaxWg * 4];
+__device__ __forceinline__ void trace_lap(int which)
+{
+    __shared__ unsigned long long mark;
+    if (threadIdx.x == 0) {
+        const unsigned long long now = wall_clock64();
+        if (which == -2)
+            for (int i = 0; i < 4; ++i) g_lap[blockIdx.x * 4 + i] = 0;
+        if (which >= 0) g_lap[blockIdx.x * 4 + which] += now - mark;
+        mark = now;
+    }
+}
+#define TRACE_LAP(which) trace_lap(which)
+#else
+#define TRACE(slot) do { } while (0)
+#define TRACE_LAP(which) do { } while (0)
+#endif
+
+
+}  // namespace
+}  // namespace lychee

@@ -1,0 +1,648 @@
+// C, T, S and A units (included by lychee_units.hip only): the log-sum-exp merge of partials, the
+// sampled selection threshold, the exact radix select of Eq. 2 with the Ratio, Threshold and Top-p
+// rules of Sec. 4.4.1, the set copies, and the cache append of Alg. 1.
+#pragma once
+#include "lychee_device.h"
+
+namespace lychee {
+namespace {
+
+// ------------------------------------------------------------------------------ C
+// out = (sum_s w_s o_s) / (sum_s w_s l_s),  w_s = 2^((m_s - M) log2(e)/sqrt(d)),  M = max_s m_s,
+// over the head's partial slots in ascending order (a fixed summation tree).
+__device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p, int bh, SharedCombine &sh,
+                                             SharedPool &pool)
+{
+    int count = gload(p.part_count + bh);
+    count = count < 0 ? 0 : (count > c.part_stride ? c.part_stride : count);
+    const float *ml = p.part_ml + (int64_t)bh * c.part_stride * 2;
+    const float *po = p.part_o + (int64_t)bh * c.part_stride * kHeadDim;
+    float m_loc = kMinusBig;
+    for (int s = threadIdx.x; s < count; s += kThreads)
+        if (gload(ml + 2 * s + 1) > 0.0f) m_loc = fmaxf(m_loc, gload(ml + 2 * s));
+    const float M = block_max(m_loc, pool.fred);
+    float l_loc = 0.0f;
+    for (int s = threadIdx.x; s < count; s += kThreads) {
+        const float ls = gload(ml + 2 * s + 1);
+        const float w = ls > 0.0f ? fast_exp2((gload(ml + 2 * s) - M) * c.scale_log2e) : 0.0f;
+        sh.w[s] = w;
+        l_loc = fmaf(w, ls, l_loc);
+    }
+    const float lsum = block_sum(l_loc, pool.fred);  // also publishes sh.w
+    constexpr int kLanes = kThreads / 32;  // interleaved slot subsets
+    const int lane8 = threadIdx.x >> 5;
+    const int c4 = threadIdx.x & 31;       // which 4 columns
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = lane8; s0 < count; s0 += 8 * kLanes) {
+        // 8 slots per thread and round, all loads issued before the first use
+        float wv[8];
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = s0 + kLanes * u;
+            wv[u] = s < count ? sh.w[s] : 0.0f;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (wv[u] > 0.0f) v[u] = gload_f4(po + (int64_t)s * kHeadDim + c4 * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            acc.x = fmaf(wv[u], v[u].x, acc.x);
+            acc.y = fmaf(wv[u], v[u].y, acc.y);
+            acc.z = fmaf(wv[u], v[u].z, acc.z);
+            acc.w = fmaf(wv[u], v[u].w, acc.w);
+        }
+    }
+    reinterpret_cast<float4 *>(sh.red + lane8 * kHeadDim)[c4] = acc;
+    __syncthreads();
+    if (threadIdx.x < kHeadDim) {
+        float o = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kLanes; ++i) o += sh.red[i * kHeadDim + threadIdx.x];
+        const float r = lsum > 0.0f ? o / lsum : 0.0f;
+        gstore(p.out + (int64_t)bh * kHeadDim + threadIdx.x, f32_to_bf16_rne(r));
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------ T and S
+// In the histogram of `n_bins` digits, finds the highest digit d whose suffix count
+// (keys with digit >= d) reaches `need`; returns d and need minus the count above d.
+template <int kBins>
+__device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t need, uint32_t *found,
+                                           uint32_t *scan_scratch, uint32_t &digit, uint32_t &rest)
+{
+    constexpr int per = kBins / kThreads;
+    uint32_t mine[per];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        mine[j] = hist[kBins - 1 - (threadIdx.x * per + j)];  // bins taken from the top
+        sum += mine[j];
+    }
+    uint32_t total;
+    uint32_t above = block_scan(sum, scan_scratch, total) - sum;
+    if (threadIdx.x == 0) {
+        found[0] = 0;      // need > total: every key qualifies
+        found[1] = need;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        if (above < need && need <= above + mine[j]) {
+            found[0] = (uint32_t)(kBins - 1 - (threadIdx.x * per + j));
+            found[1] = need - above;
+        }
+        above += mine[j];
+    }
+    __syncthreads();
+    digit = found[0];
+    rest = found[1];
+    __syncthreads();
+}
+
+template <int NH>
+__device__ __forceinline__ void load_q(const Common &c, const uint16_t *q, int b, int g, uint32_t hmask,
+                                       uint4 (&qf)[NH])
+{
+    const int ch = threadIdx.x & 15;
+    uint32_t mk = hmask;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        const int bit = __builtin_ctz(mk);
+        mk &= mk - 1;
+        qf[h] = gload_u4(q + ((int64_t)b * c.n_q_heads + g * c.group + bit) * kHeadDim + ch * 8);
+    }
+}
+
+// Pooled scores of the 16 rows base .. base+15 of one KV head (rows past L-1 repeat row L-1);
+// afterwards lane (rs, ch) with ch < 4 holds the score of row base + 4*ch + rs.
+template <int NH>
+__device__ __forceinline__ float tile_pooled_score(const uint4 (&kr)[4], const uint4 (&qf)[NH], float sel_mul)
+{
+    const int ch = threadIdx.x & 15;
+    float mine = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float pooled = row_score(kr[j], qf[0]);
+#pragma unroll
+        for (int h = 1; h < NH; ++h) pooled += row_score(kr[j], qf[h]);
+        mine = (ch == j) ? sel_value(pooled, sel_mul) : mine;
+    }
+    return mine;
+}
+
+// T unit of score row (b, rgi): the ordered key that a row's pooled score has to reach to
+// become a candidate.  The key is the target-th largest of a sample of the row's scores,
+// to 22 bits, where target is the number of sampled rows expected among the top n = min(k, L)
+// plus sel_margin (six, unless the caller changes it) standard deviations; the streamed rows
+// that reach it are then very likely at least n and a few thousand more at most.  Whatever the sample yields, the select unit
+// checks the candidate count and ranks the whole row itself when the list cannot be used.
+// The sample is one row at a hashed offset inside each of 2048 to 4096 equal strata.
+template <int NH>
+__device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc &p, int b, int rgi,
+                                               SharedSelect &sh, SharedPool &pool)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rs = lane >> 4;
+    const int ch = lane & 15;
+    const int L = pool.len[b];  // staged by the kernel, clamped
+    const int n = budget_of(c, L);
+    const int64_t row = (int64_t)b * p.n_rgroups + rgi;
+    if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
+    if (p.q_keep != nullptr && (int)threadIdx.x < c.group * (kHeadDim / 8)) {
+        // the group's query rows (consecutive heads, 16 chunks of 16 bytes each)
+        const int64_t at = ((int64_t)b * c.n_q_heads + p.rgroup[rgi] * c.group) * kHeadDim + threadIdx.x * 8;
+        *(LYCHEE_GLOBAL u32x4_t *)(p.q_keep + at) = *(const LYCHEE_GLOBAL u32x4_t *)(p.q + at);
+    }
+    if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
+        // everything is selected anyway (no candidates wanted), or every row is a candidate
+        // (a probability rule may keep fewer than everything: it still needs the candidates)
+        if (threadIdx.x == 0) gstore(p.thr + row, n == L && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u);
+        return;
+    }
+    int n_tiles = L / 1024;
+    n_tiles = n_tiles < kSampleTilesMin ? kSampleTilesMin : (n_tiles > kSampleTilesMax ? kSampleTilesMax : n_tiles);
+    const int n_sample = n_tiles * 16;
+    const int g = p.rgroup[rgi];
+    const uint32_t hmask = p.rmask[g] & ((1u << c.group) - 1u);
+    uint4 qf[NH];
+    load_q<NH>(c, p.q, b, g, hmask, qf);
+    const uint16_t *kbase = p.k_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
+    const float sel_mul = c.scale / (float)NH;
+    for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
+    __syncthreads();
+
+    constexpr int kBatch = 8;  // groups of 16 sampled rows a wavefront has in flight
+    // One row at a hashed offset in each of n_sample equal strata of rows 0 .. L-2 (the newest
+    // row may be being appended in this very launch).  Row by row, not tile by tile: scores
+    // come in runs (a passage that matters is hundreds of consecutive rows), and a sample of
+    // contiguous tiles would over- or under-count such runs far beyond its nominal deviation.
+    const int stratum = (L - 1) / n_sample;  // >= 2
+    for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
+        uint4 kr[kBatch][4];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int t = t0 + u < n_tiles ? t0 + u : n_tiles - 1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = t * 16 + 4 * j + rs;  // sample number
+                const uint32_t hsh = ((uint32_t)i * 2654435761u + (uint32_t)row * 40503u) >> 12;
+                const int pos = i * stratum + (int)(hsh % (uint32_t)stratum);
+                kr[u][j] = gload_u4(kbase + (int64_t)pos * c.stride_t + ch * 8);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const uint32_t key = ordered_key(tile_pooled_score<NH>(kr[u], qf, sel_mul));
+            if (t0 + u < n_tiles && ch < 4) {
+                sh.samp[(t0 + u) * 16 + 4 * ch + rs] = key;
+                atomicAdd(&sh.hist[key >> 20], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    const float f = (float)n_sample * (float)n / (float)L;
+    const float want = f + c.sel_margin * sqrtf(f) + 6.0f;
+    const uint32_t target = want < 1.0f ? 1u : (want > (float)n_sample ? (uint32_t)n_sample : (uint32_t)want);
+    uint32_t t_key = 0;
+    if (target < (uint32_t)n_sample) {
+        // the sample's target-th largest key: top 12 bits, then the next 10
+        uint32_t d1, rest1, d2, rest2;
+        find_digit<4096>(sh.hist, target, sh.found, pool.scan, d1, rest1);
+        for (int i = threadIdx.x; i < 1024; i += kThreads) sh.hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < n_sample; i += kThreads) {
+            const uint32_t key = sh.samp[i];
+            if ((key >> 20) == d1) atomicAdd(&sh.hist[(key >> 10) & 1023u], 1u);
+        }
+        __syncthreads();
+        find_digit<1024>(sh.hist, rest1, sh.found, pool.scan, d2, rest2);
+        t_key = (d1 << 20) | (d2 << 10);
+    }
+    if (threadIdx.x == 0) gstore(p.thr + row, t_key);
+}
+
+// Writes the pooled score of every row of (b, g) into sel[0 .. L): what the select unit falls
+// back on when a row's candidate list is short of n entries or has overflowed.
+template <int NH>
+__device__ __forceinline__ void score_row_unit(const Common &c, const LayerDesc &p, int b, int g, int L, float *sel)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rs = lane >> 4;
+    const int ch = lane & 15;
+    const uint32_t hmask = p.rmask[g] & ((1u << c.group) - 1u);
+    uint4 qf[NH];
+    load_q<NH>(c, p.q, b, g, hmask, qf);
+    const uint16_t *kbase = p.k_cache + (int64_t)b * c.stride_b + (int64_t)g * c.stride_h;
+    const float sel_mul = c.scale / (float)NH;
+    const int n_tiles = (L + 15) / 16;
+    constexpr int kBatch = 4;
+    for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
+        uint4 kr[kBatch][4];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int r = (t0 + u) * 16 + 4 * j + rs;
+                r = r < L ? r : L - 1;
+                kr[u][j] = gload_u4(kbase + (int64_t)r * c.stride_t + ch * 8);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const float v = tile_pooled_score<NH>(kr[u], qf, sel_mul);
+            const int r = (t0 + u) * 16 + 4 * ch + rs;
+            if (ch < 4 && r < L) gstore(sel + r, v);
+        }
+    }
+}
+
+// The three sources of (ordered key, position) entries the select unit ranks.  for_each may
+// also hand out "no entry" (position kNoEntry).  The visitors below fold everything that
+// decides whether an entry counts into one flag, with bitwise operators, and guard a single
+// LDS operation with it: short-circuit conditions made the compiler keep a lane mask per entry
+// and condition, spill them, and branch several times per entry.
+constexpr uint32_t kNoEntry = 0xFFFFFFFFu;
+constexpr int kSelRegs = 40;  // entries one thread keeps in registers
+struct RegEntries {           // up to kThreads * kSelRegs list entries, loaded once
+    uint32_t key[kSelRegs], pos[kSelRegs];
+    __device__ __forceinline__ void load(const unsigned long long *list, int total)
+    {
+#pragma unroll
+        for (int e = 0; e < kSelRegs; ++e) {
+            const int i = threadIdx.x + e * kThreads;
+            const unsigned long long v = gload(list + (i < total ? i : 0));  // total >= 1
+            key[e] = (uint32_t)v;
+            pos[e] = i < total ? (uint32_t)(v >> 32) : kNoEntry;
+        }
+    }
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+#pragma unroll
+        for (int e = 0; e < kSelRegs; ++e) f(key[e], pos[e]);
+    }
+};
+struct ListEntries {          // a longer list, read from memory on every pass
+    const unsigned long long *list;
+    int total;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kThreads) {
+            unsigned long long v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                v[u] = gload(list + (i < total ? i : total - 1));  // unconditional: the loads overlap
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                f((uint32_t)v[u], i0 + u * kThreads < total ? (uint32_t)(v[u] >> 32) : kNoEntry);
+        }
+    }
+};
+struct RowEntries {           // every row of the sequence, from its recomputed scores
+    const float *sel;
+    int total;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kThreads) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                v[u] = gload(sel + (i < total ? i : total - 1));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                f(ordered_key(v[u]), i < total ? (uint32_t)i : kNoEntry);
+            }
+        }
+    }
+};
+
+// The `need`-th largest of the 32-bit values val(key, pos) over the entries that pass
+// `among`, by radix select (12 + 10 + 10 bits); `rest` = how many entries equal to the
+// result are among the `need` largest.
+template <typename Entries, typename Val, typename Among>
+__device__ __forceinline__ uint32_t radix_select(const Entries &E, uint32_t need, Val val, Among among,
+                                                 uint32_t &rest, SharedSelect &sh, SharedPool &pool)
+{
+    uint32_t prefix = 0, prefix_mask = 0;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+        const int n_bins = pass == 0 ? 4096 : 1024;
+        const uint32_t digit_mask = (uint32_t)n_bins - 1u;
+        for (int i = threadIdx.x; i < n_bins; i += kThreads) sh.hist[i] = 0;
+        __syncthreads();
+        E.for_each([&](uint32_t key, uint32_t pos) {
+            const uint32_t v = val(key, pos);
+            const bool in = (pos != kNoEntry) & among(key, pos) & ((v & prefix_mask) == prefix);
+            if (in) atomicAdd(&sh.hist[(v >> shift) & digit_mask], 1u);
+        });
+        __syncthreads();
+        uint32_t digit, left;
+        if (pass == 0)
+            find_digit<4096>(sh.hist, need, sh.found, pool.scan, digit, left);
+        else
+            find_digit<1024>(sh.hist, need, sh.found, pool.scan, digit, left);
+        prefix |= digit << shift;
+        prefix_mask |= digit_mask << shift;
+        need = left;
+    }
+    rest = need;
+    return prefix;
+}
+
+// Exact top-n of the entries by key, ties to the lower position (Eq. 2), written to dst in
+// ascending position order.  The entries may come in any order: the n-th largest key T and the
+// number r_eq of entries equal to T that belong to the top n come from a radix select; when
+// more than r_eq entries equal T, a second radix select finds the r_eq-th lowest position
+// among them; the chosen positions are then marked in an LDS bitmap, 131072 positions at a
+// time, and read back in order.
+template <typename Entries>
+__device__ __forceinline__ void select_from(const Entries &E, int n, int L, int32_t *dst, SharedSelect &sh,
+                                            SharedPool &pool)
+{
+    uint32_t r_eq;
+    const uint32_t T = radix_select(
+        E, (uint32_t)n, [](uint32_t key, uint32_t) { return key; }, [](uint32_t, uint32_t) { return true; }, r_eq,
+        sh, pool);
+    TRACE(7);
+    uint32_t my_eq = 0;
+    E.for_each([&](uint32_t key, uint32_t pos) { my_eq += (uint32_t)((key == T) & (pos != kNoEntry)); });
+    uint32_t n_eq;
+    (void)block_scan(my_eq, pool.scan, n_eq);
+    uint32_t pos_cut = 0xFFFFFFFEu;  // entries equal to T are taken up to this position
+    if (r_eq < n_eq) {
+        uint32_t unused;
+        pos_cut = ~radix_select(
+            E, r_eq, [](uint32_t, uint32_t pos) { return ~pos; }, [&](uint32_t key, uint32_t) { return key == T; },
+            unused, sh, pool);
+    }
+    constexpr uint32_t kWindow = 4096u * 32u;
+    constexpr int kPer = 4096 / kThreads;
+    uint32_t base = 0;
+    for (uint32_t w0 = 0; w0 < (uint32_t)L; w0 += kWindow) {
+        for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
+        __syncthreads();
+        E.for_each([&](uint32_t key, uint32_t pos) {
+            const uint32_t rel = pos - w0;  // "no entry" lies outside every window
+            const bool take = ((key > T) | ((key == T) & (pos <= pos_cut))) & (rel < kWindow);
+            if (take) atomicOr(&sh.hist[rel >> 5], 1u << (rel & 31u));
+        });
+        __syncthreads();
+        TRACE(2);
+        uint32_t words[kPer], cnt = 0;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            words[j] = sh.hist[threadIdx.x * kPer + j];
+            cnt += (uint32_t)__builtin_popcount(words[j]);
+        }
+        uint32_t tot;
+        uint32_t at = base + block_scan(cnt, pool.scan, tot) - cnt;
+        TRACE(3);
+        // (handing neighbouring words to neighbouring lanes, for store addresses that share
+        // cache lines, was measured to be slower: the loop below is bound by its divergence)
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            uint32_t wd = words[j];
+            while (wd != 0) {
+                const uint32_t bit = (uint32_t)__builtin_ctz(wd);
+                wd &= wd - 1u;
+                if (at < (uint32_t)n) gstore(dst + at, (int32_t)(w0 + (uint32_t)(threadIdx.x * kPer + j) * 32u + bit));
+                ++at;
+            }
+        }
+        base += tot;
+    }
+    TRACE(4);
+}
+
+// A unit of one layer (Alg. 1, "C.append(k, v)"): the decoded token's key and value rows become
+// row L_b - 1 of every KV head's cache.  16 lanes move one 256-byte row.
+__device__ __forceinline__ void append_unit(const Common &c, const LayerDesc &p)
+{
+    const int ch = threadIdx.x & 15;
+    const int n_rows = c.batch * c.n_kv_heads * 2;  // K rows, then V rows
+    for (int r = threadIdx.x >> 4; r < n_rows; r += kThreads >> 4) {
+        const int which = r / (c.batch * c.n_kv_heads);
+        const int bg = r % (c.batch * c.n_kv_heads);
+        const int b = bg / c.n_kv_heads, g = bg % c.n_kv_heads;
+        const int L = clamp_len(c.lengths[b], c.max_len);
+        const uint16_t *src = (which ? p.v_new : p.k_new) + (int64_t)bg * kHeadDim + ch * 8;
+        const uint16_t *dst = (which ? p.v_cache : p.k_cache) + (int64_t)b * c.stride_b +
+                              (int64_t)g * c.stride_h + (int64_t)(L - 1) * c.stride_t + ch * 8;
+        const uint4 v = gload_u4(src);
+        *(LYCHEE_GLOBAL u32x4_t *)const_cast<uint16_t *>(dst) = u32x4_t{v.x, v.y, v.z, v.w};
+    }
+}
+
+// ---- the probability rules of Sec. 4.4.1 (Threshold, Top-p): how many entries to keep
+// The pooled logit an ordered key stands for.
+__device__ __forceinline__ float key_score(uint32_t key)
+{
+    return __builtin_bit_cast(float, (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+// Probability of a pooled logit under the softmax over the whole sequence, as a 40-bit
+// fixed-point number: sums of these are integer sums, the same in any order.
+constexpr float kMassOne = 1099511627776.0f;  // 2^40
+__device__ __forceinline__ unsigned long long mass_of(uint32_t key, float lse)
+{
+    const float p = fast_exp2((key_score(key) - lse) * kLog2e);  // <= 1 up to rounding
+    return (unsigned long long)(fminf(p, 1.0f) * kMassOne);
+}
+
+// In a histogram of probability mass per digit, finds the highest digit d at which the mass
+// of the digits >= d reaches `need`; returns d and what is still needed inside d, or digit
+// 0xFFFFFFFF when all the mass together does not reach it.
+template <int kBins>
+__device__ __forceinline__ void find_digit_mass(const unsigned long long *hist, unsigned long long need,
+                                                SharedPool &pool, uint32_t &digit, unsigned long long &rest)
+{
+    constexpr int per = kBins / kThreads;
+    unsigned long long mine[per], sum = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        mine[j] = hist[kBins - 1 - (threadIdx.x * per + j)];  // bins taken from the top
+        sum += mine[j];
+    }
+    unsigned long long total;
+    unsigned long long above = block_scan64(sum, pool.scan64, total) - sum;
+    if (threadIdx.x == 0) {
+        pool.scan64[kWaves] = 0xFFFFFFFFull << 32;  // "not reached"
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        if (above < need && need <= above + mine[j]) {
+            // digit in the high word, the remaining need (< 2^41) cannot be packed with it: two words
+            pool.scan64[kWaves] = (unsigned long long)(uint32_t)(kBins - 1 - (threadIdx.x * per + j)) << 32;
+            pool.scan64[kWaves - 1] = need - above;
+        }
+        above += mine[j];
+    }
+    __syncthreads();
+    digit = (uint32_t)(pool.scan64[kWaves] >> 32);
+    rest = pool.scan64[kWaves - 1];
+    __syncthreads();
+}
+
+// Entries the rule keeps, before the clamp to [1, n]: Threshold counts the entries whose
+// probability exceeds the parameter; Top-p finds, digit by digit, the key at which the
+// probability mass of the descending order reaches the parameter (all entries with that key
+// have the same mass, so a division says how many of them are needed).  `lse` is the
+// log-sum-exp of the pooled logits of the whole sequence.  The entries hold at least the n best
+// positions, and a rule that would go beyond them is capped at n anyway.
+template <typename Entries>
+__device__ __forceinline__ int rule_keeps(const Common &c, const Entries &E, int n, float lse, SharedSelect &sh,
+                                          SharedPool &pool)
+{
+    uint32_t want;
+    if (c.prob_rule == 1) {
+        const uint32_t cut = ordered_key(lse + __logf(c.prob_param));
+        uint32_t mine = 0;
+        E.for_each([&](uint32_t key, uint32_t pos) { mine += (uint32_t)((pos != kNoEntry) & (key > cut)); });
+        (void)block_scan(mine, pool.scan, want);
+    } else {
+        if (c.prob_param >= 1.0f) return n;  // all of the mass: everything, i.e. the cap
+        unsigned long long *mh = reinterpret_cast<unsigned long long *>(sh.hist);  // 4096 x 8 bytes: hist + samp
+        unsigned long long need = (unsigned long long)((double)c.prob_param * (double)kMassOne);
+        need = need < 1 ? 1 : need;
+        uint32_t prefix = 0, prefix_mask = 0;
+        bool reached = true;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int n_bins = pass == 0 ? 4096 : 1024;
+            const uint32_t digit_mask = (uint32_t)n_bins - 1u;
+            for (int i = threadIdx.x; i < n_bins; i += kThreads) mh[i] = 0;
+            __syncthreads();
+            E.for_each([&](uint32_t key, uint32_t pos) {
+                const bool in = (pos != kNoEntry) & ((key & prefix_mask) == prefix);
+                if (in) atomicAdd(&mh[(key >> shift) & digit_mask], mass_of(key, lse));
+            });
+            __syncthreads();
+            uint32_t digit;
+            unsigned long long left;
+            if (pass == 0)
+                find_digit_mass<4096>(mh, need, pool, digit, left);
+            else
+                find_digit_mass<1024>(mh, need, pool, digit, left);
+            if (digit == 0xFFFFFFFFu) {  // (uniform) not even all entries reach the mass: the cap decides
+                reached = false;
+                break;
+            }
+            prefix |= digit << shift;
+            prefix_mask |= digit_mask << shift;
+            need = left;
+        }
+        if (!reached) return n;
+        const unsigned long long each = mass_of(prefix, lse);  // > 0: its digit held mass
+        const uint32_t of_last = (uint32_t)((need + each - 1) / each);
+        uint32_t mine = 0;
+        E.for_each([&](uint32_t key, uint32_t pos) { mine += (uint32_t)((pos != kNoEntry) & (key > prefix)); });
+        uint32_t above;
+        (void)block_scan(mine, pool.scan, above);
+        want = above + of_last;
+    }
+    return want < 1u ? 1 : (want > (uint32_t)n ? n : (int)want);
+}
+
+// Log-sum-exp of the pooled logits of score row `row`: the pieces' states, merged.
+__device__ __forceinline__ float pooled_lse(const Common &c, const LayerDesc &p, int64_t row, int count,
+                                            SharedPool &pool)
+{
+    const float *ml = p.part_pool + row * (2 * (int64_t)c.part_stride);
+    float m_loc = kMinusBig;
+    for (int s = threadIdx.x; s < count; s += kThreads) m_loc = fmaxf(m_loc, gload(ml + 2 * s));
+    const float M = block_max(m_loc, pool.fred);
+    float l_loc = 0.0f;
+    for (int s = threadIdx.x; s < count; s += kThreads)
+        l_loc = fmaf(fast_exp2((gload(ml + 2 * s) - M) * kLog2e), gload(ml + 2 * s + 1), l_loc);
+    const float l = block_sum(l_loc, pool.fred);
+    return M + __logf(l);
+}
+
+// The set of a KV head (b, g) whose group holds no retrieval head is handed on unchanged
+// (Sec. 3.1): a verbatim copy.
+__device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &p, int b, int g)
+{
+    const int64_t bg = (int64_t)b * c.n_kv_heads + g;
+    int32_t *dst = p.idx_out + bg * c.k;
+    const int32_t *src = p.idx_src[g] + bg * c.k;
+    for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, gload(src + i));
+}
+
+// S unit of KV head (b, g), whose group holds a retrieval head: the set the next layer's
+// sparse heads of the group inherit.  PROB: the build that knows the probability rules (their
+// 64-bit mass arithmetic over register-resident entries would cost the plain build registers).
+template <bool PROB>
+__device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p, int b, int g,
+                                            SharedSelect &sh, SharedPool &pool)
+{
+    const int64_t bg = (int64_t)b * c.n_kv_heads + g;
+    int32_t *dst = p.idx_out + bg * c.k;
+    const int rgi = p.rindex[g];
+    const int len = pool.len[b];  // staged by the kernel, clamped
+    const int L = units_of(c, len);  // what is ranked: positions, or blocks of positions
+    const int n = budget_of(c, L);
+    const bool by_prob = PROB && c.prob_rule != 0;
+    if (n == L && !by_prob) {  // everything is selected
+        for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
+        return;
+    }
+    const int64_t row = (int64_t)b * p.n_rgroups + rgi;
+    const unsigned long long *list = p.list + row * (int64_t)c.list_row;
+    // block-granular: the streaming left every block's score at its place in the list
+    const int total = c.block_shift ? L : gload(p.list_count + row);
+    TRACE(5);
+    float lse = 0.0f;
+    if (by_prob) {
+        // the pieces of this KV head's segment, counted by its first retrieval head
+        const int h = g * c.group + __builtin_ctz((uint32_t)p.rmask[g]);
+        int count = gload(p.part_count + (int64_t)b * c.n_q_heads + h);
+        count = count < 0 ? 0 : (count > c.part_stride ? c.part_stride : count);
+        lse = pooled_lse(c, p, row, count, pool);
+    }
+    int keep = n;  // what is selected in the end: n, or fewer under a probability rule
+    if (total >= n && total <= kThreads * kSelRegs && total <= c.list_row) {
+        RegEntries E;
+        E.load(list, total);
+        TRACE(6);
+        if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
+        select_from(E, keep, L, dst, sh, pool);
+    } else if (total >= n && total <= c.list_row) {
+        const ListEntries E{list, total};
+        if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
+        select_from(E, keep, L, dst, sh, pool);
+    } else {
+        // too few candidates reached the threshold, or too many for the list: rank the row
+        // (token-granular only: a block list is always complete)
+        if (threadIdx.x == 0) atomicAdd(c.stats + (total < n ? 0 : 1), 1u);
+        float *sel = p.sel + row * c.sel_stride;
+        switch (__builtin_popcount(p.rmask[g] & ((1u << c.group) - 1u))) {
+        case 1: score_row_unit<1>(c, p, b, g, len, sel); break;
+        case 2: score_row_unit<2>(c, p, b, g, len, sel); break;
+        case 3: score_row_unit<3>(c, p, b, g, len, sel); break;
+        default: score_row_unit<4>(c, p, b, g, len, sel); break;
+        }
+        __threadfence();
+        __syncthreads();  // the scores are read back by other threads of the workgroup
+        const RowEntries E{sel, len};
+        if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
+        select_from(E, keep, L, dst, sh, pool);
+    }
+    for (int i = keep + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
+}
+
+
+}  // namespace
+}  // namespace lychee
