@@ -304,9 +304,11 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
     const int n_chunks = pad ? 0 : (T - T_static + chunk - 1) / chunk;
     auto item_of = [&](int blk) { return blk < T_static ? blk / share : n_static + (blk - T_static) / chunk; };
     uint32_t *counter = c.tickets + c.ticket_slot;
-    uint32_t next_ticket = 0;
+    // Tickets: workgroup w's first chunk is chunk w, without asking; every later one is W plus
+    // what the counter hands out, asked for a chunk ahead.  (All workgroups asking at the start
+    // of the launch were served one after the other, and the first barrier waited for it.)
+    uint32_t next_ticket = (uint32_t)w;
     if (threadIdx.x == 0) {
-        if (n_chunks > 0) next_ticket = atomicAdd(counter, 1u);  // asked for early, looked at after the static run
         if (w == 0) c.tickets[(c.ticket_slot + kTicketRing / 2) % kTicketRing] = 0u;
     }
     TRACE(2);
@@ -435,7 +437,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
         const int ticket = (int)pool.scan[0];
         __syncthreads();
         if (ticket >= n_chunks) break;
-        if (threadIdx.x == 0) next_ticket = atomicAdd(counter, 1u);
+        if (threadIdx.x == 0) next_ticket = (uint32_t)W + atomicAdd(counter, 1u);
         item = n_static + ticket;
         x = T_static + ticket * chunk;
         x1 = x + chunk;
