@@ -337,6 +337,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     TRACE(7);
     TRACE_LAP(2);  // streaming
     at_rows_done();  // what the caller wants in flight while the partial is merged and written
+    if (collects && lane == 0) sh.cand_left[wave] = cand_left;
     // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).
     const float c_log2e = c.scale_log2e;
 #pragma unroll
@@ -370,11 +371,22 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     }
     // Merge the 4 wavefronts through LDS and write the piece's partial.
     __syncthreads();  // red_o / idx_s readers of the previous piece are done
+    int cand_base = 0;
+    if (collects && threadIdx.x == kThreads - 1) {
+        // room for the workgroup's last candidates, asked for by a thread that writes no
+        // partial, as early as every wavefront's count is known: the answer is on its way
+        // while the others merge
+        int n = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) n += sh.cand_left[w];
+        if (n > 0)
+            cand_base = __hip_atomic_fetch_add((LYCHEE_GLOBAL int32_t *)em.count, (int32_t)n, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (pooled_lse && lane == 0) {
         sh.pool_ml[2 * wave] = pool_m;
         sh.pool_ml[2 * wave + 1] = pool_l;
     }
-    if (collects && lane == 0) sh.cand_left[wave] = cand_left;
     if (rs == 0) {
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
@@ -388,18 +400,7 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         }
     }
     __syncthreads();
-    if (collects && threadIdx.x == kThreads - 1) {
-        // room for the workgroup's last candidates, asked for by a thread that writes no
-        // partial: the answer is on its way while the others merge
-        int n = 0;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) n += sh.cand_left[w];
-        int base = 0;
-        if (n > 0)
-            base = __hip_atomic_fetch_add((LYCHEE_GLOBAL int32_t *)em.count, (int32_t)n, __ATOMIC_RELAXED,
-                                          __HIP_MEMORY_SCOPE_AGENT);
-        sh.cand_base = base;
-    }
+    if (collects && threadIdx.x == kThreads - 1) sh.cand_base = cand_base;
     if (threadIdx.x < kHeadDim) {
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
