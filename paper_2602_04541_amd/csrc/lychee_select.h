@@ -172,6 +172,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     const float sel_mul = c.scale / (float)NH;
     for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
     __syncthreads();
+    TRACE(5);
 
     constexpr int kBatch = 8;  // groups of 16 sampled rows a wavefront has in flight
     // One row at a hashed offset in each of n_sample equal strata of rows 0 .. L-2 (the newest
@@ -202,6 +203,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
         }
     }
     __syncthreads();
+    TRACE(6);
     const float f = (float)n_sample * (float)n / (float)L;
     const float want = f + c.sel_margin * sqrtf(f) + 6.0f;
     const uint32_t target = want < 1.0f ? 1u : (want > (float)n_sample ? (uint32_t)n_sample : (uint32_t)want);
@@ -221,6 +223,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
         t_key = (d1 << 20) | (d2 << 10);
     }
     if (threadIdx.x == 0) gstore(p.thr + row, t_key);
+    TRACE(7);
 }
 
 // Writes the pooled score of every row of (b, g) into sel[0 .. L): what the select unit falls
