@@ -174,6 +174,9 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
             bool ok;
             if (GATHER) {
                 // set entry (r - r0) >> bshift names 2^bshift consecutive cache rows
+                // (reading a tile's four entries unconditionally and ahead of the address
+                // arithmetic removes the branches the compiler puts around these reads, and
+                // made the gather launch 3.5 % slower)
                 const int e = (r < r1) ? idx_s[(r - r0) >> bshift] : -1;
                 const int tpos = (e << bshift) + (r & ((1 << bshift) - 1));
                 ok = (e >= 0) && (tpos < L);
