@@ -339,6 +339,26 @@ struct Launcher {
         p.t_first = r.t_first, p.t_count = r.t_count;
         p.s_first = r.s_first, p.s_count = r.s_count;
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.collect |= host_table[l].emit_sel;
+        if (p.collect && s.block_size != 64 && ctx->n_wg == 0 && ctx->wg_per_cu == 2) {
+            // A small launch that collects candidates of a few score rows (a single layer's call
+            // at batch 1) is a few percent faster with one workgroup per CU: half as many pieces
+            // to start, to merge and to reserve list space for.  Batches, block-granular sets
+            // (no lists) and the dense baseline are faster with two.  The bound below uses
+            // max_len: the lengths are on the device.
+            const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
+            const int64_t g_rows = s.k < s.max_len ? s.k : s.max_len;
+            const int64_t g_blocks = (g_rows + c.g_block_rows - 1) / c.g_block_rows;
+            int64_t t_max = 0, n_segs = 0;
+            for (int l = r.r_first; l < r.r_first + r.r_count; ++l) {
+                n_segs += (int64_t)host_table[l].n_rgroups * s.batch;
+                t_max += (int64_t)host_table[l].n_rgroups * s.batch * seg_blocks;
+            }
+            for (int l = r.g_first; l < r.g_first + r.g_count; ++l) {
+                n_segs += (int64_t)host_table[l].n_sgroups * s.batch;
+                t_max += (int64_t)host_table[l].n_sgroups * s.batch * g_blocks;
+            }
+            if (8 * n_segs <= ctx->n_cu && t_max < 48ll * ctx->n_cu) c.n_wg = ctx->n_cu < kWsWg ? ctx->n_cu : kWsWg;
+        }
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
         for (int l = r.t_first; l < r.t_first + r.t_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
         for (int l = r.s_first; l < r.s_first + r.s_count; ++l) {
