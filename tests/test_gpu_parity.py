@@ -937,3 +937,46 @@ def test_a_pending_select_pins_its_workspace_and_shape(ctx):
     ctx.select_flush()
     torch.cuda.synchronize()
     assert torch.equal(idx_a, idx_b)
+
+
+@pytest.mark.parametrize("rule", ["ratio", "threshold", "top_p"])
+def test_pending_selects_under_the_other_selection_rules(ctx, rule):
+    """The rules of Sec. 4.4.1 decide inside the select, from what the streaming left in the
+    layer's scratch (for the probability rules also the pooled log-sum-exp): a pending select must
+    find all of it in its own half of the workspace.  The plain layer call, whose parity with the
+    oracle the tests above establish, is the reference here, bit for bit."""
+    lb = H.binding()
+    n_layers = 4
+    k = 600
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=2, max_len=9000, k=k, n_layers=n_layers, planted=32,
+                  len_lo=2500, len_hi=9000)
+    lens_h = wl.lengths(w)
+    layers = [wl.make_layer(w, layer=l, device="cuda", lens=lens_h, l_cap=9000) for l in range(n_layers)]
+    kw = {"ratio": dict(keep_ppm=40000), "threshold": dict(prob_rule=lb.RULE_THRESHOLD, prob_param=2e-4),
+          "top_p": dict(prob_rule=lb.RULE_TOP_P, prob_param=0.6)}[rule]
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 9000, k, kv=layers[0].k_cache, **kw)
+    lens = torch.from_numpy(lens_h).cuda()
+    first = torch.from_numpy(H.previous_layer_sets(layers[0], k)).cuda()
+
+    def run(deferred):
+        ws = lb.alloc_workspace(shape, n_layers=2 if deferred else 1)
+        ws.fill_(0xFF)
+        outs = [torch.zeros_like(ly.q) for ly in layers]
+        sets = [torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda") for _ in layers]
+        for l, ly in enumerate(layers):
+            call = ctx.decode_attn_deferred if deferred else ctx.decode_attn
+            call(shape, ly.q, ly.k_cache, ly.v_cache, ly.mask, sets[l - 1] if l else first, outs[l], sets[l], lens, ws)
+        if deferred:
+            ctx.select_flush()
+        torch.cuda.synchronize()
+        return outs, sets
+
+    _say("pending selects, rule %s" % rule)
+    outs_a, sets_a = run(False)
+    outs_b, sets_b = run(True)
+    kept = 0
+    for l in range(n_layers):
+        assert torch.equal(outs_a[l], outs_b[l]), "layer %d: outputs differ" % l
+        assert torch.equal(sets_a[l], sets_b[l]), "layer %d: sets differ" % l
+        kept += int((sets_a[l] >= 0).sum())
+    assert 0 < kept < n_layers * w.batch * w.n_kv_heads * k, "the rule kept everything or nothing"
