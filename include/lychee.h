@@ -155,7 +155,8 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
  *               pending selection has run.  In particular flush before the lengths grow for
  *               the next token, and before the workspace serves any other call.
  * While a selection is pending, the next deferred call must pass the same shape, lengths
- * pointer and workspace (else EINVAL: flush first).  With block_size 64 nothing is left
+ * pointer and workspace (else EINVAL: flush first), and every other call that is given that
+ * workspace returns EINVAL.  With block_size 64 nothing is left
  * pending (the selection has no later launch to join and is enqueued with this call).
  * lychee_select_flush: enqueues a pending selection, if there is one; EINVAL for a NULL ctx.
  */

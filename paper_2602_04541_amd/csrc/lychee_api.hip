@@ -141,13 +141,15 @@ int check_shape(const lychee_shape *s)
 }
 
 int check_common(lychee_ctx *ctx, const lychee_shape *shape, const void *workspace,
-                 size_t workspace_bytes, int n_layers)
+                 size_t workspace_bytes, int n_layers, bool continues_pending = false)
 {
     if (ctx == nullptr) return LYCHEE_EINVAL;
     const int rc = check_shape(shape);
     if (rc != LYCHEE_OK) return rc;
     if (workspace == nullptr || !aligned(workspace, 256)) return LYCHEE_EWORKSPACE;
     if (workspace_bytes < carve(*shape, n_layers).total) return LYCHEE_EWORKSPACE;
+    // a pending select still reads this workspace: only the call that runs it may use it
+    if (!continues_pending && ctx->pending.active && ctx->pending.workspace == workspace) return LYCHEE_EINVAL;
     return LYCHEE_OK;
 }
 
@@ -643,7 +645,7 @@ int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, cons
                                 const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
                                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_common(ctx, shape, workspace, workspace_bytes, 2);
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, 2, true);
     if (rc != LYCHEE_OK) return rc;
     rc = check_mask(shape, head_type_mask, idx_in != nullptr);
     if (rc != LYCHEE_OK) return rc;

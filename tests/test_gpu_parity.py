@@ -932,6 +932,9 @@ def test_a_pending_select_pins_its_workspace_and_shape(ctx):
     with pytest.raises(lb.LycheeError) as e:      # another workspace while a select is pending
         ctx.decode_attn_deferred(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_b, lens, other)
     assert e.value.code == lb.EINVAL
+    with pytest.raises(lb.LycheeError) as e:      # nor may another kind of call use the pinned workspace
+        ctx.decode_attn(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_b, lens, ws2)
+    assert e.value.code == lb.EINVAL
     ctx.select_flush()
     ctx.decode_attn_deferred(shape, inp.q, inp.k_cache, inp.v_cache, ones, None, out, idx_b, lens, other)
     ctx.select_flush()
