@@ -412,8 +412,9 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         uint32_t at = base + block_scan(cnt, pool.scan, tot) - cnt;
         TRACE(3);
         // (handing neighbouring words to neighbouring lanes, for store addresses that share
-        // cache lines, was measured to be slower, and so was putting the set together in LDS
-        // and copying it out in order: the loop below is bound by its divergence)
+        // cache lines, was measured to be slower, and so were putting the set together in LDS
+        // and copying it out in order, and dealing 16 ranks to every thread, found by bisection
+        // over the threads' first ranks: 4.4 us for 4096 positions it stays)
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
             uint32_t wd = words[j];
