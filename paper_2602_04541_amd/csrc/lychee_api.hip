@@ -361,6 +361,13 @@ struct Launcher {
             }
             if (8 * n_segs <= ctx->n_cu && t_max < 48ll * ctx->n_cu) c.n_wg = ctx->n_cu < kWsWg ? ctx->n_cu : kWsWg;
         }
+        {   // the pooled block space of a launch is indexed with 32-bit integers
+            const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
+            int64_t segs = 0;
+            for (int l = r.r_first; l < r.r_first + r.r_count; ++l) segs += host_table[l].n_rgroups;
+            for (int l = r.g_first; l < r.g_first + r.g_count; ++l) segs += host_table[l].n_sgroups;
+            if (segs * s.batch * (4 * seg_blocks + 8) >= (1ll << 31)) return LYCHEE_EUNSUPPORTED;  // (gathered blocks are shorter)
+        }
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
         for (int l = r.t_first; l < r.t_first + r.t_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
         for (int l = r.s_first; l < r.s_first + r.s_count; ++l) {
