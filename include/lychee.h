@@ -130,7 +130,8 @@ size_t lychee_step_workspace_bytes(const lychee_shape *shape, int32_t n_layers);
  *   lengths         int32 [B], 1 <= L_b <= max_len, the current token included (values
  *                   outside that range are clamped into it)
  * Errors: EINVAL (NULL / misaligned pointer, bad shape, sparse heads without idx_in,
- * idx_out == idx_in), EUNSUPPORTED (head_dim, group size), EWORKSPACE, EHIP.
+ * idx_out == idx_in), EUNSUPPORTED (head_dim, group size; more than 2^31 blocks of 16 cache rows in
+ * one launch, far beyond what fits a GPU), EWORKSPACE, EHIP.
  */
 int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
                        const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
