@@ -983,3 +983,108 @@ def test_pending_selects_under_the_other_selection_rules(ctx, rule):
         assert torch.equal(sets_a[l], sets_b[l]), "layer %d: sets differ" % l
         kept += int((sets_a[l] >= 0).sum())
     assert 0 < kept < n_layers * w.batch * w.n_kv_heads * k, "the rule kept everything or nothing"
+
+
+# ------------------------------------------------------------------ seeded sweep over odd shapes
+def _sweep_cases(n=24, seed=20260204):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        G = int(rng.choice([1, 2, 3, 4]))
+        B = int(rng.choice([1, 1, 2, 3, 5]))
+        l_cap = int(rng.choice([97, 640, 1500, 4097, 9000, 20000]))
+        lens = [int(x) for x in rng.integers(max(1, l_cap // 3), l_cap + 1, size=B)]
+        block = int(rng.choice([1, 1, 1, 64]))
+        units = (l_cap + 63) // 64 if block == 64 else l_cap
+        k = int(max(1, min(units, rng.choice([1, 7, 64, 300, 1024, 5000]))))
+        keep_ppm = int(rng.choice([0, 0, 0, 30000]))
+        mask = (rng.random(Hkv * G) < rng.choice([0.15, 0.4, 0.8])).astype(np.uint8)
+        cases.append((i, B, Hkv, G, l_cap, lens, k, block, keep_ppm, mask))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: "s%02d_B%d_kv%d_G%d_L%d_k%d_b%d_r%d" % (
+    c[0], c[1], c[2], c[3], c[4], c[6], c[7], c[8]))
+def test_seeded_sweep_of_shapes_masks_and_modes(ctx, case):
+    """Layer calls on drawn shapes (KV heads 1-8, group sizes 1-4, batches of ragged lengths, budgets
+    from 1 to more than the sequence, token- and block-granular sets, the Ratio rule, masks from
+    mostly sparse to mostly retrieval): outputs and sets against the oracle.  The grid's padded and
+    unpadded static splits, one or two workgroups per CU, all depend on these numbers."""
+    i, B, Hkv, G, l_cap, lens, k, block, keep_ppm, mask = case
+    w = wl.scaled(wl.WORKLOADS["c1"], batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, max_len=l_cap, k=k,
+                  planted=min(6, min(lens)), retrieval_heads=(), config_id=900 + i)
+    inp = wl.make_layer(w, mask=mask, lens=np.asarray(lens, np.int32), l_cap=l_cap)
+    idx_in = None if mask.all() else H.previous_layer_sets(inp, k, block=block)
+    _say("sweep %s lens=%s mask=%s" % (case[:5] + case[6:9], lens, mask.tolist()))
+    H.check_layer(ctx, inp, mask, k, idx_in, "sweep%d" % i, keep_ppm=keep_ppm, block=block)
+
+
+def _step_cases(n=10, seed=20260205):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        Hkv = int(rng.choice([2, 4, 8]))
+        G = int(rng.choice([1, 2, 4]))
+        B = int(rng.choice([1, 2, 4]))
+        n_layers = int(rng.integers(2, 6))
+        l_cap = int(rng.choice([700, 3000, 11000, 30000]))
+        lens = [int(x) for x in rng.integers(max(1, l_cap // 4), l_cap + 1, size=B)]
+        block = int(rng.choice([1, 1, 64]))
+        units = (l_cap + 63) // 64 if block == 64 else l_cap
+        k = int(max(1, min(units, rng.choice([5, 100, 900, 4000]))))
+        masks = (rng.random((n_layers, Hkv * G)) < rng.choice([0.1, 0.3, 0.6])).astype(np.uint8)
+        mode = str(rng.choice(["phased", "layerwise"]))
+        cases.append((i, B, Hkv, G, n_layers, l_cap, lens, k, block, mode, masks))
+    return cases
+
+
+@pytest.mark.parametrize("case", _step_cases(), ids=lambda c: "t%02d_B%d_kv%d_G%d_n%d_L%d_k%d_b%d_%s" % (
+    c[0], c[1], c[2], c[3], c[4], c[5], c[7], c[8], c[9]))
+def test_seeded_sweep_of_decode_steps(ctx, case):
+    """Whole steps on drawn shapes and per-layer masks (layers without any retrieval head included:
+    their sets pass through), in both step modes, with caller-supplied sets for the first layer:
+    every layer's output and the final sets against the oracle's chain."""
+    lb = H.binding()
+    i, B, Hkv, G, n_layers, l_cap, lens_l, k, block, mode, masks = case
+    w = wl.scaled(wl.WORKLOADS["c4"], batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, max_len=l_cap, k=k,
+                  n_layers=n_layers, planted=min(6, min(lens_l)), config_id=950 + i)
+    lens_h = np.asarray(lens_l, np.int32)
+    layers = [wl.make_layer(w, layer=l, device="cuda", mask=masks[l], lens=lens_h, l_cap=l_cap) for l in range(n_layers)]
+    idx0 = H.previous_layer_sets(layers[0], k, block=block)
+    idx = idx0
+    refs = []
+    for l, ly in enumerate(layers):
+        out_ref, idx, sel_ref = H.oracle_layer(ly, masks[l], k, idx, block=block)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(B, Hkv * G, Hkv, l_cap, k, kv=layers[0].k_cache, block_size=block)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    ws.fill_(0xFF)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((B, Hkv, k), -9, dtype=torch.int32, device="cuda")
+    lens = torch.from_numpy(lens_h).cuda()
+    _say("step sweep %s lens=%s" % (case[:6] + case[7:10], lens_l))
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED if mode == "phased" else lb.STEP_LAYERWISE)
+    try:
+        ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
+                        [ly.v_cache for ly in layers], masks, torch.from_numpy(idx0).cuda(), outs, idx_final, lens, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "step sweep %d layer %d" % (i, l))
+    # the final set of a KV head comes from the last layer that selected for it (or from idx0)
+    got = idx_final.cpu().numpy()
+    for g in range(Hkv):
+        src = None
+        for l in range(n_layers - 1, -1, -1):
+            if masks[l][g * G:(g + 1) * G].any():
+                src = l
+                break
+        for b in range(B):
+            if src is None:
+                assert (got[b, g] == idx0[b, g]).all(), "head %d: caller's set not handed on" % g
+            else:
+                sc = H.unit_scores(refs[src][2][b, g], int(lens_h[b]), block)
+                ok, _, msg = H.index_sets_match(got[b, g], refs[src][1][b, g], sc, min(k, sc.size), H.TIE_REL)
+                assert ok, "seq %d head %d (selected in layer %d): %s" % (b, g, src, msg)
