@@ -910,6 +910,19 @@ def test_layer_calls_that_leave_their_select_pending(ctx, margin, block):
                 assert ok, "layer %d head %d: %s" % (l, g, msg)
             else:
                 assert (got[0, g] == refs[l][1][0, g]).all(), "layer %d head %d: inherited set not copied" % (l, g)
+    # the same chain through two set buffers used in turn, as a model would hold them: layer l reads
+    # the buffer that the select of layer l-1 fills in this very call, and writes the other one
+    pair = [torch.full_like(sets[0], -9) for _ in range(2)]
+    outs2 = [torch.zeros_like(o) for o in outs]
+    for l, ly in enumerate(layers):
+        q_buf.copy_(ly.q)
+        ctx.decode_attn_deferred(shape, q_buf, ly.k_cache, ly.v_cache, ly.mask,
+                                 pair[(l - 1) % 2] if l else None, outs2[l], pair[l % 2], lens, ws)
+    ctx.select_flush()
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        assert torch.equal(outs2[l], outs[l]), "two buffers in turn: layer %d differs" % l
+    assert torch.equal(pair[(n_layers - 1) % 2], sets[-1])
 
 
 def test_a_pending_select_pins_its_workspace_and_shape(ctx):
