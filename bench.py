@@ -162,6 +162,23 @@ def main() -> int:
         dense_other_sec = timed(dense_step, max(3, args.steps // 3), 1)
         set_mode(args.layerwise)
         dense_sec = timed(dense_step, max(3, args.steps // 3), 1)
+    # ---- the same layers through per-layer calls, as a model that computes q[l+1] from
+    #      out[l] has to make them: plain calls, and calls that leave their select pending -----
+    calls_sec = deferred_sec = None
+    if not args.quick and n_layers > 1 and masks[0].all():
+        ws2 = lb.alloc_workspace(shape, dev, n_layers=2)
+        pair = [torch.zeros_like(idx_final) for _ in range(2)]
+
+        def layer_calls(deferred):
+            call = ctx.decode_attn_deferred if deferred else ctx.decode_attn
+            for l in range(n_layers):
+                call(shape, qs[l], ks[l], vs[l], masks[l], pair[(l - 1) % 2] if l else None, outs[l],
+                     pair[l % 2], lens, ws2)
+            if deferred:
+                ctx.select_flush()
+        calls_sec = timed(lambda: layer_calls(False), max(3, args.steps // 3), 1)
+        deferred_sec = timed(lambda: layer_calls(True), max(3, args.steps // 3), 1)
+        del ws2
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
     probe_bytes = ks[0].numel() * 2
     n_probe = min(n_layers, 8)
@@ -254,6 +271,10 @@ def main() -> int:
         result["dense_achieved_gbps"] = round(dense_bytes / dense_sec / 1e9, 1)
         result["speedup_vs_dense"] = round(dense_sec / sec, 3)
         result["speedup_vs_dense_%s" % other] = round(dense_other_sec / other_sec, 3)
+    if calls_sec is not None:
+        # the step as n_layers lychee_decode_attn calls, and as lychee_decode_attn_deferred calls + a flush
+        result["layer_calls_us"] = round(calls_sec * 1e6, 2)
+        result["layer_calls_deferred_select_us"] = round(deferred_sec * 1e6, 2)
 
     # ---- the CPU oracle on a bounded sample of the same workload --------------------------
     if not args.no_cpu_baseline:
