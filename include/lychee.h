@@ -261,6 +261,7 @@ int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, vo
  *                 small that fewer than k rows pass, or so large that the candidate list
  *                 overflows, costs time (the row is then ranked from all of its scores) but
  *                 never changes a result */
+#define LYCHEE_OPT_DEFAULTS     0   /* puts every option back to its default (value ignored) */
 #define LYCHEE_OPT_WG_PER_CU    1
 #define LYCHEE_OPT_STEP_MODE    2
 #define LYCHEE_OPT_GATHER_BLOCK 6

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "liblychee.so")
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 KERNEL_STREAM, KERNEL_GATHER, KERNEL_THRESHOLD, KERNEL_SELECT, KERNEL_COMBINE = 0, 1, 2, 3, 4
 N_KERNEL_CLASSES = 5
+OPT_DEFAULTS = 0
 OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE, OPT_SELECT_MARGIN = 1, 2, 6, 7, 8, 9
 STEP_PHASED, STEP_LAYERWISE = 1, 0
 RULE_THRESHOLD, RULE_TOP_P = 1, 2

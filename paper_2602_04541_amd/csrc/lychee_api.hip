@@ -210,23 +210,29 @@ int32_t *idx_set_of(const Workspace &w, char *ws, int layer_slot)
     return reinterpret_cast<int32_t *>(ws + (size_t)layer_slot * w.layer_bytes + w.idx_set);
 }
 
-uint64_t hash_bytes(const void *p, size_t n)
+// FNV-1a over 64-bit words (descriptor tables are a whole number of them).
+uint64_t hash_words(const void *p, size_t bytes)
 {
     const unsigned char *b = static_cast<const unsigned char *>(p);
-    uint64_t h = 1469598103934665603ull;  // FNV-1a
-    for (size_t i = 0; i < n; ++i) h = (h ^ b[i]) * 1099511628211ull;
+    uint64_t h = 1469598103934665603ull;
+    for (size_t i = 0; i + 8 <= bytes; i += 8) {
+        uint64_t w;
+        memcpy(&w, b + i, 8);
+        h = (h ^ w) * 1099511628211ull;
+    }
     return h;
 }
+static_assert(sizeof(LayerDesc) % 8 == 0, "tables are hashed word by word");
 
-// Returns the device address of a table with exactly these descriptors, uploading it (one
+// Returns the device address of a table with exactly these n descriptors, uploading it (one
 // asynchronous copy on `stream`) unless an identical table is already resident.
-const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &descs, hipStream_t stream)
+const LayerDesc *resident_table(lychee_ctx *ctx, const LayerDesc *descs, size_t n, hipStream_t stream)
 {
-    const size_t bytes = descs.size() * sizeof(LayerDesc);
+    const size_t bytes = n * sizeof(LayerDesc);
     if (bytes > kArenaBytes - kArenaReserved) return nullptr;
-    const uint64_t h = hash_bytes(descs.data(), bytes);
+    const uint64_t h = hash_words(descs, bytes);
     for (const auto &e : ctx->cache)
-        if (e.hash == h && e.bytes == bytes && memcmp(ctx->arena_host + e.offset, descs.data(), bytes) == 0)
+        if (e.hash == h && e.bytes == bytes && memcmp(ctx->arena_host + e.offset, descs, bytes) == 0)
             return reinterpret_cast<const LayerDesc *>(ctx->arena_dev + e.offset);
     if (ctx->arena_used + bytes > kArenaBytes) {
         // Arena full: start over.  Tables still in use by enqueued launches, and staging
@@ -236,7 +242,7 @@ const LayerDesc *resident_table(lychee_ctx *ctx, const std::vector<LayerDesc> &d
         ctx->cache.clear();
     }
     const size_t off = ctx->arena_used;
-    memcpy(ctx->arena_host + off, descs.data(), bytes);
+    memcpy(ctx->arena_host + off, descs, bytes);
     if (hipMemcpyAsync(ctx->arena_dev + off, ctx->arena_host + off, bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
         return nullptr;
     ctx->arena_used = (size_t)round_up((int64_t)(off + bytes), 256);
@@ -494,7 +500,7 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     fin.idx_out = idx_out;
     fin.copy_keep = 1;
 
-    const LayerDesc *table = resident_table(ctx, descs, stream);
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
 
@@ -543,6 +549,44 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     return LYCHEE_OK;
 }
 
+// One layer call.
+int decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q, const void *k_cache,
+                const void *v_cache, const uint8_t *head_type_mask, const int32_t *idx_in, void *out,
+                int32_t *idx_out, const int32_t *lengths, void *workspace, size_t workspace_bytes,
+                void *hip_stream)
+{
+    int rc = check_common(ctx, shape, workspace, workspace_bytes, 1);
+    if (rc != LYCHEE_OK) return rc;
+    rc = check_mask(shape, head_type_mask, idx_in != nullptr);
+    if (rc != LYCHEE_OK) return rc;
+    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr ||
+        idx_out == nullptr || lengths == nullptr)
+        return LYCHEE_EINVAL;
+    if (!aligned(q, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 16) ||
+        !aligned(idx_out, 4) || !aligned(idx_in, 4) || !aligned(lengths, 4))
+        return LYCHEE_EINVAL;
+    if (idx_in == idx_out) return LYCHEE_EINVAL;
+    if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = carve(*shape, 1);
+    LayerDesc d;  // (on the stack: this path allocates nothing, not even host memory)
+    memset(&d, 0, sizeof d);
+    d.q = static_cast<const uint16_t *>(q);
+    d.k_cache = static_cast<const uint16_t *>(k_cache);
+    d.v_cache = static_cast<const uint16_t *>(v_cache);
+    d.out = static_cast<uint16_t *>(out);
+    set_groups(d, *shape, head_type_mask);
+    set_scratch(d, w, static_cast<char *>(workspace), 0);
+    d.idx_out = idx_out;
+    for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = idx_in;
+    d.emit_sel = 1;
+    d.copy_keep = 1;
+    const LayerDesc *table = resident_table(ctx, &d, 1, stream);
+    if (table == nullptr) return LYCHEE_EHIP;
+    const Launcher L{ctx, *shape, w, lengths, table, &d, stream};
+    return run_layer(L, 0, true, true);
+}
+
 }  // namespace
 
 extern "C" {
@@ -557,6 +601,8 @@ int lychee_create(lychee_ctx **out, int device)
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return LYCHEE_EHIP;
     lychee_ctx *ctx = new (std::nothrow) lychee_ctx();
     if (ctx == nullptr) return LYCHEE_EHIP;
+    ctx->cache.reserve(kArenaBytes / 1024 + 1);  // (a table is at least a descriptor: the hot calls never grow these)
+    ctx->used_slots.reserve(kTicketRing);
     ctx->device = device;
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     int cur = -1;
@@ -614,37 +660,8 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
                        const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
                        void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_common(ctx, shape, workspace, workspace_bytes, 1);
-    if (rc != LYCHEE_OK) return rc;
-    rc = check_mask(shape, head_type_mask, idx_in != nullptr);
-    if (rc != LYCHEE_OK) return rc;
-    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr ||
-        idx_out == nullptr || lengths == nullptr)
-        return LYCHEE_EINVAL;
-    if (!aligned(q, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 16) ||
-        !aligned(idx_out, 4) || !aligned(idx_in, 4) || !aligned(lengths, 4))
-        return LYCHEE_EINVAL;
-    if (idx_in == idx_out) return LYCHEE_EINVAL;
-    if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
-    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const Workspace w = carve(*shape, 1);
-    std::vector<LayerDesc> descs(1);
-    LayerDesc &d = descs[0];
-    memset(&d, 0, sizeof d);
-    d.q = static_cast<const uint16_t *>(q);
-    d.k_cache = static_cast<const uint16_t *>(k_cache);
-    d.v_cache = static_cast<const uint16_t *>(v_cache);
-    d.out = static_cast<uint16_t *>(out);
-    set_groups(d, *shape, head_type_mask);
-    set_scratch(d, w, static_cast<char *>(workspace), 0);
-    d.idx_out = idx_out;
-    for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = idx_in;
-    d.emit_sel = 1;
-    d.copy_keep = 1;
-    const LayerDesc *table = resident_table(ctx, descs, stream);
-    if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    return run_layer(L, 0, true, true);
+    return decode_attn(ctx, shape, q, k_cache, v_cache, head_type_mask, idx_in, out, idx_out, lengths, workspace,
+                       workspace_bytes, hip_stream);
 }
 
 int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
@@ -690,7 +707,7 @@ int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, cons
     d.emit_sel = 1;
     d.copy_keep = 1;
     if (pd.active) descs[1] = pd.desc;
-    const LayerDesc *table = resident_table(ctx, descs, stream);
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     Ranges t;
@@ -728,7 +745,7 @@ int lychee_select_flush(lychee_ctx *ctx, void *hip_stream)
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Workspace w = carve(pd.shape, 2);
     std::vector<LayerDesc> descs(1, pd.desc);
-    const LayerDesc *table = resident_table(ctx, descs, stream);
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, pd.shape, w, pd.lengths, table, descs.data(), stream};
     Ranges sl;
@@ -762,7 +779,7 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
     d.out = static_cast<uint16_t *>(out);
     set_groups(d, *shape, nullptr);
     set_scratch(d, w, static_cast<char *>(workspace), 0);
-    const LayerDesc *table = resident_table(ctx, descs, stream);
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     return run_layer(L, 0, false, false);
@@ -811,7 +828,7 @@ int lychee_append_kv(lychee_ctx *ctx, const lychee_shape *shape, const void *k_n
     d.v_cache = static_cast<const uint16_t *>(v_cache);
     d.k_new = static_cast<const uint16_t *>(k_new);
     d.v_new = static_cast<const uint16_t *>(v_new);
-    const LayerDesc *table = resident_table(ctx, descs, stream);
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Workspace w = carve(*shape, 1);
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
@@ -852,7 +869,7 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
         set_groups(d, *shape, nullptr);
         set_scratch(d, w, static_cast<char *>(workspace), l);
     }
-    const LayerDesc *table = resident_table(ctx, descs, stream);
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     if (ctx->step_mode != LYCHEE_STEP_PHASED || n_layers == 1 || (int64_t)n_layers * shape->batch > kMaxItems) {
@@ -908,6 +925,16 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
 {
     if (ctx == nullptr) return LYCHEE_EINVAL;
     switch (option) {
+    case LYCHEE_OPT_DEFAULTS: {
+        const lychee_ctx fresh{};
+        ctx->wg_per_cu = fresh.wg_per_cu;
+        ctx->n_wg = fresh.n_wg;
+        ctx->step_mode = fresh.step_mode;
+        ctx->g_block_rows = fresh.g_block_rows;
+        ctx->tail_permille = fresh.tail_permille;
+        ctx->select_margin = fresh.select_margin;
+        return LYCHEE_OK;
+    }
     case LYCHEE_OPT_WG_PER_CU:
         if (value < 1 || value > 3) return LYCHEE_EINVAL;
         ctx->wg_per_cu = value;

@@ -162,6 +162,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
         return by_block ? r0 + (span >> 1) * (2 * kSpan) + 64 * wave + 32 * (span & 1) : r0 + span * kSpan + 32 * wave;
     };
     float block_best = 0.0f;
+    const int n_units = units_of(c, L);  // set entries at or beyond this name nothing
 
     // tile `half` (0 or 1) of span `span`: rows base .. base+15 of this wavefront
     auto issue = [&](Tile &t, int span, int half) {
@@ -178,8 +179,11 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
                 // arithmetic removes the branches the compiler puts around these reads, and
                 // made the gather launch 3.5 % slower)
                 const int e = (r < r1) ? idx_s[(r - r0) >> bshift] : -1;
-                const int tpos = (e << bshift) + (r & ((1 << bshift) - 1));
-                ok = (e >= 0) && (tpos < L);
+                // the entry is range-checked before it is shifted: a junk entry of 2^25 or more
+                // would otherwise wrap to a negative position that passes `tpos < L`
+                const bool named = (uint32_t)e < (uint32_t)n_units;
+                const int tpos = named ? (e << bshift) + (r & ((1 << bshift) - 1)) : 0;
+                ok = named && (tpos < L);
                 row = ok ? tpos : 0;
             } else {
                 ok = r < r1;
