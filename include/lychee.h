@@ -167,6 +167,26 @@ int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, cons
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 int lychee_select_flush(lychee_ctx *ctx, void *hip_stream);
 
+/*
+ * lychee_decode_attn for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same layer call without a workspace
+ * argument.  Its scratch is an array of LYCHEE_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library's device code, so every GPU the library runs on holds it until the process ends; the
+ * call allocates nothing, on the device or on the host.  Arguments, results and errors as for
+ * lychee_decode_attn, and:
+ *   EWORKSPACE    lychee_workspace_bytes(shape) exceeds LYCHEE_STATIC_SCRATCH_BYTES (the Qwen3-8B-shaped
+ *                 128K layer at batch 1 needs about 22 MiB); nothing is enqueued
+ *   EUNSUPPORTED  per-launch timing is enabled on the context (it creates events)
+ * All calls on one GPU share the one array, whatever their context or stream, and it keeps the last
+ * call's contents (which no call depends on): calls that overlap on a GPU race, so order them on one
+ * stream or with events.
+ */
+#define LYCHEE_STATIC_SCRATCH_BYTES (32u << 20)
+int lychee_decode_attn_static(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
+                              const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
+                              const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
+                              void *hip_stream);
+
 /* Dense decode attention on the same buffers: every head runs Eq. 1 and o = A V, nothing
  * is selected.  The in-run speed baseline; `shape->k` is ignored (any value >= 1). */
 int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q,

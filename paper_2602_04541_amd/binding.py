@@ -21,6 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 KERNEL_STREAM, KERNEL_GATHER, KERNEL_THRESHOLD, KERNEL_SELECT, KERNEL_COMBINE = 0, 1, 2, 3, 4
 N_KERNEL_CLASSES = 5
 OPT_DEFAULTS = 0
+STATIC_SCRATCH_BYTES = 32 << 20
 OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE, OPT_SELECT_MARGIN = 1, 2, 6, 7, 8, 9
 STEP_PHASED, STEP_LAYERWISE = 1, 0
 RULE_THRESHOLD, RULE_TOP_P = 1, 2
@@ -28,7 +29,7 @@ RULE_THRESHOLD, RULE_TOP_P = 1, 2
 EXPORTS = [
     "lychee_create", "lychee_destroy", "lychee_check_shape", "lychee_workspace_bytes",
     "lychee_step_workspace_bytes",
-    "lychee_decode_attn", "lychee_decode_attn_deferred", "lychee_select_flush",
+    "lychee_decode_attn", "lychee_decode_attn_static", "lychee_decode_attn_deferred", "lychee_select_flush",
     "lychee_dense_decode_attn", "lychee_decode_step",
     "lychee_dense_decode_step", "lychee_decode_step_append", "lychee_append_kv", "lychee_select_stats",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
@@ -69,6 +70,7 @@ def _load() -> ctypes.CDLL:
     lib.lychee_step_workspace_bytes.restype = sz
     lib.lychee_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_attn_deferred.argtypes = lib.lychee_decode_attn.argtypes
+    lib.lychee_decode_attn_static.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.lychee_select_flush.argtypes = [vp, vp]
     lib.lychee_dense_decode_attn.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_decode_step.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -179,6 +181,15 @@ class Context:
                                        _ptr(idx_out), _ptr(lengths), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(),
                                        _stream(stream)), "lychee_decode_attn")
+
+    def decode_attn_static(self, shape: Shape, q, k_cache, v_cache, head_type_mask: np.ndarray, idx_in,
+                           out, idx_out, lengths, stream=None) -> None:
+        """lychee_decode_attn on the library's own static scratch: no workspace, no allocation."""
+        mask = np.ascontiguousarray(head_type_mask, dtype=np.uint8)
+        _check(_lib.lychee_decode_attn_static(self._h, ctypes.byref(shape), _ptr(q), _ptr(k_cache),
+                                              _ptr(v_cache), mask.ctypes.data, _ptr(idx_in), _ptr(out),
+                                              _ptr(idx_out), _ptr(lengths), _stream(stream)),
+               "lychee_decode_attn_static")
 
     def decode_attn_deferred(self, shape: Shape, q, k_cache, v_cache, head_type_mask: np.ndarray,
                              idx_in, out, idx_out, lengths, workspace, stream=None) -> None:

@@ -14,6 +14,12 @@
 using namespace lychee;
 
 namespace {
+// Scratch of lychee_decode_attn_static, the entry point for callers that cannot allocate: every
+// GPU the library is loaded on holds this array until the process ends.  In host code the name
+// is only a handle for hipGetSymbolAddress; the device address is looked up once per context
+// (lychee_create, with the context's device current) and only that address is ever passed on.
+static __device__ __align__(256) unsigned char scratch[LYCHEE_STATIC_SCRATCH_BYTES];
+
 constexpr size_t kArenaBytes = 4u << 20;  // device memory for descriptor tables, per context
 constexpr size_t kArenaReserved = 512;    // its first bytes hold the ring of chunk counters (256 B)
 constexpr size_t kArenaStats = 256;       // and, from here, the select's fall-back counters
@@ -40,6 +46,7 @@ struct lychee_ctx {
     // Descriptor tables: built on the host, staged in pinned memory, copied to the arena
     // with an asynchronous copy on the caller's stream, and cached by content so that a
     // serving loop that passes the same buffers every step uploads nothing.
+    void *static_scratch = nullptr;  // this device's address of the file-scope scratch array
     char *arena_dev = nullptr;
     char *arena_host = nullptr;  // pinned, same layout as the device arena
     size_t arena_used = 0;
@@ -549,7 +556,7 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     return LYCHEE_OK;
 }
 
-// One layer call.
+// One layer call (lychee_decode_attn; lychee_decode_attn_static with the library's own scratch).
 int decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q, const void *k_cache,
                 const void *v_cache, const uint8_t *head_type_mask, const int32_t *idx_in, void *out,
                 int32_t *idx_out, const int32_t *lengths, void *workspace, size_t workspace_bytes,
@@ -610,6 +617,8 @@ int lychee_create(lychee_ctx **out, int device)
     ok = ok && hipMalloc(reinterpret_cast<void **>(&ctx->arena_dev), kArenaBytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void **>(&ctx->arena_host), kArenaBytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemset(ctx->arena_dev, 0, kArenaReserved) == hipSuccess;
+    ok = ok && hipGetSymbolAddress(&ctx->static_scratch, HIP_SYMBOL(scratch)) == hipSuccess &&
+         ctx->static_scratch != nullptr;
     ctx->arena_used = kArenaReserved;
     if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     if (!ok) {
@@ -662,6 +671,21 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
 {
     return decode_attn(ctx, shape, q, k_cache, v_cache, head_type_mask, idx_in, out, idx_out, lengths, workspace,
                        workspace_bytes, hip_stream);
+}
+
+int lychee_decode_attn_static(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
+                              const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
+                              const int32_t *idx_in, void *out, int32_t *idx_out, const int32_t *lengths,
+                              void *hip_stream)
+{
+    if (ctx == nullptr) return LYCHEE_EINVAL;
+    const int rc = check_shape(shape);
+    if (rc != LYCHEE_OK) return rc;
+    // the shape's scratch must fit the static array: nothing is allocated to make room
+    if (carve(*shape, 1).total > (size_t)LYCHEE_STATIC_SCRATCH_BYTES) return LYCHEE_EWORKSPACE;
+    if (ctx->timing) return LYCHEE_EUNSUPPORTED;  // timing creates events: not from this entry point
+    return decode_attn(ctx, shape, q, k_cache, v_cache, head_type_mask, idx_in, out, idx_out, lengths,
+                       ctx->static_scratch, (size_t)LYCHEE_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
