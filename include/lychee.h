@@ -288,6 +288,7 @@ int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, vo
 #define LYCHEE_OPT_N_WG         7
 #define LYCHEE_OPT_TAIL_PERMILLE 8
 #define LYCHEE_OPT_SELECT_MARGIN 9
+#define LYCHEE_OPT_SELECT_LEAD  10
 #define LYCHEE_STEP_PHASED      1
 #define LYCHEE_STEP_LAYERWISE   0
 int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);

@@ -21,6 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 KERNEL_STREAM, KERNEL_GATHER, KERNEL_THRESHOLD, KERNEL_SELECT, KERNEL_COMBINE = 0, 1, 2, 3, 4
 N_KERNEL_CLASSES = 5
 OPT_DEFAULTS = 0
+OPT_SELECT_LEAD = 10
 STATIC_SCRATCH_BYTES = 32 << 20
 OPT_WG_PER_CU, OPT_STEP_MODE, OPT_GATHER_BLOCK, OPT_N_WG, OPT_TAIL_PERMILLE, OPT_SELECT_MARGIN = 1, 2, 6, 7, 8, 9
 STEP_PHASED, STEP_LAYERWISE = 1, 0

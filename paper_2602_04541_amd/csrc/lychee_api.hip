@@ -34,6 +34,7 @@ struct lychee_ctx {
     int32_t g_block_rows = 48;
     int32_t tail_permille = 250;
     int32_t select_margin = 60;  // tenths of a standard deviation, see LYCHEE_OPT_SELECT_MARGIN
+    int32_t select_lead = 4000;  // blocks of 64 rows streamed while a select runs, see LYCHEE_OPT_SELECT_LEAD
     uint32_t launch_seq = 0;   // pooled launches so far: picks the chunk counter
     std::vector<int32_t> used_slots;  // counters of pooled launches that no later launch has reset yet
     bool timing = false;
@@ -47,6 +48,12 @@ struct lychee_ctx {
     // with an asynchronous copy on the caller's stream, and cached by content so that a
     // serving loop that passes the same buffers every step uploads nothing.
     void *static_scratch = nullptr;  // this device's address of the file-scope scratch array
+    // What the workgroups of a layer launch hand to one another (zeroed once, then kept clean by
+    // the launches themselves): the launch generation, the threshold and set flags, the
+    // segments' arrival counters, and three banks of candidate counters (banks 0 and 1 alternate
+    // between the layer calls that leave their select pending; calls that do not, and the layers of a
+    // layer-after-layer step, use bank 2 and whichever of the others no pending select owns).
+    char *sync_dev = nullptr;
     char *arena_dev = nullptr;
     char *arena_host = nullptr;  // pinned, same layout as the device arena
     size_t arena_used = 0;
@@ -63,10 +70,20 @@ struct lychee_ctx {
         const int32_t *lengths = nullptr;
         void *workspace = nullptr;
         int slot = 0;                // which of the workspace's two layer slots holds its scratch
+        int bank = 0;                // which bank of candidate counters it collected into
     } pending;
 };
 
 namespace {
+
+// Layout of lychee_ctx::sync_dev
+constexpr size_t kSyncGen = 0, kSyncExit = 64;
+constexpr size_t kSyncRows = (size_t)kMaxBatch * kMaxKvHeads;  // (sequence, KV head) pairs a shape can have
+constexpr size_t kSyncThr = 4096;                               // uint64 [kSyncRows]
+constexpr size_t kSyncSet = kSyncThr + kSyncRows * 8;           // uint32 [kSyncRows]
+constexpr size_t kSyncSeg = kSyncSet + kSyncRows * 4;           // uint32 [kSyncRows][2]
+constexpr size_t kSyncCount = kSyncSeg + kSyncRows * 8;         // int32 [3][kSyncRows]
+constexpr size_t kSyncBytes = kSyncCount + 3 * kSyncRows * 4;
 
 constexpr int kWsWg = 768;        // largest grid a launch uses
 constexpr int kPartSlots = 1024;  // partial slots per head in the workspace: static runs + chunks
@@ -274,6 +291,48 @@ hipEvent_t take_event(lychee_ctx *ctx)
     return e;
 }
 
+// The part of a launch's arguments that follows from the shape and the context alone.
+void fill_common(Common &c, const lychee_ctx *ctx, const lychee_shape &s, const Workspace &w,
+                 const int32_t *lengths, int n_wg)
+{
+    c.lengths = lengths;
+    c.stride_b = s.kv_stride_batch;
+    c.stride_h = s.kv_stride_head;
+    c.stride_t = s.kv_stride_tok;
+    c.batch = s.batch;
+    c.n_q_heads = s.n_q_heads;
+    c.n_kv_heads = s.n_kv_heads;
+    c.group = s.n_q_heads / s.n_kv_heads;
+    c.k = s.k;
+    c.keep_ppm = s.keep_ppm;
+    c.block_shift = s.block_size == 64 ? 6 : 0;
+    c.prob_rule = s.prob_rule;
+    c.prob_param = s.prob_param;
+    c.max_len = s.max_len;
+    c.sel_stride = w.sel_stride;
+    c.list_row = w.list_row;
+    c.n_wg = n_wg;
+    c.part_stride = kPartSlots;
+    c.g_block_rows = ctx->g_block_rows;
+    c.tickets = reinterpret_cast<uint32_t *>(ctx->arena_dev);
+    c.stats = reinterpret_cast<uint32_t *>(ctx->arena_dev + kArenaStats);
+    c.tail_permille = ctx->tail_permille;
+    // chunks small enough to level the finish times, large enough that a segment
+    // never has more than ~192 of them (partial slots per head are limited)
+    const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
+    c.chunk_blocks = (int32_t)((seg_blocks + 191) / 192);
+    if (c.chunk_blocks < 2) c.chunk_blocks = 2;
+    c.sel_margin = 0.1f * (float)ctx->select_margin;
+    c.scale = (float)(1.0 / sqrt((double)kHeadDim));
+    c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
+}
+
+int grid_of(const lychee_ctx *ctx)
+{
+    const int n_wg = ctx->n_wg > 0 ? ctx->n_wg : ctx->n_cu * ctx->wg_per_cu;
+    return n_wg > kWsWg ? kWsWg : n_wg;
+}
+
 struct Launcher {
     lychee_ctx *ctx;
     const lychee_shape &s;
@@ -283,54 +342,14 @@ struct Launcher {
     const LayerDesc *host_table;  // the same descriptors on the host
     hipStream_t stream;
 
-    int grid() const
-    {
-        const int n_wg = ctx->n_wg > 0 ? ctx->n_wg : ctx->n_cu * ctx->wg_per_cu;
-        return n_wg > kWsWg ? kWsWg : n_wg;
-    }
+    int grid() const { return grid_of(ctx); }
     int go(const Ranges &r) const
     {
         if (r.r_count + r.g_count + r.c_count + r.t_count + r.s_count + r.a_count == 0) return LYCHEE_OK;
-#ifdef LYCHEE_TRACE
-        {   // trace builds: LYCHEE_TRACE_STOP=n drops every launch after the n-th of a call
-            static int budget = -1, left = 0;
-            if (budget < 0) budget = getenv("LYCHEE_TRACE_STOP") ? atoi(getenv("LYCHEE_TRACE_STOP")) : 0;
-            if (budget > 0) {
-                if (r.t_count > 0 && r.t_first == 0) left = budget;  // a call starts with its thresholds
-                if (left-- <= 0) return LYCHEE_OK;
-            }
-        }
-#endif
         LaunchPlan p;
         memset(&p, 0, sizeof p);
         Common &c = p.c;
-        c.lengths = lengths;
-        c.stride_b = s.kv_stride_batch;
-        c.stride_h = s.kv_stride_head;
-        c.stride_t = s.kv_stride_tok;
-        c.batch = s.batch;
-        c.n_q_heads = s.n_q_heads;
-        c.n_kv_heads = s.n_kv_heads;
-        c.group = s.n_q_heads / s.n_kv_heads;
-        c.k = s.k;
-        c.keep_ppm = s.keep_ppm;
-        c.block_shift = s.block_size == 64 ? 6 : 0;
-        c.prob_rule = s.prob_rule;
-        c.prob_param = s.prob_param;
-        c.max_len = s.max_len;
-        c.sel_stride = w.sel_stride;
-        c.list_row = w.list_row;
-        c.n_wg = grid();
-        c.part_stride = kPartSlots;
-        c.g_block_rows = ctx->g_block_rows;
-        c.tickets = reinterpret_cast<uint32_t *>(ctx->arena_dev);
-        c.stats = reinterpret_cast<uint32_t *>(ctx->arena_dev + kArenaStats);
-        c.tail_permille = ctx->tail_permille;
-        // chunks small enough to level the finish times, large enough that a segment
-        // never has more than ~192 of them (partial slots per head are limited)
-        const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
-        c.chunk_blocks = (int32_t)((seg_blocks + 191) / 192);
-        if (c.chunk_blocks < 2) c.chunk_blocks = 2;
+        fill_common(c, ctx, s, w, lengths, grid());
         if (r.r_count || r.g_count) {
             c.ticket_slot = (int32_t)(ctx->launch_seq++ % kTicketRing);
             ctx->used_slots.push_back(c.ticket_slot);
@@ -343,9 +362,6 @@ struct Launcher {
             }
             ctx->used_slots.clear();
         }
-        c.sel_margin = 0.1f * (float)ctx->select_margin;
-        c.scale = (float)(1.0 / sqrt((double)kHeadDim));
-        c.scale_log2e = (float)(1.4426950408889634 / sqrt((double)kHeadDim));
         p.layers = table;
         p.r_first = r.r_first, p.r_count = r.r_count;
         p.g_first = r.g_first, p.g_count = r.g_count;
@@ -403,26 +419,77 @@ struct Launcher {
     }
 };
 
-// Layer `l` of the table, dependent launches: T (only when the layer selects; the cache append,
-// if the layer has one, rides along or goes alone), then R+G, then C.  The layer's own S units
-// go with C when `select_now`; `select_prev` >= 0 names an earlier layer whose S units ride in
-// the first launch instead: nothing of layer l before its gather needs them, and a select next
-// to the thresholds costs no launch of its own.
-int run_layer(const Launcher &L, int l, bool select, bool select_now, int select_prev = -1)
+// The row spaces of a layer launch are indexed with 32-bit integers.
+int check_layer_space(const lychee_shape &s, const LayerDesc &d)
 {
-    int rc;
-    Ranges t;
-    if (select && L.s.block_size != 64) t.t_first = l, t.t_count = 1;  // block scores need no threshold
-    if (L.host_table[l].k_new != nullptr) t.a_first = l, t.a_count = 1;
-    if (select_prev >= 0) t.s_first = select_prev, t.s_count = 1;
-    if ((rc = L.go(t)) != LYCHEE_OK) return rc;
-    Ranges a;
-    a.r_first = a.g_first = l, a.r_count = a.g_count = 1;
-    if ((rc = L.go(a)) != LYCHEE_OK) return rc;
-    Ranges b;
-    b.c_first = l, b.c_count = 1;
-    if (select && select_now) b.s_first = l, b.s_count = 1;
-    return L.go(b);
+    const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
+    if ((int64_t)(d.n_rgroups + d.n_sgroups) * s.batch * (4 * seg_blocks + 8) >= (1ll << 31))
+        return LYCHEE_EUNSUPPORTED;  // (gathered blocks are shorter than streamed ones)
+    return LYCHEE_OK;
+}
+
+// One launch of lychee_layer_kernel: everything `cur`'s output needs (cur may be null: only the
+// pending select), with the select and set copies of `prev` (may be null) among its front units.
+// Every check happens before the launch; nothing else is enqueued.
+int layer_launch(lychee_ctx *ctx, const lychee_shape &s, const Workspace &w, const int32_t *lengths,
+                 const LayerDesc *cur, const LayerDesc *prev, hipStream_t stream)
+{
+    if (cur == nullptr && prev == nullptr) return LYCHEE_OK;
+    LayerLaunch p;
+    memset(&p, 0, sizeof p);
+    const int W = grid_of(ctx);
+    fill_common(p.c, ctx, s, w, lengths, W);
+    const bool blocks = s.block_size == 64;
+    int64_t units = 0;
+    if (prev != nullptr) {
+        p.prev = *prev;
+        p.has_prev = 1;
+        units += (int64_t)s.batch * prev->n_rgroups;
+        if (prev->copy_keep) units += (int64_t)s.batch * (s.n_kv_heads - prev->n_rgroups);
+    }
+    if (cur != nullptr) {
+        p.cur = *cur;
+        p.has_cur = 1;
+        if (cur->emit_sel && !blocks) units += (int64_t)s.batch * cur->n_rgroups;
+        if (prev != nullptr)
+            for (int g = 0; g < s.n_kv_heads; ++g)
+                if (cur->idx_src[g] != nullptr && cur->idx_src[g] == prev->idx_out &&
+                    (prev->rindex[g] != 0xFF || prev->copy_keep))
+                    p.gate_mask |= 1ull << g;
+        const int rc = check_layer_space(s, *cur);
+        if (rc != LYCHEE_OK) return rc;
+    } else {
+        // only front units: one workgroup each, up to the usual grid
+        p.c.n_wg = (int32_t)(units < 1 ? 1 : (units > W ? W : units));
+    }
+    // The front units get up to a quarter of the grid to themselves (a handful of workgroups in a
+    // batch-1 call); a grid too small to set workgroups aside lets them take pieces afterwards.
+    const int wg = p.c.n_wg;
+    const int front_max = cur == nullptr ? wg : (wg >= 8 ? wg / 4 : wg);
+    p.n_front = (int32_t)(units < front_max ? units : front_max);
+    p.lead_blocks = ctx->select_lead;
+    p.gen = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncGen);
+    p.exit_count = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncExit);
+    p.thr_flags = reinterpret_cast<unsigned long long *>(ctx->sync_dev + kSyncThr);
+    p.set_flags = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncSet);
+    p.seg_count = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncSeg);
+    const bool selects = prev != nullptr && prev->n_rgroups > 0;
+    const bool collects = cur != nullptr && cur->emit_sel;
+    const int build = !(selects || collects) ? 0 : (s.prob_rule != 0 ? 2 : 1);
+    if (!ctx->timing) return launch_layer(p, build, stream) == hipSuccess ? LYCHEE_OK : LYCHEE_EHIP;
+    lychee_ctx::Rec rec{cur != nullptr ? LYCHEE_KERNEL_STREAM : LYCHEE_KERNEL_SELECT, take_event(ctx), take_event(ctx)};
+    if (rec.start == nullptr || rec.stop == nullptr) return LYCHEE_EHIP;
+    if (hipEventRecord(rec.start, stream) != hipSuccess) return LYCHEE_EHIP;
+    if (launch_layer(p, build, stream) != hipSuccess) return LYCHEE_EHIP;
+    if (hipEventRecord(rec.stop, stream) != hipSuccess) return LYCHEE_EHIP;
+    ctx->recs.push_back(rec);
+    return LYCHEE_OK;
+}
+
+// The candidate counters of a layer that a layer launch streams: one of the context's two banks.
+int32_t *count_bank(lychee_ctx *ctx, int bank)
+{
+    return reinterpret_cast<int32_t *>(ctx->sync_dev + kSyncCount) + (size_t)bank * kSyncRows;
 }
 
 int check_step_pointers(int32_t n_layers, const void *const *q, const void *const *k_cache,
@@ -492,9 +559,6 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
         d.idx_out = idx_set_of(w, ws, l);
         for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = cur[g];
         d.emit_sel = l < n_select;
-#ifdef LYCHEE_TRACE
-        if (getenv("LYCHEE_TRACE_NOSEL")) d.emit_sel = 0;  // trace builds: cost of collecting candidates
-#endif
         d.copy_keep = 0;
         for (int i = 0; i < d.n_rgroups; ++i) cur[d.rgroup[i]] = d.idx_out;
     }
@@ -507,29 +571,41 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     fin.idx_out = idx_out;
     fin.copy_keep = 1;
 
-    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-    if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-
     // (a single layer has nothing to pool across layers: its streaming and gather share a launch)
     const bool phased = ctx->step_mode == LYCHEE_STEP_PHASED && n_layers > 1 &&
                         (int64_t)n_layers * shape->batch <= kMaxItems;
     if (!phased) {
-        // Layer l's output needs its partials combined, not its sets selected: where layer
-        // l + 1 starts with a launch of small units anyway (thresholds, an append), the select
-        // of layer l waits for that launch and runs beside them; otherwise it goes with the
-        // combine of its own layer.
-        auto has_first_launch = [&](int l) {
-            return l < n_layers && ((l < n_select && shape->block_size != 64) || k_new != nullptr);
-        };
-        for (int l = 0; l < n_layers; ++l) {
-            const bool prev_waits = l > 0 && l - 1 < n_select && has_first_launch(l);
-            rc = run_layer(L, l, l < n_select, !has_first_launch(l + 1), prev_waits ? l - 1 : -1);
-            if (rc != LYCHEE_OK) return rc;
+        // Layer after layer, one launch each: out[l] is complete when launch l is.  The select of
+        // layer l is read again only by layer l + 1's sparse heads, so it runs among the front
+        // units of launch l + 1, beside that layer's streaming; the last layer's runs alone.
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = check_layer_space(*shape, descs[l])) != LYCHEE_OK) return rc;
+        if (k_new != nullptr) {  // every layer's append first, in one small launch (they are all inputs of the call)
+            const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
+            if (table == nullptr) return LYCHEE_EHIP;
+            const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
+            Ranges t;
+            t.a_first = 0, t.a_count = n_layers;
+            if ((rc = L.go(t)) != LYCHEE_OK) return rc;
         }
+        const int other = ctx->pending.active ? 1 - ctx->pending.bank : 0;
+        LayerDesc &last = descs[n_layers - 1];
+        if (assemble) {  // the last layer writes the caller's array: its own sets, copies of the kept ones
+            last.idx_out = idx_out;
+            last.copy_keep = 1;
+        }
+        for (int l = 0; l < n_layers; ++l) {
+            descs[l].list_count = count_bank(ctx, (l & 1) ? other : 2);
+            const LayerDesc *prev = l > 0 && descs[l - 1].emit_sel ? &descs[l - 1] : nullptr;
+            if ((rc = layer_launch(ctx, *shape, w, lengths, &descs[l], prev, stream)) != LYCHEE_OK) return rc;
+        }
+        if (assemble && (rc = layer_launch(ctx, *shape, w, lengths, nullptr, &last, stream)) != LYCHEE_OK) return rc;
     } else {
         // All layers at once, one launch per phase; each phase needs only earlier phases:
         //   A + T (appends, thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
+        const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
+        if (table == nullptr) return LYCHEE_EHIP;
+        const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
         Ranges t;
         t.t_first = 0, t.t_count = shape->block_size == 64 ? 0 : n_select;
         if (k_new != nullptr) t.a_first = 0, t.a_count = n_layers;
@@ -547,11 +623,6 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
         c.c_first = 0, c.c_count = n_layers;
         if (assemble) c.s_first = n_layers, c.s_count = 1;  // the set copies ride along
         if ((rc = L.go(c)) != LYCHEE_OK) return rc;
-    }
-    if (assemble && !phased) {
-        Ranges f;
-        f.s_first = n_layers, f.s_count = 1;
-        if ((rc = L.go(f)) != LYCHEE_OK) return rc;
     }
     return LYCHEE_OK;
 }
@@ -588,10 +659,11 @@ int decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q, const
     for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = idx_in;
     d.emit_sel = 1;
     d.copy_keep = 1;
-    const LayerDesc *table = resident_table(ctx, &d, 1, stream);
-    if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, &d, stream};
-    return run_layer(L, 0, true, true);
+    d.list_count = count_bank(ctx, 2);
+    if ((rc = check_layer_space(*shape, d)) != LYCHEE_OK) return rc;
+    // idx_out is complete when the call's work is: the layer's launch, then its select alone
+    if ((rc = layer_launch(ctx, *shape, w, lengths, &d, nullptr, stream)) != LYCHEE_OK) return rc;
+    return layer_launch(ctx, *shape, w, lengths, nullptr, &d, stream);
 }
 
 }  // namespace
@@ -617,12 +689,17 @@ int lychee_create(lychee_ctx **out, int device)
     ok = ok && hipMalloc(reinterpret_cast<void **>(&ctx->arena_dev), kArenaBytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void **>(&ctx->arena_host), kArenaBytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemset(ctx->arena_dev, 0, kArenaReserved) == hipSuccess;
+    ok = ok && hipMalloc(reinterpret_cast<void **>(&ctx->sync_dev), kSyncBytes) == hipSuccess;
+    ok = ok && hipMemset(ctx->sync_dev, 0, kSyncBytes) == hipSuccess;
+    const uint32_t first_gen = 1;  // (zero is what the untouched flags hold)
+    ok = ok && hipMemcpy(ctx->sync_dev + kSyncGen, &first_gen, sizeof first_gen, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipGetSymbolAddress(&ctx->static_scratch, HIP_SYMBOL(scratch)) == hipSuccess &&
          ctx->static_scratch != nullptr;
     ctx->arena_used = kArenaReserved;
     if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     if (!ok) {
         if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
+        if (ctx->sync_dev) (void)hipFree(ctx->sync_dev);
         if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
         delete ctx;
         return LYCHEE_EHIP;
@@ -640,6 +717,7 @@ int lychee_destroy(lychee_ctx *ctx)
     }
     for (auto e : ctx->pool) (void)hipEventDestroy(e);
     if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
+    if (ctx->sync_dev) (void)hipFree(ctx->sync_dev);
     if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
     delete ctx;
     return LYCHEE_OK;
@@ -713,11 +791,8 @@ int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, cons
     const Workspace w = carve(*shape, 2);
     char *ws = static_cast<char *>(workspace);
     const int slot = pd.active ? 1 - pd.slot : 0;
-    // With block-granular sets a layer has no threshold launch for the next layer's call to
-    // carry a select in: the select stays with the layer's combine and nothing is left pending.
-    const bool defer = shape->block_size != 64;
-    std::vector<LayerDesc> descs(pd.active ? 2 : 1);
-    LayerDesc &d = descs[0];
+    const int bank = pd.active ? 1 - pd.bank : 0;
+    LayerDesc d;
     memset(&d, 0, sizeof d);
     d.q = static_cast<const uint16_t *>(q);
     d.k_cache = static_cast<const uint16_t *>(k_cache);
@@ -725,37 +800,25 @@ int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, cons
     d.out = static_cast<uint16_t *>(out);
     set_groups(d, *shape, head_type_mask);
     set_scratch(d, w, ws, slot);
-    if (defer) d.q_keep = reinterpret_cast<uint16_t *>(ws + (size_t)slot * w.layer_bytes + w.q_keep);
+    d.list_count = count_bank(ctx, bank);
+    // a select that ranks a whole score row needs the row's queries: the threshold units leave a
+    // copy (block-granular sets never take that route: their lists are always complete)
+    if (shape->block_size != 64) d.q_keep = reinterpret_cast<uint16_t *>(ws + (size_t)slot * w.layer_bytes + w.q_keep);
     d.idx_out = idx_out;
     for (int g = 0; g < shape->n_kv_heads; ++g) d.idx_src[g] = idx_in;
     d.emit_sel = 1;
     d.copy_keep = 1;
-    if (pd.active) descs[1] = pd.desc;
-    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-    if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    Ranges t;
-    if (defer) t.t_first = 0, t.t_count = 1;
-    if (pd.active) t.s_first = 1, t.s_count = 1;
-    if ((rc = L.go(t)) != LYCHEE_OK) return rc;
-    pd.active = false;
-    Ranges a;
-    a.r_first = a.g_first = 0, a.r_count = a.g_count = 1;
-    if ((rc = L.go(a)) != LYCHEE_OK) return rc;
-    Ranges b;
-    b.c_first = 0, b.c_count = 1;
-    if (!defer) b.s_first = 0, b.s_count = 1;
-    if ((rc = L.go(b)) != LYCHEE_OK) return rc;
-    if (defer) {
-        pd.active = true;
-        pd.desc = d;
-        pd.desc.q = d.q_keep;  // the caller's q may hold the next layer's queries by then
-        pd.desc.q_keep = nullptr;
-        pd.shape = *shape;
-        pd.lengths = lengths;
-        pd.workspace = workspace;
-        pd.slot = slot;
-    }
+    // one launch: this layer, with the pending select among its front units
+    if ((rc = layer_launch(ctx, *shape, w, lengths, &d, pd.active ? &pd.desc : nullptr, stream)) != LYCHEE_OK) return rc;
+    pd.active = true;
+    pd.desc = d;
+    if (d.q_keep != nullptr) pd.desc.q = d.q_keep;  // the caller's q may hold the next layer's queries by then
+    pd.desc.q_keep = nullptr;
+    pd.shape = *shape;
+    pd.lengths = lengths;
+    pd.workspace = workspace;
+    pd.slot = slot;
+    pd.bank = bank;
     return LYCHEE_OK;
 }
 
@@ -768,13 +831,7 @@ int lychee_select_flush(lychee_ctx *ctx, void *hip_stream)
     if (rc != LYCHEE_OK) return rc;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Workspace w = carve(pd.shape, 2);
-    std::vector<LayerDesc> descs(1, pd.desc);
-    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-    if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, pd.shape, w, pd.lengths, table, descs.data(), stream};
-    Ranges sl;
-    sl.s_first = 0, sl.s_count = 1;
-    if ((rc = L.go(sl)) != LYCHEE_OK) return rc;
+    if ((rc = layer_launch(ctx, pd.shape, w, pd.lengths, nullptr, &pd.desc, stream)) != LYCHEE_OK) return rc;
     pd.active = false;
     return LYCHEE_OK;
 }
@@ -794,8 +851,7 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Workspace w = carve(*shape, 1);
-    std::vector<LayerDesc> descs(1);
-    LayerDesc &d = descs[0];
+    LayerDesc d;
     memset(&d, 0, sizeof d);
     d.q = static_cast<const uint16_t *>(q);
     d.k_cache = static_cast<const uint16_t *>(k_cache);
@@ -803,10 +859,8 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
     d.out = static_cast<uint16_t *>(out);
     set_groups(d, *shape, nullptr);
     set_scratch(d, w, static_cast<char *>(workspace), 0);
-    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-    if (table == nullptr) return LYCHEE_EHIP;
-    const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    return run_layer(L, 0, false, false);
+    if ((rc = check_layer_space(*shape, d)) != LYCHEE_OK) return rc;
+    return layer_launch(ctx, *shape, w, lengths, &d, nullptr, stream);
 }
 
 int lychee_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
@@ -893,14 +947,15 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
         set_groups(d, *shape, nullptr);
         set_scratch(d, w, static_cast<char *>(workspace), l);
     }
+    if (ctx->step_mode != LYCHEE_STEP_PHASED || n_layers == 1 || (int64_t)n_layers * shape->batch > kMaxItems) {
+        if ((rc = check_layer_space(*shape, descs[0])) != LYCHEE_OK) return rc;
+        for (int l = 0; l < n_layers; ++l)
+            if ((rc = layer_launch(ctx, *shape, w, lengths, &descs[l], nullptr, stream)) != LYCHEE_OK) return rc;
+        return LYCHEE_OK;
+    }
     const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
     if (table == nullptr) return LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
-    if (ctx->step_mode != LYCHEE_STEP_PHASED || n_layers == 1 || (int64_t)n_layers * shape->batch > kMaxItems) {
-        for (int l = 0; l < n_layers; ++l)
-            if ((rc = run_layer(L, l, false, false)) != LYCHEE_OK) return rc;
-        return LYCHEE_OK;
-    }
     Ranges r;
     r.r_first = 0, r.r_count = n_layers;
     if ((rc = L.go(r)) != LYCHEE_OK) return rc;
@@ -957,6 +1012,7 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
         ctx->g_block_rows = fresh.g_block_rows;
         ctx->tail_permille = fresh.tail_permille;
         ctx->select_margin = fresh.select_margin;
+        ctx->select_lead = fresh.select_lead;
         return LYCHEE_OK;
     }
     case LYCHEE_OPT_WG_PER_CU:
@@ -978,6 +1034,10 @@ int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value)
     case LYCHEE_OPT_SELECT_MARGIN:
         if (value < -10000 || value > 100000) return LYCHEE_EINVAL;
         ctx->select_margin = value;
+        return LYCHEE_OK;
+    case LYCHEE_OPT_SELECT_LEAD:
+        if (value < 0 || value > (1 << 24)) return LYCHEE_EINVAL;
+        ctx->select_lead = value;
         return LYCHEE_OK;
     case LYCHEE_OPT_GATHER_BLOCK:
         if (value < 16 || value > 128 || value % 16) return LYCHEE_EINVAL;

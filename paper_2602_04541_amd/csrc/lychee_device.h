@@ -13,9 +13,15 @@ struct SharedAttn {
     float red_o[kWaves * kMaxGroup * kHeadDim];
     float red_ml[kWaves * kMaxGroup * 2];
     float pool_ml[kWaves * 2];
-    unsigned long long cand[kWaves][kCandBuf];  // per wavefront: candidates not yet flushed
+    union {
+        unsigned long long cand[kWaves][kCandBuf];  // per wavefront: candidates not yet flushed
+        uint32_t keys[kKeyBuf];                     // or: the ordered keys of the piece's last kKeyBuf rows,
+    };                                              //     filtered once the row's threshold is known
     int32_t cand_left[kWaves];                  // what each wavefront still holds when a piece ends
     int32_t cand_base;                          // where the workgroup's last candidates go
+    uint32_t late_thr;                          // the row's threshold, once a piece has fetched it
+    int32_t late_have;
+    uint32_t scan[kWaves + 1];                  // block_scan scratch of the key filter
 };
 struct SharedSelect {
     uint32_t hist[4096];                   // radix histograms; position bitmap of the ordered write
@@ -95,6 +101,18 @@ __device__ __forceinline__ void gstore(T *p, T v)
 {
     *(LYCHEE_GLOBAL T *)p = v;
 }
+// Write-through store: the value goes through the XCD's L2 to device memory, and the store counts
+// as outstanding (vmcnt) until it is there.  A workgroup on another XCD that learns, through an
+// agent-scope atomic issued after wait_stores(), that the data exists reads it after an acquire
+// fence.  This is what lets a workgroup hand a partial result to another one in the same launch
+// without the agent-scope release fence, whose write-back of the whole L2 costs tens of
+// microseconds when hundreds of workgroups execute it.
+__device__ __forceinline__ void gstore_through(float *p, float v)
+{
+    __hip_atomic_store((LYCHEE_GLOBAL float *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float4 gload_f4(const float *p)
 {
     const f32x4_t r = *(const LYCHEE_GLOBAL f32x4_t *)p;
@@ -140,6 +158,50 @@ __device__ __forceinline__ int budget_of(const Common &c, int L)
         n = r < n ? (int)r : n;
     }
     return n;
+}
+
+// Fields of a layer descriptor staged in LDS as 32-bit words.  The values are the same in
+// every lane; reading them back through readfirstlane tells the compiler so (scalar registers,
+// scalar address arithmetic in the streaming loop).
+constexpr int kDescWords = (int)(sizeof(LayerDesc) / 4);
+static_assert(sizeof(LayerDesc) % 4 == 0 && kDescWords <= kThreads, "one word per thread");
+
+__device__ __forceinline__ uint32_t desc_u32(const uint32_t *dw, size_t off)
+{
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)dw[off / 4]);
+}
+__device__ __forceinline__ uint32_t desc_u8(const uint32_t *dw, size_t off)
+{
+    return (desc_u32(dw, off & ~(size_t)3) >> (8 * (off & 3))) & 0xFFu;
+}
+template <typename T>
+__device__ __forceinline__ T *desc_ptr(const uint32_t *dw, size_t off)
+{
+    const uint64_t lo = desc_u32(dw, off), hi = desc_u32(dw, off + 4);
+    return reinterpret_cast<T *>(lo | (hi << 32));
+}
+
+// Largest i in [0, n) with pre[i] <= x, for a non-decreasing pre[0..n] with pre[0] <= x < pre[n].
+__device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pre[mid] <= x) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Rows a sparse KV head gathers for a sequence of L cache rows (set entries that are -1 or
+// name rows past L are skipped one by one), and how many of them make one pooled block.
+__device__ __forceinline__ int gather_rows(const Common &c, int L)
+{
+    const int units = units_of(c, L);
+    return (c.k < units ? c.k : units) << c.block_shift;
+}
+__device__ __forceinline__ int gather_block(const Common &c)
+{
+    return c.block_shift ? (1 << c.block_shift) : c.g_block_rows;  // whole blocks stream like R rows
 }
 
 // Inclusive prefix sum over the 256 threads of the workgroup; `total` = sum of all.

@@ -24,6 +24,7 @@ constexpr int kSampleTilesMin = 128;     // the threshold sample: 128 to 256 til
 constexpr int kSampleTilesMax = 256;
 constexpr int kDirectLen = 4096;         // sequences this short are ranked without a threshold
 constexpr int kCandBuf = 256;            // candidates a wavefront collects in LDS between flushes
+constexpr int kKeyBuf = 4096;            // rows whose keys a piece buffers in LDS when its threshold comes late
 constexpr float kMinusBig = -1.0e30f;    // "no score yet" sentinel of the running maximum
 
 constexpr int kMaxLayers = 128;          // layers one launch can cover
@@ -107,6 +108,38 @@ struct LaunchPlan {
     // arguments instead of all of them loading the same table lines
     uint8_t n_rseg[kMaxLayers], n_gseg[kMaxLayers], keeps[kMaxLayers];
 };
+
+// Kernel argument of lychee_layer_kernel, the single launch of one layer call.  It carries, side by
+// side and with hand-offs inside the launch, everything the layer's output needs and the select
+// that the previous layer call left pending:
+//   front units   the pending select (and set copies) of `prev`, the selection thresholds of `cur`;
+//                 they run first, on the first n_front workgroups, and wait for nothing
+//   R pieces      cur's retrieval streaming; a piece polls for its row's threshold when it ends
+//   G pieces      cur's sparse gathers; a piece of a KV head in gate_mask polls until the front
+//                 unit that writes that head's inherited set has published it
+//   combine       the workgroup that writes the last partial of a (sequence, KV head, kind)
+//                 segment merges the segment's partials into `out`
+// Flags carry the launch's generation, a counter in device memory that the last workgroup to
+// finish advances: a flag of an earlier launch, or of an earlier replay of a captured launch,
+// never matches.
+struct LayerLaunch {
+    Common c;
+    LayerDesc cur;         // the layer whose rows are streamed and gathered (has_cur)
+    LayerDesc prev;        // the layer whose select is pending (has_prev)
+    int32_t has_cur, has_prev;
+    int32_t n_front;       // workgroups that run front units
+    int32_t lead_blocks;   // blocks of 64 rows the device streams while a select runs: how much
+                           // later than the streaming the gated gathers can start
+    uint64_t gate_mask;    // bit g: KV head g's inherited set is written by this launch's front units
+    uint32_t *gen;         // the generation (read at the start, advanced at the end)
+    uint32_t *exit_count;  // workgroups that have finished
+    unsigned long long *thr_flags;  // [B * n_rgroups] {generation, threshold} of cur's score rows
+    uint32_t *set_flags;   // [B * H_kv] generation once the set of (sequence, KV head) is final
+    uint32_t *seg_count;   // [B * H_kv * 2] partials written so far of each R / G segment (zero between launches)
+};
+// 0: no selection anywhere in the launch (the dense baseline); 1: the hybrid build; 2: the one
+// that also knows the probability rules
+hipError_t launch_layer(const LayerLaunch &plan, int build, hipStream_t stream);
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream);
 hipError_t launch_validate_idx(const int32_t *idx, const int32_t *lengths, int32_t batch,

@@ -1,0 +1,346 @@
+// The single launch of one layer call (Alg. 1, one pass of the layer loop's per-head loop).
+//
+// A model that decodes layer after layer computes the next layer's query from this layer's
+// output, so the layer's work cannot be pooled with other layers', and at 128K a layer is only
+// about 30 microseconds of HBM time: every dependent launch (each costs a few microseconds of gap,
+// a prologue and a tail) shows.  This kernel therefore runs the whole layer in ONE launch and
+// hands results from workgroup to workgroup inside it:
+//
+//   front units  (the first n_front workgroups, before anything else; they wait for nothing)
+//       S  the select of the PREVIOUS layer call (Eq. 2), left pending by that call: its set is
+//          read again only by this layer's sparse heads (Sec. 3.1), so it runs beside this
+//          layer's streaming instead of after the previous layer's; copies of the sets of KV
+//          heads that keep theirs
+//       T  the selection thresholds of this layer (a sample of each score row)
+//   R pieces     Eq. 1 / o = A V over this layer's cache rows.  The threshold of a piece's score
+//                row is computed by a T unit of the same launch, so the piece keeps its rows'
+//                keys in LDS and filters them when it ends (by then the T unit, about half as
+//                long as a piece, has published the threshold; a piece polls for it if not)
+//   G pieces     Eq. 3 over the inherited set, on the last workgroups of the grid; a piece polls
+//                until the front unit that writes its KV head's set has published it
+//   combine      every piece writes its partial through to device memory and counts itself in;
+//                the piece that completes a segment merges the segment's partials into `out`
+//
+// Waiting is safe because every wait is for a front unit, front units never wait, and they run
+// on the lowest workgroup indices, which are dispatched first; waits are bounded all the same.
+// Partials cross from one XCD's L2 to another's without the agent-scope release fence (its
+// write-back of the whole L2, executed by every workgroup, costs more than the layer): they are
+// written with write-through stores, the writer waits until those have completed before it
+// counts itself in, and the merging workgroup takes an acquire fence.  The sets, written by a
+// handful of front units, are published with the ordinary release fence.
+#include "lychee_internal.h"
+#include "lychee_device.h"
+#include "lychee_stream.h"
+#include "lychee_select.h"
+
+namespace lychee {
+namespace {
+
+struct SharedLayer {
+    int32_t pre[kMaxBatch + 1];  // first block of every sequence in this workgroup's row space
+    int32_t len[kMaxBatch];
+    uint32_t scan[kWaves + 1];
+    unsigned long long scan64[kWaves + 1];
+    float fred[kWaves + 1];
+    uint32_t gen;
+    int32_t flag;
+};
+union SharedRole {
+    SharedAttn attn;  // a piece
+    SharedUnit unit;  // a front unit, or the combine that follows a piece
+};
+
+__device__ __forceinline__ uint32_t load_agent(const uint32_t *p)
+{
+    return __hip_atomic_load((const LYCHEE_GLOBAL uint32_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store((LYCHEE_GLOBAL uint32_t *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A front unit has written the set of (b, g): make it visible to the whole device, then say so.
+__device__ __forceinline__ void publish_set(uint32_t *flag, uint32_t gen)
+{
+    wait_stores();  // each wavefront: its stores have left the CU
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        store_agent(flag, gen);
+    }
+}
+
+// Before a gather piece reads a set that a front unit of this launch writes.
+__device__ __forceinline__ void await_set(const uint32_t *flag, uint32_t gen, uint32_t *timeouts, SharedLayer &pool)
+{
+    if (threadIdx.x == 0) {
+        int spin = 0;
+        for (; spin < kSpinMax; ++spin) {
+            if (load_agent(flag) == gen) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (spin == kSpinMax) atomicAdd(timeouts, 1u);  // (the piece then reads whatever the array holds; entries are range-checked)
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+template <bool COLLECT, int SELECTS>
+__global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLaunch P)
+{
+    __shared__ SharedRole sh;
+    __shared__ SharedLayer pool;
+    // Both layer descriptors are staged in LDS, one word per thread, and read from there.  (The
+    // kernel argument is never indexed with a run-time value: for `idx_src[g]` the compiler
+    // emitted a scalar load whose base register held `argument + g` and whose offset register
+    // held `7 g` - only their sum is a multiple of 4 -, and the scalar memory unit drops the
+    // low bits of each, so that the load returned the halves of two neighbouring pointers.)
+    __shared__ __align__(16) uint32_t desc_cur[kDescWords], desc_prev[kDescWords];
+    const Common &c = P.c;
+    const int w = blockIdx.x;
+    const int W = c.n_wg;
+    const int tid = threadIdx.x;
+
+    if (tid == 0) pool.gen = load_agent(P.gen);
+    if (tid < c.batch) pool.len[tid] = clamp_len(c.lengths[tid], c.max_len);
+    if (tid < kDescWords) {
+        desc_cur[tid] = reinterpret_cast<const uint32_t *>(&P.cur)[tid];
+        desc_prev[tid] = reinterpret_cast<const uint32_t *>(&P.prev)[tid];
+    }
+    __syncthreads();
+    const LayerDesc &cur = *reinterpret_cast<const LayerDesc *>(desc_cur);
+    const LayerDesc &prev = *reinterpret_cast<const LayerDesc *>(desc_prev);
+    const uint32_t *dw = desc_cur;
+    const uint32_t gen = pool.gen;
+    uint32_t *timeouts = c.stats + 2;
+
+    // ------------------------------------------------------------------ front units
+    if (w < P.n_front) {
+        const int n_rp = P.has_prev ? prev.n_rgroups : 0;
+        const int nS = SELECTS ? c.batch * n_rp : 0;
+        const int nC = P.has_prev && prev.copy_keep ? c.batch * (c.n_kv_heads - n_rp) : 0;
+        const int nT = COLLECT && P.has_cur && cur.emit_sel && c.block_shift == 0 ? c.batch * cur.n_rgroups : 0;
+        for (int j = w; j < nS + nC + nT; j += P.n_front) {
+            if (j < nS) {
+                const int b = j / n_rp;
+                const int g = prev.rgroup[j % n_rp];
+                if (SELECTS == 1) select_unit<false>(c, prev, b, g, sh.unit.sel, pool);
+                if (SELECTS == 2) select_unit<true>(c, prev, b, g, sh.unit.sel, pool);
+                publish_set(P.set_flags + b * c.n_kv_heads + g, gen);
+            } else if (j < nS + nC) {
+                const int n_keep = c.n_kv_heads - n_rp;
+                const int u = j - nS;
+                const int b = u / n_keep;
+                int want = u % n_keep, g = 0;
+                for (int gg = 0; gg < c.n_kv_heads; ++gg)
+                    if (prev.rindex[gg] == 0xFF && want-- == 0) g = gg;
+                copy_set_unit(c, prev, b, g);
+                publish_set(P.set_flags + b * c.n_kv_heads + g, gen);
+            } else {
+                const int u = j - nS - nC;
+                const int n_rc = cur.n_rgroups;
+                const int b = u / n_rc, rgi = u % n_rc;
+                unsigned long long *flag = P.thr_flags + ((int64_t)b * n_rc + rgi);
+                switch (__builtin_popcount(cur.rmask[cur.rgroup[rgi]] & ((1u << c.group) - 1u))) {
+                case 1: threshold_unit<1>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
+                case 2: threshold_unit<2>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
+                case 3: threshold_unit<3>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
+                default: threshold_unit<4>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // ------------------------------------------------------------------ the two row spaces
+    // Per sequence: blocks of 64 cache rows per retrieval KV head, blocks of gathered rows per
+    // sparse KV head.  The workgroups after the front ones are split between the two in
+    // proportion to the blocks; when the gathers wait for a select, the streaming is
+    // lead_blocks ahead by the time they start, and they get workgroups for what is then left.
+    const int n_rseg = P.has_cur ? (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) : 0;
+    const int n_gseg = P.has_cur ? (int)desc_u32(dw, offsetof(LayerDesc, n_sgroups)) : 0;
+    uint32_t nb_r = 0, nb_g = 0;
+    if (tid < c.batch) {
+        const int L = pool.len[tid];
+        nb_r = n_rseg ? (uint32_t)((L + kBlockRows - 1) / kBlockRows) : 0u;
+        nb_g = n_gseg ? (uint32_t)((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c)) : 0u;
+    }
+    unsigned long long tot64;
+    (void)block_scan64((unsigned long long)nb_r | ((unsigned long long)nb_g << 32), pool.scan64, tot64);
+    const int64_t TR = (int64_t)(uint32_t)tot64 * n_rseg;
+    const int64_t TG = (int64_t)(uint32_t)(tot64 >> 32) * n_gseg;
+    const int first = W >= 8 ? P.n_front : 0;  // tiny grids: the front workgroups also take pieces
+    const int Wn = W - first;
+    int W_R = 0, W_G = 0;
+    if (Wn < 2) {  // a single workgroup does both kinds, one after the other
+        W_R = TR > 0;
+        W_G = TG > 0;
+    } else if (TR > 0 && TG > 0) {
+        const int64_t lead = P.has_prev && P.gate_mask != 0 ? P.lead_blocks : 0;
+        int64_t rest = TR + TG - lead;
+        rest = rest < TG ? TG : rest;
+        W_G = (int)((Wn * TG + rest - 1) / rest);
+        W_G = W_G < 1 ? 1 : (W_G > Wn - 1 ? Wn - 1 : W_G);
+        W_R = Wn - W_G;
+    } else if (TG > 0) {
+        W_G = Wn;
+    } else if (TR > 0) {
+        W_R = Wn;
+    }
+    const int g_first = Wn < 2 ? first : first + W_R;
+
+    for (int kind = 0; kind < 2; ++kind) {
+        const bool gather = kind == 1;
+        const int role_first = gather ? g_first : first;
+        const int role_n = gather ? W_G : W_R;
+        const int wl = w - role_first;
+        if (role_n <= 0 || wl < 0 || wl >= role_n) continue;  // (uniform in the workgroup)
+        const int nseg = gather ? n_gseg : n_rseg;
+        const uint32_t nb_mine = gather ? nb_g : nb_r;
+        const int64_t T_real = gather ? TG : TR;
+        const int brows = gather ? gather_block(c) : kBlockRows;
+
+        // Equal contiguous runs of blocks; when the segments are few, every segment is padded to
+        // a whole number of runs, so that each workgroup has exactly one piece (a second piece
+        // costs a second start-up and merge, which a launch this short cannot level out).
+        int share = (int)((T_real + role_n - 1) / role_n);
+        int pad = 0;
+        if (8ll * nseg * c.batch <= role_n) {
+            const int s_last = share + (share / 8 > 1 ? share / 8 : 1);
+            int s = share;
+            for (; s <= s_last; ++s) {
+                uint32_t runs = nseg * ((nb_mine + s - 1) / s), all;
+                (void)block_scan(runs, pool.scan, all);
+                if ((int)all <= role_n) break;
+            }
+            if (s <= s_last) share = s, pad = 1;
+        }
+        {
+            const uint32_t mine = pad ? nseg * ((nb_mine + share - 1) / share) * share : nseg * nb_mine;
+            uint32_t all;
+            const uint32_t incl = block_scan(mine, pool.scan, all);
+            if (tid < c.batch) pool.pre[tid + 1] = (int32_t)incl;
+            if (tid == 0) pool.pre[0] = 0;
+        }
+        __syncthreads();
+        const int T = pool.pre[c.batch];
+
+        int x = wl * share;
+        int x1 = x + share;
+        x1 = x1 < T ? x1 : T;
+        while (x < x1) {
+            const int b = find_item(pool.pre, c.batch, x);
+            const int len_b = pool.len[b];
+            const int seg_rows = gather ? gather_rows(c, len_b) : len_b;
+            const int nb = (seg_rows + brows - 1) / brows;
+            const int nbv = pad ? (nb + share - 1) / share * share : nb;
+            const int xo = x - pool.pre[b];
+            const int gi = xo / nbv;
+            const int blk = xo % nbv;
+            if (blk >= nb) break;  // the run lies in a segment's padding
+            const int seg_start = pool.pre[b] + gi * nbv;
+            int len = x1 - x;
+            len = len < nb - blk ? len : nb - blk;
+            const int r0 = blk * brows;
+            int r1 = (blk + len) * brows;
+            r1 = r1 < seg_rows ? r1 : seg_rows;
+            const int slot = x / share - seg_start / share;
+            const int pieces = (seg_start + nb - 1) / share - seg_start / share + 1;
+            const bool ends = blk + len == nb;
+            const uint32_t gmask = (1u << c.group) - 1u;
+            auto nothing = []() {};
+            const uint16_t *dq = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, q));
+            const uint16_t *dk = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, k_cache));
+            const uint16_t *dv = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, v_cache));
+            float *d_part_o = desc_ptr<float>(dw, offsetof(LayerDesc, part_o));
+            float *d_part_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_ml));
+            int32_t *d_part_count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, part_count));
+            int g;
+            uint32_t hmask;
+            if (!gather) {
+                g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
+                hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
+                Emit em{};
+                if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
+                    const int64_t row = (int64_t)b * n_rseg + gi;
+                    em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
+                    em.count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, list_count)) + row;
+                    em.cap = c.list_row;
+                    em.direct = c.block_shift != 0;
+                    if (c.prob_rule != 0)
+                        em.pool_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_pool)) + row * (2 * (int64_t)c.part_stride);
+                    // rows that need no sample have their threshold at once (what the T unit would say)
+                    const int n = budget_of(c, len_b);
+                    em.thr_known = n == len_b || len_b <= kDirectLen || 2 * (int64_t)n >= len_b;
+                    em.thr = n == len_b && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u;
+                    em.thr_flag = P.thr_flags + row;
+                    em.gen = gen;
+                    em.timeouts = timeouts;
+                }
+                dispatch_piece<false, true>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
+                                            d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sh.attn, nothing);
+            } else {
+                g = (int)desc_u8(dw, offsetof(LayerDesc, sgroup) + gi);
+                hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
+                if ((P.gate_mask >> g) & 1ull) await_set(P.set_flags + b * c.n_kv_heads + g, gen, timeouts, pool);
+                const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)g) +
+                                         ((int64_t)b * c.n_kv_heads + g) * c.k;
+                dispatch_piece<true, true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{}, d_part_o, d_part_ml,
+                                           d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sh.attn, nothing);
+            }
+            // The piece's partials are in device memory.  Count it in; whoever completes the
+            // segment merges its partials (slots 0 .. pieces-1 of every head of the segment).
+            __syncthreads();
+            if (tid == 0) {
+                int last = 1;
+                if (pieces > 1) {
+                    uint32_t *counter = P.seg_count + (((int64_t)b * c.n_kv_heads + g) * 2 + kind);
+                    const uint32_t old = __hip_atomic_fetch_add((LYCHEE_GLOBAL uint32_t *)counter, 1u, __ATOMIC_RELAXED,
+                                                                __HIP_MEMORY_SCOPE_AGENT);
+                    last = old == (uint32_t)pieces - 1u;
+                    if (last) store_agent(counter, 0u);  // as every launch finds it
+                }
+                pool.flag = last;
+            }
+            __syncthreads();
+            if (pool.flag) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                uint32_t mk = hmask;
+                while (mk != 0) {
+                    const int bit = __builtin_ctz(mk);
+                    mk &= mk - 1;
+                    combine_unit(c, cur, b * c.n_q_heads + g * c.group + bit, sh.unit.comb, pool, pieces);
+                }
+            }
+            __syncthreads();
+            x += len;
+        }
+    }
+
+    // ------------------------------------------------------------------ the generation moves on
+    if (tid == 0) {
+        const uint32_t old = __hip_atomic_fetch_add((LYCHEE_GLOBAL uint32_t *)P.exit_count, 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+        if (old == (uint32_t)W - 1u) {
+            store_agent(P.exit_count, 0u);
+            store_agent(P.gen, gen + 1u);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_layer(const LayerLaunch &plan, int build, hipStream_t stream)
+{
+    if (plan.c.n_wg < 1 || plan.c.n_wg > kMaxWg || plan.n_front > plan.c.n_wg) return hipErrorInvalidValue;
+    const dim3 grid(plan.c.n_wg), block(kThreads);
+    if (build == 0)
+        hipLaunchKernelGGL((lychee_layer_kernel<false, 0>), grid, block, 0, stream, plan);
+    else if (build == 1)
+        hipLaunchKernelGGL((lychee_layer_kernel<true, 1>), grid, block, 0, stream, plan);
+    else
+        hipLaunchKernelGGL((lychee_layer_kernel<true, 2>), grid, block, 0, stream, plan);
+    return hipGetLastError();
+}
+
+}  // namespace lychee

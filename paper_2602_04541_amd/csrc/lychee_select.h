@@ -10,10 +10,12 @@ namespace {
 // ------------------------------------------------------------------------------ C
 // out = (sum_s w_s o_s) / (sum_s w_s l_s),  w_s = 2^((m_s - M) log2(e)/sqrt(d)),  M = max_s m_s,
 // over the head's partial slots in ascending order (a fixed summation tree).
+// `known_count` >= 0: the number of partial slots, known to the caller; else it is read from part_count.
+template <typename Pool>
 __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p, int bh, SharedCombine &sh,
-                                             SharedPool &pool)
+                                             Pool &pool, int known_count = -1)
 {
-    int count = gload(p.part_count + bh);
+    int count = known_count >= 0 ? known_count : gload(p.part_count + bh);
     count = count < 0 ? 0 : (count > c.part_stride ? c.part_stride : count);
     const float *ml = p.part_ml + (int64_t)bh * c.part_stride * 2;
     const float *po = p.part_o + (int64_t)bh * c.part_stride * kHeadDim;
@@ -138,9 +140,14 @@ __device__ __forceinline__ float tile_pooled_score(const uint4 (&kr)[4], const u
 // that reach it are then very likely at least n and a few thousand more at most.  Whatever the sample yields, the select unit
 // checks the candidate count and ranks the whole row itself when the list cannot be used.
 // The sample is one row at a hashed offset inside each of 2048 to 4096 equal strata.
-template <int NH>
+// `publish` != nullptr (launches whose streaming runs beside this unit): the threshold goes, with
+// the launch's generation `gen` in the upper half, into *publish by one 64-bit atomic store, which
+// the row's pieces poll; the candidate counter is not touched (it is zero between uses, and the
+// pieces may already be counting).
+template <int NH, typename Pool>
 __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc &p, int b, int rgi,
-                                               SharedSelect &sh, SharedPool &pool)
+                                               SharedSelect &sh, Pool &pool, unsigned long long *publish = nullptr,
+                                               uint32_t gen = 0)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -149,7 +156,15 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     const int L = pool.len[b];  // staged by the kernel, clamped
     const int n = budget_of(c, L);
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
-    if (threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
+    auto emit = [&](uint32_t key) {
+        if (threadIdx.x != 0) return;
+        if (publish != nullptr)
+            __hip_atomic_store((LYCHEE_GLOBAL unsigned long long *)publish, ((unsigned long long)gen << 32) | key,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else
+            gstore(p.thr + row, key);
+    };
+    if (publish == nullptr && threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
     if (p.q_keep != nullptr && (int)threadIdx.x < c.group * (kHeadDim / 8)) {
         // the group's query rows (consecutive heads, 16 chunks of 16 bytes each)
         const int64_t at = ((int64_t)b * c.n_q_heads + p.rgroup[rgi] * c.group) * kHeadDim + threadIdx.x * 8;
@@ -158,7 +173,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
         // everything is selected anyway (no candidates wanted), or every row is a candidate
         // (a probability rule may keep fewer than everything: it still needs the candidates)
-        if (threadIdx.x == 0) gstore(p.thr + row, n == L && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u);
+        emit(n == L && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u);
         return;
     }
     int n_tiles = L / 1024;
@@ -222,7 +237,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
         find_digit<1024>(sh.hist, rest1, sh.found, pool.scan, d2, rest2);
         t_key = (d1 << 20) | (d2 << 10);
     }
-    if (threadIdx.x == 0) gstore(p.thr + row, t_key);
+    emit(t_key);
     TRACE(7);
 }
 
@@ -332,9 +347,9 @@ struct RowEntries {           // every row of the sequence, from its recomputed 
 // The `need`-th largest of the 32-bit values val(key, pos) over the entries that pass
 // `among`, by radix select (12 + 10 + 10 bits); `rest` = how many entries equal to the
 // result are among the `need` largest.
-template <typename Entries, typename Val, typename Among>
+template <typename Entries, typename Val, typename Among, typename Pool>
 __device__ __forceinline__ uint32_t radix_select(const Entries &E, uint32_t need, Val val, Among among,
-                                                 uint32_t &rest, SharedSelect &sh, SharedPool &pool)
+                                                 uint32_t &rest, SharedSelect &sh, Pool &pool)
 {
     uint32_t prefix = 0, prefix_mask = 0;
 #pragma unroll
@@ -369,9 +384,9 @@ __device__ __forceinline__ uint32_t radix_select(const Entries &E, uint32_t need
 // more than r_eq entries equal T, a second radix select finds the r_eq-th lowest position
 // among them; the chosen positions are then marked in an LDS bitmap, 131072 positions at a
 // time, and read back in order.
-template <typename Entries>
+template <typename Entries, typename Pool>
 __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int32_t *dst, SharedSelect &sh,
-                                            SharedPool &pool)
+                                            Pool &pool)
 {
     uint32_t r_eq;
     const uint32_t T = radix_select(
@@ -468,9 +483,9 @@ __device__ __forceinline__ unsigned long long mass_of(uint32_t key, float lse)
 // In a histogram of probability mass per digit, finds the highest digit d at which the mass
 // of the digits >= d reaches `need`; returns d and what is still needed inside d, or digit
 // 0xFFFFFFFF when all the mass together does not reach it.
-template <int kBins>
+template <int kBins, typename Pool>
 __device__ __forceinline__ void find_digit_mass(const unsigned long long *hist, unsigned long long need,
-                                                SharedPool &pool, uint32_t &digit, unsigned long long &rest)
+                                                Pool &pool, uint32_t &digit, unsigned long long &rest)
 {
     constexpr int per = kBins / kThreads;
     unsigned long long mine[per], sum = 0;
@@ -506,9 +521,9 @@ __device__ __forceinline__ void find_digit_mass(const unsigned long long *hist, 
 // have the same mass, so a division says how many of them are needed).  `lse` is the
 // log-sum-exp of the pooled logits of the whole sequence.  The entries hold at least the n best
 // positions, and a rule that would go beyond them is capped at n anyway.
-template <typename Entries>
+template <typename Entries, typename Pool>
 __device__ __forceinline__ int rule_keeps(const Common &c, const Entries &E, int n, float lse, SharedSelect &sh,
-                                          SharedPool &pool)
+                                          Pool &pool)
 {
     uint32_t want;
     if (c.prob_rule == 1) {
@@ -538,9 +553,9 @@ __device__ __forceinline__ int rule_keeps(const Common &c, const Entries &E, int
             uint32_t digit;
             unsigned long long left;
             if (pass == 0)
-                find_digit_mass<4096>(mh, need, pool, digit, left);
+                find_digit_mass<4096, Pool>(mh, need, pool, digit, left);
             else
-                find_digit_mass<1024>(mh, need, pool, digit, left);
+                find_digit_mass<1024, Pool>(mh, need, pool, digit, left);
             if (digit == 0xFFFFFFFFu) {  // (uniform) not even all entries reach the mass: the cap decides
                 reached = false;
                 break;
@@ -562,8 +577,9 @@ __device__ __forceinline__ int rule_keeps(const Common &c, const Entries &E, int
 }
 
 // Log-sum-exp of the pooled logits of score row `row`: the pieces' states, merged.
+template <typename Pool>
 __device__ __forceinline__ float pooled_lse(const Common &c, const LayerDesc &p, int64_t row, int count,
-                                            SharedPool &pool)
+                                            Pool &pool)
 {
     const float *ml = p.part_pool + row * (2 * (int64_t)c.part_stride);
     float m_loc = kMinusBig;
@@ -589,9 +605,9 @@ __device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &
 // S unit of KV head (b, g), whose group holds a retrieval head: the set the next layer's
 // sparse heads of the group inherit.  PROB: the build that knows the probability rules (their
 // 64-bit mass arithmetic over register-resident entries would cost the plain build registers).
-template <bool PROB>
+template <bool PROB, typename Pool>
 __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p, int b, int g,
-                                            SharedSelect &sh, SharedPool &pool)
+                                            SharedSelect &sh, Pool &pool)
 {
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
@@ -602,12 +618,19 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     const bool by_prob = PROB && c.prob_rule != 0;
     if (n == L && !by_prob) {  // everything is selected
         for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
+        if (threadIdx.x == 0 && c.block_shift == 0 && rgi != 0xFF)
+            gstore(p.list_count + ((int64_t)b * p.n_rgroups + rgi), (int32_t)0);  // (nothing was collected; see below)
         return;
     }
     const int64_t row = (int64_t)b * p.n_rgroups + rgi;
     const unsigned long long *list = p.list + row * (int64_t)c.list_row;
     // block-granular: the streaming left every block's score at its place in the list
     const int total = c.block_shift ? L : gload(p.list_count + row);
+    // The select is the counter's only reader: it leaves it at zero for the next launch that
+    // collects into it (a launch whose streaming runs beside its threshold units has nobody who
+    // could clear it first).  Every thread has read it before any thread gets past the barriers
+    // that follow, so one thread may clear it then.
+    const bool clear_count = c.block_shift == 0;
     TRACE(5);
     float lse = 0.0f;
     if (by_prob) {
@@ -646,6 +669,7 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
         select_from(E, keep, L, dst, sh, pool);
     }
     for (int i = keep + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
+    if (clear_count && threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
 }
 
 

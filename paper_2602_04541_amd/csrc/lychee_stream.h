@@ -110,7 +110,76 @@ struct Emit {
                                // written in place; no threshold, no counter
     float *pool_ml;            // Threshold / Top-p rules: this score row's per-piece (maximum,
                                // sum of exp) of the pooled logits; nullptr otherwise
+    // Launches whose thresholds are computed by units of the same launch (LATE pieces): the
+    // piece keeps its rows' keys in LDS and filters them when it ends; by then the threshold
+    // unit has normally published {generation, threshold} in *thr_flag.  thr_known: `thr` above
+    // is valid without waiting (rows that need no sample).
+    const unsigned long long *thr_flag;
+    uint32_t gen;
+    int32_t thr_known;
+    uint32_t *timeouts;        // counts waits that gave up
 };
+
+constexpr int kSpinMax = 1 << 20;  // polls of a flag before a wait gives up (seconds; never reached in a working launch)
+
+// Waits until the 64-bit word at `flag` carries this launch's generation in its upper half and
+// returns the lower half; `fail` if that does not happen within kSpinMax polls.  The producer
+// is a unit that runs on a workgroup with a lower index, started before this one, and waits for
+// nothing itself.
+__device__ __forceinline__ uint32_t wait_word(const unsigned long long *flag, uint32_t gen, uint32_t fail,
+                                              uint32_t *timeouts)
+{
+    for (int spin = 0; spin < kSpinMax; ++spin) {
+        const unsigned long long v = __hip_atomic_load((const LYCHEE_GLOBAL unsigned long long *)flag,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(v >> 32) == gen) return (uint32_t)v;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    atomicAdd(timeouts, 1u);
+    return fail;
+}
+
+// The threshold of a LATE piece's score row, the same in every thread (one thread polls).
+__device__ __forceinline__ uint32_t late_threshold(const Emit &em, SharedAttn &sh)
+{
+    if (threadIdx.x == 0 && sh.late_have == 0) {
+        // on a time-out nothing is collected; the select then ranks the whole row itself
+        sh.late_thr = wait_word(em.thr_flag, em.gen, 0xFFFFFFFFu, em.timeouts);
+        sh.late_have = 1;
+    }
+    __syncthreads();
+    return sh.late_thr;
+}
+
+// LATE pieces, first half of a filter over the n_rows keys in sh.keys: counts this thread's
+// rows that reach the threshold (`mine`), their rank among the workgroup's (`incl`, inclusive),
+// and has the last thread reserve list space for all of them; the reservation's answer, which
+// takes a microsecond or two, is only needed by late_write.
+__device__ __forceinline__ void late_count(const Emit &em, SharedAttn &sh, int n_rows, uint32_t thr,
+                                           uint32_t &mine, uint32_t &incl, int &base)
+{
+    mine = 0;
+    for (int i = threadIdx.x; i < n_rows; i += kThreads) mine += (uint32_t)(sh.keys[i] >= thr);
+    uint32_t total;
+    incl = block_scan(mine, sh.scan, total);
+    base = 0;
+    if (threadIdx.x == kThreads - 1 && total > 0)
+        base = __hip_atomic_fetch_add((LYCHEE_GLOBAL int32_t *)em.count, (int32_t)total, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+}
+// Second half: sh.cand_base holds the reservation; row i of the window is position first_row + i.
+__device__ __forceinline__ void late_write(const Emit &em, SharedAttn &sh, int first_row, int n_rows, uint32_t thr,
+                                           uint32_t mine, uint32_t incl)
+{
+    int at = sh.cand_base + (int)(incl - mine);
+    for (int i = threadIdx.x; i < n_rows; i += kThreads) {
+        const uint32_t key = sh.keys[i];
+        if (key >= thr) {
+            if (at < em.cap) gstore(em.list + at, (unsigned long long)key | ((unsigned long long)(uint32_t)(first_row + i) << 32));
+            ++at;
+        }
+    }
+}
 
 // Appends a wavefront's n buffered candidates to the row's list.  The counter keeps counting
 // past the capacity, which is how the select unit learns that the list is incomplete.
@@ -138,13 +207,13 @@ __device__ __forceinline__ void flush_candidates(const unsigned long long *buf, 
 // alternate: one tile's loads are in flight while the other is consumed.  After both tiles of
 // a span the wavefront compares its 32 pooled scores with the threshold and puts the rows
 // that reach it into its LDS buffer, which goes to the list in bursts.
-template <int NH, bool GATHER>
+template <int NH, bool GATHER, bool LATE>
 __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kbase,
                                             const uint16_t *vbase, const uint4 (&qf)[NH],
                                             Acc<NH> &acc, int L, int r0, int r1,
                                             const int32_t *idx_s, const Emit &em, float sel_mul,
                                             unsigned long long *cand_buf, int &cand_left,
-                                            float &pool_m, float &pool_l)
+                                            float &pool_m, float &pool_l, SharedAttn &sh)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -262,6 +331,24 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
                 pool_l = pool_l * fast_exp2((pool_m - m_new) * kLog2e) + fast_exp2((score - m_new) * kLog2e);
                 pool_m = m_new;
             }
+            if (LATE) {
+                // the threshold may not exist yet: keep the key; a full window of keys is
+                // filtered here, the piece's last window when the piece ends (run_piece)
+                constexpr int kWindowSpans = kKeyBuf / kSpan;
+                if (ch < 8) sh.keys[(r - r0) & (kKeyBuf - 1)] = key;
+                if (((span + 1) & (kWindowSpans - 1)) == 0 && span + 1 < n_spans) {  // uniform in the workgroup
+                    __syncthreads();
+                    const uint32_t thr = late_threshold(em, sh);
+                    uint32_t mine, incl;
+                    int base;
+                    late_count(em, sh, kKeyBuf, thr, mine, incl, base);
+                    if (threadIdx.x == kThreads - 1) sh.cand_base = base;
+                    __syncthreads();
+                    late_write(em, sh, r0 + (span + 1) * kSpan - kKeyBuf, kKeyBuf, thr, mine, incl);
+                    __syncthreads();
+                }
+                continue;
+            }
             const bool hit = ch < 8 && r < r1 && key >= em.thr;
             const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
             if (hits != 0) {  // wave-uniform
@@ -282,7 +369,10 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
 // One (workgroup, segment) piece: rows/entries [r0, r1) of segment (b, g) for the heads in
 // hmask.  Leaves one un-normalised partial per head in `slot`; the piece that ends the
 // segment also records how many slots the segment has.
-template <int NH, bool GATHER, typename Hook>
+// LATE: the piece runs in a launch that also computes its thresholds and merges its partials
+// (lychee_layer_kernel): keys are filtered at the end of the piece, and the partial is written
+// through to device memory, complete when run_piece returns.
+template <int NH, bool GATHER, bool LATE, typename Hook>
 __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, const uint16_t *k_cache,
                                           const uint16_t *v_cache, const int32_t *idx_src,
                                           const Emit &em, float *part_o, float *part_ml,
@@ -323,6 +413,10 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     const float sel_mul = c.scale / (float)NH;
     float pool_m = kMinusBig, pool_l = 0.0f;  // per lane: log-sum-exp state of the pooled logits
     int cand_left = 0;                        // candidates still in this wavefront's LDS buffer
+    if (LATE && !GATHER && threadIdx.x == 0) {  // (barriers lie between this and the first use)
+        sh.late_have = em.thr_known;
+        sh.late_thr = em.thr;
+    }
 
     if (GATHER) {
         // rows r0 .. r1-1 of the gathered sequence are row (r mod 2^shift) of set entry r >> shift
@@ -334,17 +428,17 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             __syncthreads();  // the previous chunk's readers are done
             for (int i = threadIdx.x; i < n_entries; i += kThreads) sh.idx_s[i] = gload(idx_src + (e0 >> shift) + i);
             __syncthreads();
-            stream_rows<NH, true>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr, cand_left, pool_m, pool_l);
+            stream_rows<NH, true, LATE>(c, kbase, vbase, qf, acc, L, e0, e1, sh.idx_s, em, 0.0f, nullptr, cand_left, pool_m, pool_l, sh);
         }
     } else {
-        stream_rows<NH, false>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave], cand_left, pool_m, pool_l);
+        stream_rows<NH, false, LATE>(c, kbase, vbase, qf, acc, L, r0, r1, nullptr, em, sel_mul, sh.cand[wave], cand_left, pool_m, pool_l, sh);
     }
     const bool collects = !GATHER && em.list != nullptr && em.direct == 0;  // the same in every wavefront
 
     TRACE(7);
     TRACE_LAP(2);  // streaming
     at_rows_done();  // what the caller wants in flight while the partial is merged and written
-    if (collects && lane == 0) sh.cand_left[wave] = cand_left;
+    if (!LATE && collects && lane == 0) sh.cand_left[wave] = cand_left;
     // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).
     const float c_log2e = c.scale_log2e;
 #pragma unroll
@@ -379,7 +473,14 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     // Merge the 4 wavefronts through LDS and write the piece's partial.
     __syncthreads();  // red_o / idx_s readers of the previous piece are done
     int cand_base = 0;
-    if (collects && threadIdx.x == kThreads - 1) {
+    uint32_t late_thr = 0, late_mine = 0, late_incl = 0;
+    // the piece's last window of keys: rows late_first .. r1 - 1
+    const int late_first = r0 + (r1 - r0 > 0 ? (r1 - r0 - 1) / kKeyBuf * kKeyBuf : 0);
+    if (LATE && collects) {
+        late_thr = late_threshold(em, sh);
+        late_count(em, sh, r1 - late_first, late_thr, late_mine, late_incl, cand_base);
+    }
+    if (!LATE && collects && threadIdx.x == kThreads - 1) {
         // room for the workgroup's last candidates, asked for by a thread that writes no
         // partial, as early as every wavefront's count is known: the answer is on its way
         // while the others merge
@@ -423,12 +524,20 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
             }
             const int64_t bh = (int64_t)b * c.n_q_heads + heads[h];
             const int64_t prow = bh * c.part_stride + slot;
-            gstore(part_o + prow * kHeadDim + threadIdx.x, o);
-            if (threadIdx.x == 0) {
-                gstore(part_ml + prow * 2 + 0, M);
-                gstore(part_ml + prow * 2 + 1, l);
-                if (ends_segment) gstore(part_count + bh, (int32_t)(slot + 1));
+            if (LATE) {
+                gstore_through(part_o + prow * kHeadDim + threadIdx.x, o);
+                if (threadIdx.x == 0) {
+                    gstore_through(part_ml + prow * 2 + 0, M);
+                    gstore_through(part_ml + prow * 2 + 1, l);
+                }
+            } else {
+                gstore(part_o + prow * kHeadDim + threadIdx.x, o);
+                if (threadIdx.x == 0) {
+                    gstore(part_ml + prow * 2 + 0, M);
+                    gstore(part_ml + prow * 2 + 1, l);
+                }
             }
+            if (threadIdx.x == 0 && ends_segment) gstore(part_count + bh, (int32_t)(slot + 1));
         }
     }
     if (pooled_lse && threadIdx.x == 0) {  // the piece's pooled log-sum-exp state, same slot
@@ -440,7 +549,10 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         gstore(em.pool_ml + 2 * slot, M);
         gstore(em.pool_ml + 2 * slot + 1, l);
     }
-    if (collects) {
+    if (LATE && collects) {
+        __syncthreads();
+        late_write(em, sh, late_first, r1 - late_first, late_thr, late_mine, late_incl);
+    } else if (collects) {
         __syncthreads();
         int base = sh.cand_base;
         for (int w = 0; w < wave; ++w) base += sh.cand_left[w];
@@ -448,9 +560,10 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
         for (int i = lane; i < cand_left; i += 64)
             if (base + i < em.cap) gstore(em.list + base + i, buf[i]);
     }
+    if (LATE) wait_stores();  // the partial has reached device memory
 }
 
-template <bool GATHER, typename Hook>
+template <bool GATHER, bool LATE, typename Hook>
 __device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const uint16_t *q,
                                                const uint16_t *k_cache, const uint16_t *v_cache,
                                                const int32_t *idx_src, const Emit &em, float *part_o,
@@ -459,10 +572,10 @@ __device__ __forceinline__ void dispatch_piece(int nh, const Common &c, const ui
                                                bool ends_segment, SharedAttn &sh, Hook &at_rows_done)
 {
     switch (nh) {
-    case 1: run_piece<1, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
-    case 2: run_piece<2, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
-    case 3: run_piece<3, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
-    default: run_piece<4, GATHER>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    case 1: run_piece<1, GATHER, LATE>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    case 2: run_piece<2, GATHER, LATE>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    case 3: run_piece<3, GATHER, LATE>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
+    default: run_piece<4, GATHER, LATE>(c, q, k_cache, v_cache, idx_src, em, part_o, part_ml, part_count, b, g, hmask, L, r0, r1, slot, ends_segment, sh, at_rows_done); break;
     }
 }
 

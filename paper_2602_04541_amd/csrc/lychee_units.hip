@@ -53,38 +53,6 @@ namespace lychee {
 namespace {
 
 // ------------------------------------------------------------------------------ the kernels
-// Fields of a layer descriptor staged in LDS as 32-bit words.  The values are the same in
-// every lane; reading them back through readfirstlane tells the compiler so (scalar registers,
-// scalar address arithmetic in the streaming loop).
-constexpr int kDescWords = (int)(sizeof(LayerDesc) / 4);
-static_assert(sizeof(LayerDesc) % 4 == 0 && kDescWords <= kThreads, "one word per thread");
-
-__device__ __forceinline__ uint32_t desc_u32(const uint32_t *dw, size_t off)
-{
-    return (uint32_t)__builtin_amdgcn_readfirstlane((int)dw[off / 4]);
-}
-__device__ __forceinline__ uint32_t desc_u8(const uint32_t *dw, size_t off)
-{
-    return (desc_u32(dw, off & ~(size_t)3) >> (8 * (off & 3))) & 0xFFu;
-}
-template <typename T>
-__device__ __forceinline__ T *desc_ptr(const uint32_t *dw, size_t off)
-{
-    const uint64_t lo = desc_u32(dw, off), hi = desc_u32(dw, off + 4);
-    return reinterpret_cast<T *>(lo | (hi << 32));
-}
-
-// Largest i in [0, n) with pre[i] <= x, for a non-decreasing pre[0..n] with pre[0] <= x < pre[n].
-__device__ __forceinline__ int find_item(const int32_t *pre, int n, int x)
-{
-    int lo = 0, hi = n - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (pre[mid] <= x) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
 // Launches that carry T, S and C units: unit j runs on workgroup j mod W.  SELECTS = 0 is
 // the lighter build for launches without S units on retrieval groups (their candidates held
 // in registers set this kernel's register budget, and spill code with it), 1 the build with
@@ -194,18 +162,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
 
 // Launches that carry pooled R and G rows.  Two workgroups per CU must fit (the static shares
 // assume that every workgroup runs from the start): at most 256 registers per lane.
-// Rows a sparse KV head gathers for a sequence of L cache rows (set entries that are -1 or
-// name rows past L are skipped one by one), and how many of them make one pooled block.
-__device__ __forceinline__ int gather_rows(const Common &c, int L)
-{
-    const int units = units_of(c, L);
-    return (c.k < units ? c.k : units) << c.block_shift;
-}
-__device__ __forceinline__ int gather_block(const Common &c)
-{
-    return c.block_shift ? (1 << c.block_shift) : c.g_block_rows;  // whole blocks stream like R rows
-}
-
 // COLLECT = false is the dense baseline's streaming: no layer selects anything.
 template <bool HAS_R, bool HAS_G, bool COLLECT>
 __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPlan P)
@@ -400,7 +356,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
             if (!gather) {
                 const int g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
                 const uint32_t hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
-                Emit em{nullptr, nullptr, 0u, 0, 0, nullptr};
+                Emit em{};
                 if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
                     const int64_t row = (int64_t)b * (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) + gi;
                     em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
@@ -411,14 +367,14 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                     if (c.prob_rule != 0)
                         em.pool_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_pool)) + row * (2 * (int64_t)c.part_stride);
                 }
-                dispatch_piece<false>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
+                dispatch_piece<false, false>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
                                       d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa, at_rows_done);
             } else {
                 const int g = (int)desc_u8(dw, offsetof(LayerDesc, sgroup) + gi);
                 const uint32_t hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
                 const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)g) +
                                          ((int64_t)b * c.n_kv_heads + g) * c.k;
-                dispatch_piece<true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{nullptr, nullptr, 0u, 0, 0, nullptr},
+                dispatch_piece<true, false>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{},
                                      d_part_o, d_part_ml, d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sa,
                                      at_rows_done);
             }
