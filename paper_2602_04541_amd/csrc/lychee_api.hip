@@ -34,7 +34,7 @@ struct lychee_ctx {
     int32_t g_block_rows = 48;
     int32_t tail_permille = 250;
     int32_t select_margin = 60;  // tenths of a standard deviation, see LYCHEE_OPT_SELECT_MARGIN
-    int32_t select_lead = 4000;  // blocks of 64 rows streamed while a select runs, see LYCHEE_OPT_SELECT_LEAD
+    int32_t select_lead = 3000;  // blocks of 64 rows streamed while a select runs, see LYCHEE_OPT_SELECT_LEAD
     uint32_t launch_seq = 0;   // pooled launches so far: picks the chunk counter
     std::vector<int32_t> used_slots;  // counters of pooled launches that no later launch has reset yet
     bool timing = false;
@@ -83,7 +83,8 @@ constexpr size_t kSyncThr = 4096;                               // uint64 [kSync
 constexpr size_t kSyncSet = kSyncThr + kSyncRows * 8;           // uint32 [kSyncRows]
 constexpr size_t kSyncSeg = kSyncSet + kSyncRows * 4;           // uint32 [kSyncRows][2]
 constexpr size_t kSyncCount = kSyncSeg + kSyncRows * 8;         // int32 [3][kSyncRows]
-constexpr size_t kSyncBytes = kSyncCount + 3 * kSyncRows * 4;
+constexpr size_t kSyncArrived = kSyncCount + 3 * kSyncRows * 4; // uint32 [kSyncRows]
+constexpr size_t kSyncBytes = kSyncArrived + kSyncRows * 4;
 
 constexpr int kWsWg = 768;        // largest grid a launch uses
 constexpr int kPartSlots = 1024;  // partial slots per head in the workspace: static runs + chunks
@@ -450,7 +451,7 @@ int layer_launch(lychee_ctx *ctx, const lychee_shape &s, const Workspace &w, con
     if (cur != nullptr) {
         p.cur = *cur;
         p.has_cur = 1;
-        if (cur->emit_sel && !blocks) units += (int64_t)s.batch * cur->n_rgroups;
+        if (cur->emit_sel && !blocks) units += (int64_t)s.batch * cur->n_rgroups * kThrSplit;
         if (prev != nullptr)
             for (int g = 0; g < s.n_kv_heads; ++g)
                 if (cur->idx_src[g] != nullptr && cur->idx_src[g] == prev->idx_out &&
@@ -473,6 +474,7 @@ int layer_launch(lychee_ctx *ctx, const lychee_shape &s, const Workspace &w, con
     p.thr_flags = reinterpret_cast<unsigned long long *>(ctx->sync_dev + kSyncThr);
     p.set_flags = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncSet);
     p.seg_count = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncSeg);
+    p.thr_arrived = reinterpret_cast<uint32_t *>(ctx->sync_dev + kSyncArrived);
     const bool selects = prev != nullptr && prev->n_rgroups > 0;
     const bool collects = cur != nullptr && cur->emit_sel;
     const int build = !(selects || collects) ? 0 : (s.prob_rule != 0 ? 2 : 1);

@@ -30,7 +30,8 @@ struct SharedSelect {
 };
 struct SharedCombine {
     float w[kMaxWg];
-    float red[(kThreads / 32) * kHeadDim];
+    float red[kMaxGroup * (kThreads / 32) * kHeadDim];  // (combine_unit uses the first head's share)
+    float l[kMaxGroup];
 };
 union SharedUnit {
     SharedSelect sel;
@@ -110,6 +111,14 @@ __device__ __forceinline__ void gstore(T *p, T v)
 __device__ __forceinline__ void gstore_through(float *p, float v)
 {
     __hip_atomic_store((LYCHEE_GLOBAL float *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void gstore_through(int32_t *p, int32_t v)
+{
+    __hip_atomic_store((LYCHEE_GLOBAL int32_t *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void gstore_through(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store((LYCHEE_GLOBAL uint32_t *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

@@ -24,6 +24,7 @@ constexpr int kSampleTilesMin = 128;     // the threshold sample: 128 to 256 til
 constexpr int kSampleTilesMax = 256;
 constexpr int kDirectLen = 4096;         // sequences this short are ranked without a threshold
 constexpr int kCandBuf = 256;            // candidates a wavefront collects in LDS between flushes
+constexpr int kThrSplit = 4;             // units that share a score row's threshold sample in a layer launch
 constexpr int kKeyBuf = 4096;            // rows whose keys a piece buffers in LDS when its threshold comes late
 constexpr float kMinusBig = -1.0e30f;    // "no score yet" sentinel of the running maximum
 
@@ -136,6 +137,7 @@ struct LayerLaunch {
     unsigned long long *thr_flags;  // [B * n_rgroups] {generation, threshold} of cur's score rows
     uint32_t *set_flags;   // [B * H_kv] generation once the set of (sequence, KV head) is final
     uint32_t *seg_count;   // [B * H_kv * 2] partials written so far of each R / G segment (zero between launches)
+    uint32_t *thr_arrived; // [B * n_rgroups] threshold units of a score row that have left their keys (likewise)
 };
 // 0: no selection anywhere in the launch (the dense baseline); 1: the hybrid build; 2: the one
 // that also knows the probability rules

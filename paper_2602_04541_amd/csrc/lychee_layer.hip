@@ -42,7 +42,6 @@ struct SharedLayer {
     uint32_t scan[kWaves + 1];
     unsigned long long scan64[kWaves + 1];
     float fred[kWaves + 1];
-    uint32_t gen;
     int32_t flag;
 };
 union SharedRole {
@@ -59,15 +58,13 @@ __device__ __forceinline__ void store_agent(uint32_t *p, uint32_t v)
     __hip_atomic_store((LYCHEE_GLOBAL uint32_t *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// A front unit has written the set of (b, g): make it visible to the whole device, then say so.
+// A front unit has written the set of (b, g), with write-through stores: once every wavefront's
+// stores have completed the set is in device memory, and the flag says so.
 __device__ __forceinline__ void publish_set(uint32_t *flag, uint32_t gen)
 {
-    wait_stores();  // each wavefront: its stores have left the CU
+    wait_stores();
     __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        store_agent(flag, gen);
-    }
+    if (threadIdx.x == 0) store_agent(flag, gen);
 }
 
 // Before a gather piece reads a set that a front unit of this launch writes.
@@ -101,7 +98,10 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
     const int W = c.n_wg;
     const int tid = threadIdx.x;
 
-    if (tid == 0) pool.gen = load_agent(P.gen);
+    TRACE(0);
+    // The generation is only ever used by thread 0 (it sets, polls and advances the flags), which
+    // keeps it in a register: the load is not waited for before its first use, late in the launch.
+    const uint32_t gen = tid == 0 ? load_agent(P.gen) : 0u;
     if (tid < c.batch) pool.len[tid] = clamp_len(c.lengths[tid], c.max_len);
     if (tid < kDescWords) {
         desc_cur[tid] = reinterpret_cast<const uint32_t *>(&P.cur)[tid];
@@ -111,7 +111,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
     const LayerDesc &cur = *reinterpret_cast<const LayerDesc *>(desc_cur);
     const LayerDesc &prev = *reinterpret_cast<const LayerDesc *>(desc_prev);
     const uint32_t *dw = desc_cur;
-    const uint32_t gen = pool.gen;
     uint32_t *timeouts = c.stats + 2;
 
     // ------------------------------------------------------------------ front units
@@ -119,7 +118,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         const int n_rp = P.has_prev ? prev.n_rgroups : 0;
         const int nS = SELECTS ? c.batch * n_rp : 0;
         const int nC = P.has_prev && prev.copy_keep ? c.batch * (c.n_kv_heads - n_rp) : 0;
-        const int nT = COLLECT && P.has_cur && cur.emit_sel && c.block_shift == 0 ? c.batch * cur.n_rgroups : 0;
+        const int nT = COLLECT && P.has_cur && cur.emit_sel && c.block_shift == 0 ? c.batch * cur.n_rgroups * kThrSplit : 0;
         for (int j = w; j < nS + nC + nT; j += P.n_front) {
             if (j < nS) {
                 const int b = j / n_rp;
@@ -137,21 +136,29 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
                 copy_set_unit(c, prev, b, g);
                 publish_set(P.set_flags + b * c.n_kv_heads + g, gen);
             } else {
-                const int u = j - nS - nC;
+                // a score row's sample is dealt to kThrSplit units: one round of loads each
+                const int u = (j - nS - nC) / kThrSplit;
                 const int n_rc = cur.n_rgroups;
                 const int b = u / n_rc, rgi = u % n_rc;
-                unsigned long long *flag = P.thr_flags + ((int64_t)b * n_rc + rgi);
+                const int64_t row = (int64_t)b * n_rc + rgi;
+                unsigned long long *flag = P.thr_flags + row;
+                ThrSplit split;
+                split.sub = (j - nS - nC) % kThrSplit;
+                split.n_sub = kThrSplit;
+                split.keys = reinterpret_cast<uint32_t *>(cur.sel + row * c.sel_stride);  // (free until a select ranks this row whole)
+                split.arrived = P.thr_arrived + row;
                 switch (__builtin_popcount(cur.rmask[cur.rgroup[rgi]] & ((1u << c.group) - 1u))) {
-                case 1: threshold_unit<1>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
-                case 2: threshold_unit<2>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
-                case 3: threshold_unit<3>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
-                default: threshold_unit<4>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen); break;
+                case 1: threshold_unit<1>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen, split); break;
+                case 2: threshold_unit<2>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen, split); break;
+                case 3: threshold_unit<3>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen, split); break;
+                default: threshold_unit<4>(c, cur, b, rgi, sh.unit.sel, pool, flag, gen, split); break;
                 }
             }
             __syncthreads();
         }
     }
 
+    TRACE(1);
     // ------------------------------------------------------------------ the two row spaces
     // Per sequence: blocks of 64 cache rows per retrieval KV head, blocks of gathered rows per
     // sparse KV head.  The workgroups after the front ones are split between the two in
@@ -176,11 +183,16 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         W_R = TR > 0;
         W_G = TG > 0;
     } else if (TR > 0 && TG > 0) {
+        // gathers that wait for a select start lead_blocks of streaming late: they get workgroups for
+        // the work that is left then, though never more than 2.5 times their share of the blocks
+        // (a layer with little to stream must not be left with a handful of streaming workgroups)
         const int64_t lead = P.has_prev && P.gate_mask != 0 ? P.lead_blocks : 0;
         int64_t rest = TR + TG - lead;
         rest = rest < TG ? TG : rest;
-        W_G = (int)((Wn * TG + rest - 1) / rest);
-        W_G = W_G < 1 ? 1 : (W_G > Wn - 1 ? Wn - 1 : W_G);
+        int64_t wg = (Wn * TG + rest - 1) / rest;
+        const int64_t cap = (5 * Wn * TG + 2 * (TR + TG) - 1) / (2 * (TR + TG));
+        wg = wg > cap ? cap : wg;
+        W_G = (int)(wg < 1 ? 1 : (wg > Wn - 1 ? Wn - 1 : wg));
         W_R = Wn - W_G;
     } else if (TG > 0) {
         W_G = Wn;
@@ -224,6 +236,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         }
         __syncthreads();
         const int T = pool.pre[c.batch];
+        TRACE(2);
 
         int x = wl * share;
         int x1 = x + share;
@@ -288,6 +301,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
                 dispatch_piece<true, true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{}, d_part_o, d_part_ml,
                                            d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sh.attn, nothing);
             }
+            TRACE(3);
             // The piece's partials are in device memory.  Count it in; whoever completes the
             // segment merges its partials (slots 0 .. pieces-1 of every head of the segment).
             __syncthreads();
@@ -305,14 +319,15 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
             __syncthreads();
             if (pool.flag) {
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                uint32_t mk = hmask;
-                while (mk != 0) {
-                    const int bit = __builtin_ctz(mk);
-                    mk &= mk - 1;
-                    combine_unit(c, cur, b * c.n_q_heads + g * c.group + bit, sh.unit.comb, pool, pieces);
+                switch (__builtin_popcount(hmask)) {
+                case 1: combine_segment<1>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
+                case 2: combine_segment<2>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
+                case 3: combine_segment<3>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
+                default: combine_segment<4>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
                 }
             }
             __syncthreads();
+            TRACE(4);
             x += len;
         }
     }
@@ -329,6 +344,13 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
 }
 
 }  // namespace
+
+#ifdef LYCHEE_TRACE
+extern "C" int lychee_trace_read_layer(unsigned long long *host, int n_wg)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * n_wg) == hipSuccess ? 0 : -4;
+}
+#endif
 
 hipError_t launch_layer(const LayerLaunch &plan, int build, hipStream_t stream)
 {

@@ -66,6 +66,99 @@ __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p
     __syncthreads();
 }
 
+// The same merge for all NH heads of a segment at once, by the workgroup that has just written the
+// segment's last partial: every load of a group of 64 slots - the (m, l) pairs and the partial
+// outputs of all heads - is issued before the first one is used, so that a segment costs about
+// one round trip to memory however many heads it has (the heads one after the other, each with
+// its own rounds of dependent loads, took 20 us for the four heads of a dense layer's segment).
+// Each wavefront keeps the running maximum and sum of every head itself (redundantly: no barrier
+// between groups); thread (o8, c4) sums slots o8, o8 + 8, ... for columns 4 c4 .. 4 c4 + 3, and
+// the eight sums per column are added in a fixed order at the end.
+template <int NH>
+__device__ __forceinline__ void combine_segment(const Common &c, const LayerDesc &p, int b, int g, uint32_t hmask,
+                                                int count, SharedCombine &sh)
+{
+    const int lane = threadIdx.x & 63;
+    const int o8 = threadIdx.x >> 5;  // which eighth of a group's slots
+    const int c4 = threadIdx.x & 31;  // which 4 columns
+    int64_t bh[NH];
+    {
+        uint32_t mk = hmask;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            bh[h] = (int64_t)b * c.n_q_heads + g * c.group + __builtin_ctz(mk);
+            mk &= mk - 1;
+        }
+    }
+    float M[NH], Ls[NH];
+    float4 acc[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        M[h] = kMinusBig;
+        Ls[h] = 0.0f;
+        acc[h] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int s0 = 0; s0 < count; s0 += 64) {
+        float2 ml[NH];
+        float4 v[NH][8];
+        const int sl = s0 + lane < count ? s0 + lane : count - 1;  // this lane's slot of the group
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const float *pm = p.part_ml + (bh[h] * c.part_stride + sl) * 2;
+            ml[h] = make_float2(gload(pm), gload(pm + 1));
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                int s = s0 + o8 + 8 * u;
+                s = s < count ? s : count - 1;
+                v[h][u] = gload_f4(p.part_o + (bh[h] * c.part_stride + s) * kHeadDim + c4 * 4);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const bool live = s0 + lane < count && ml[h].y > 0.0f;  // (a piece without a valid row leaves l = 0)
+            float mg = live ? ml[h].x : kMinusBig;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) mg = fmaxf(mg, __shfl_xor(mg, d));
+            const float m_new = fmaxf(M[h], mg);
+            const float alpha = fast_exp2((M[h] - m_new) * c.scale_log2e);
+            M[h] = m_new;
+            const float wl = live ? fast_exp2((ml[h].x - m_new) * c.scale_log2e) : 0.0f;  // this lane's slot
+            float lg = wl * ml[h].y;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) lg += __shfl_xor(lg, d);
+            Ls[h] = Ls[h] * alpha + lg;
+            acc[h].x *= alpha, acc[h].y *= alpha, acc[h].z *= alpha, acc[h].w *= alpha;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float wu = __shfl(wl, o8 + 8 * u);  // (slots past the end carry weight 0)
+                acc[h].x = fmaf(wu, v[h][u].x, acc[h].x);
+                acc[h].y = fmaf(wu, v[h][u].y, acc[h].y);
+                acc[h].z = fmaf(wu, v[h][u].z, acc[h].z);
+                acc[h].w = fmaf(wu, v[h][u].w, acc[h].w);
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        reinterpret_cast<float4 *>(sh.red + (h * 8 + o8) * kHeadDim)[c4] = acc[h];
+        if (threadIdx.x == 0) sh.l[h] = Ls[h];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < NH * kHeadDim; i += kThreads) {
+        const int h = i / kHeadDim, col = i % kHeadDim;
+        float o = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o += sh.red[(h * 8 + j) * kHeadDim + col];
+        const float l = sh.l[h];
+        // (bh[h] with a run-time h: picked without indexing the register array)
+        int64_t row = bh[0];
+#pragma unroll
+        for (int hh = 1; hh < NH; ++hh) row = h == hh ? bh[hh] : row;
+        gstore(p.out + row * kHeadDim + col, f32_to_bf16_rne(l > 0.0f ? o / l : 0.0f));
+    }
+    __syncthreads();
+}
+
 // ------------------------------------------------------------------------------ T and S
 // In the histogram of `n_bins` digits, finds the highest digit d whose suffix count
 // (keys with digit >= d) reaches `need`; returns d and need minus the count above d.
@@ -144,10 +237,18 @@ __device__ __forceinline__ float tile_pooled_score(const uint4 (&kr)[4], const u
 // the launch's generation `gen` in the upper half, into *publish by one 64-bit atomic store, which
 // the row's pieces poll; the candidate counter is not touched (it is zero between uses, and the
 // pieces may already be counting).
+// `split` (launches whose streaming waits for the threshold): the row's sample is dealt to n_sub
+// units, each of which reads its share of the rows in one round of loads and leaves the keys in
+// device memory; the unit that arrives last ranks them.  Nobody waits for anybody.
+struct ThrSplit {
+    int sub = 0, n_sub = 1;
+    uint32_t *keys = nullptr;     // [sample size] scratch of this score row
+    uint32_t *arrived = nullptr;  // units of this row that have left their keys (zero between launches)
+};
 template <int NH, typename Pool>
 __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc &p, int b, int rgi,
                                                SharedSelect &sh, Pool &pool, unsigned long long *publish = nullptr,
-                                               uint32_t gen = 0)
+                                               uint32_t gen = 0, const ThrSplit split = ThrSplit())
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -165,7 +266,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
             gstore(p.thr + row, key);
     };
     if (publish == nullptr && threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
-    if (p.q_keep != nullptr && (int)threadIdx.x < c.group * (kHeadDim / 8)) {
+    if (split.sub == 0 && p.q_keep != nullptr && (int)threadIdx.x < c.group * (kHeadDim / 8)) {
         // the group's query rows (consecutive heads, 16 chunks of 16 bytes each)
         const int64_t at = ((int64_t)b * c.n_q_heads + p.rgroup[rgi] * c.group) * kHeadDim + threadIdx.x * 8;
         *(LYCHEE_GLOBAL u32x4_t *)(p.q_keep + at) = *(const LYCHEE_GLOBAL u32x4_t *)(p.q + at);
@@ -173,7 +274,7 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     if (n == L || L <= kDirectLen || 2 * (int64_t)n >= L) {
         // everything is selected anyway (no candidates wanted), or every row is a candidate
         // (a probability rule may keep fewer than everything: it still needs the candidates)
-        emit(n == L && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u);
+        if (split.sub == 0) emit(n == L && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u);
         return;
     }
     int n_tiles = L / 1024;
@@ -195,11 +296,12 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     // come in runs (a passage that matters is hundreds of consecutive rows), and a sample of
     // contiguous tiles would over- or under-count such runs far beyond its nominal deviation.
     const int stratum = (L - 1) / n_sample;  // >= 2
-    for (int t0 = wave * kBatch; t0 < n_tiles; t0 += kWaves * kBatch) {
+    const int t_lo = n_tiles * split.sub / split.n_sub, t_hi = n_tiles * (split.sub + 1) / split.n_sub;
+    for (int t0 = t_lo + wave * kBatch; t0 < t_hi; t0 += kWaves * kBatch) {
         uint4 kr[kBatch][4];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            const int t = t0 + u < n_tiles ? t0 + u : n_tiles - 1;
+            const int t = t0 + u < t_hi ? t0 + u : t_hi - 1;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = t * 16 + 4 * j + rs;  // sample number
@@ -211,10 +313,36 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const uint32_t key = ordered_key(tile_pooled_score<NH>(kr[u], qf, sel_mul));
-            if (t0 + u < n_tiles && ch < 4) {
-                sh.samp[(t0 + u) * 16 + 4 * ch + rs] = key;
-                atomicAdd(&sh.hist[key >> 20], 1u);
+            if (t0 + u < t_hi && ch < 4) {
+                if (split.n_sub > 1) {
+                    gstore_through(split.keys + (t0 + u) * 16 + 4 * ch + rs, key);
+                } else {
+                    sh.samp[(t0 + u) * 16 + 4 * ch + rs] = key;
+                    atomicAdd(&sh.hist[key >> 20], 1u);
+                }
             }
+        }
+    }
+    if (split.n_sub > 1) {
+        // leave the keys, count this unit in; the last one to arrive goes on with all of them
+        wait_stores();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t old = __hip_atomic_fetch_add((LYCHEE_GLOBAL uint32_t *)split.arrived, 1u, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = old == (uint32_t)split.n_sub - 1u;
+            if (last) __hip_atomic_store((LYCHEE_GLOBAL uint32_t *)split.arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh.found[0] = last;
+        }
+        __syncthreads();
+        const bool last = sh.found[0] != 0;
+        __syncthreads();
+        if (!last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        for (int i = threadIdx.x; i < n_sample; i += kThreads) {
+            const uint32_t key = gload(split.keys + i);
+            sh.samp[i] = key;
+            atomicAdd(&sh.hist[key >> 20], 1u);
         }
     }
     __syncthreads();
@@ -424,21 +552,32 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
             cnt += (uint32_t)__builtin_popcount(words[j]);
         }
         uint32_t tot;
-        uint32_t at = base + block_scan(cnt, pool.scan, tot) - cnt;
+        const uint32_t at0 = base + block_scan(cnt, pool.scan, tot) - cnt;
         TRACE(3);
-        // (handing neighbouring words to neighbouring lanes, for store addresses that share
-        // cache lines, was measured to be slower, and so were putting the set together in LDS
-        // and copying it out in order, and dealing 16 ranks to every thread, found by bisection
-        // over the threads' first ranks: 4.4 us for 4096 positions it stays)
+        // The positions are put in order in LDS, kStage at a time, and copied out with coalesced
+        // write-through stores: the set is in device memory once the unit's stores have
+        // completed, whoever reads it next (a gather piece of the same launch, on another XCD,
+        // after an acquire), and a store per position from every lane's own bit loop took four
+        // times as long beside a streaming launch as it does alone.
+        constexpr uint32_t kStage = (uint32_t)(sizeof(sh.samp) / sizeof(sh.samp[0]));
+        uint32_t end = base + tot;
+        end = end < (uint32_t)n ? end : (uint32_t)n;
+        for (uint32_t c0 = base; c0 < end; c0 += kStage) {
+            uint32_t at = at0;
 #pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            uint32_t wd = words[j];
-            while (wd != 0) {
-                const uint32_t bit = (uint32_t)__builtin_ctz(wd);
-                wd &= wd - 1u;
-                if (at < (uint32_t)n) gstore(dst + at, (int32_t)(w0 + (uint32_t)(threadIdx.x * kPer + j) * 32u + bit));
-                ++at;
+            for (int j = 0; j < kPer; ++j) {
+                uint32_t wd = words[j];
+                while (wd != 0) {
+                    const uint32_t bit = (uint32_t)__builtin_ctz(wd);
+                    wd &= wd - 1u;
+                    if (at - c0 < kStage) sh.samp[at - c0] = w0 + (uint32_t)(threadIdx.x * kPer + j) * 32u + bit;
+                    ++at;
+                }
             }
+            __syncthreads();
+            const uint32_t m = end - c0 < kStage ? end - c0 : kStage;
+            for (uint32_t i = threadIdx.x; i < m; i += kThreads) gstore_through(dst + c0 + i, (int32_t)sh.samp[i]);
+            __syncthreads();
         }
         base += tot;
     }
@@ -599,7 +738,7 @@ __device__ __forceinline__ void copy_set_unit(const Common &c, const LayerDesc &
     const int64_t bg = (int64_t)b * c.n_kv_heads + g;
     int32_t *dst = p.idx_out + bg * c.k;
     const int32_t *src = p.idx_src[g] + bg * c.k;
-    for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, gload(src + i));
+    for (int i = threadIdx.x; i < c.k; i += kThreads) gstore_through(dst + i, gload(src + i));
 }
 
 // S unit of KV head (b, g), whose group holds a retrieval head: the set the next layer's
@@ -617,7 +756,7 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     const int n = budget_of(c, L);
     const bool by_prob = PROB && c.prob_rule != 0;
     if (n == L && !by_prob) {  // everything is selected
-        for (int i = threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)(i < L ? i : -1));
+        for (int i = threadIdx.x; i < c.k; i += kThreads) gstore_through(dst + i, (int32_t)(i < L ? i : -1));
         if (threadIdx.x == 0 && c.block_shift == 0 && rgi != 0xFF)
             gstore(p.list_count + ((int64_t)b * p.n_rgroups + rgi), (int32_t)0);  // (nothing was collected; see below)
         return;
@@ -668,7 +807,7 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
         if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
         select_from(E, keep, L, dst, sh, pool);
     }
-    for (int i = keep + threadIdx.x; i < c.k; i += kThreads) gstore(dst + i, (int32_t)-1);
+    for (int i = keep + threadIdx.x; i < c.k; i += kThreads) gstore_through(dst + i, (int32_t)-1);
     if (clear_count && threadIdx.x == 0) gstore(p.list_count + row, (int32_t)0);
 }
 
