@@ -12,13 +12,19 @@
  * Conventions shared by every call
  *   - Pointers are DEVICE pointers unless a parameter says HOST.  The caller owns every
  *     buffer; the library neither frees nor keeps them after the call's stream-ordered
- *     work has finished.  Nothing is allocated inside a call (a context allocates a 4 MiB
- *     device arena and its pinned mirror once, in lychee_create).
- *   - Calls only enqueue work on `hip_stream` (a hipStream_t; NULL = the default stream):
- *     kernel launches, preceded by one small asynchronous host-to-device copy when the
- *     call's pointers differ from those of earlier calls.  They never read device memory
- *     from the host and normally return without waiting (the exception: once the arena has
- *     seen about 4 MiB of distinct descriptor tables, a call waits for the stream once).
+ *     work has finished.  Nothing is allocated inside a call (a context allocates, once, in
+ *     lychee_create: a 4 MiB device arena with its pinned mirror, and about 0.6 MiB of flags and
+ *     counters through which the workgroups of a layer launch hand results to one another).
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t; NULL = the default stream) and
+ *     never read device memory from the host.  The layer calls (lychee_decode_attn,
+ *     lychee_decode_attn_static, lychee_decode_attn_deferred, lychee_select_flush,
+ *     lychee_dense_decode_attn) and the layer-after-layer steps enqueue kernel launches only,
+ *     one per layer, and never wait.  The phased steps and the cache append keep their layer
+ *     descriptors in the arena: they enqueue one small asynchronous host-to-device copy when the
+ *     call's pointers differ from those of earlier calls, and once the arena has seen about
+ *     4 MiB of distinct tables such a call waits for the stream once and starts the arena over
+ *     - unless a stream capture has seen the arena: a captured graph keeps pointing into it, so
+ *     its tables are never recycled and the call returns LYCHEE_EARENA instead.
  *   - bf16 means the upper 16 bits of an IEEE fp32.  Scores and accumulation are fp32;
  *     `out` is rounded to nearest-even bf16.
  *   - KV-cache element (b, g, t, i), g a KV head, t a position, i < 128, lives at
@@ -49,17 +55,21 @@ extern "C" {
 #define LYCHEE_EUNSUPPORTED (-2)  /* a valid request this build does not serve                 */
 #define LYCHEE_EWORKSPACE   (-3)  /* workspace NULL, misaligned or smaller than required       */
 #define LYCHEE_EHIP         (-4)  /* a HIP runtime call failed (no device, launch error, ...)  */
+#define LYCHEE_EARENA       (-5)  /* the context's descriptor arena is full and cannot be recycled
+                                     because a captured graph uses it: create another context   */
 
 #define LYCHEE_HEAD_DIM      128  /* the only head dimension served                            */
 #define LYCHEE_MAX_KV_HEADS   64
 #define LYCHEE_MAX_GROUP       4  /* query heads per KV head served (1..4)                     */
 #define LYCHEE_MAX_BATCH     256
 
-typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id, tuning and a small device
-                                         arena for per-call descriptor tables; use one context
-                                         per stream.  The attention calls only enqueue kernels (and
-                                         at most one host-to-device copy of a descriptor table from
-                                         the context's pinned memory), so a stream that is being
+typedef struct lychee_ctx lychee_ctx; /* opaque; holds the device id, tuning, a small device
+                                         arena for descriptor tables and the hand-off flags of
+                                         the layer launches; use one context per stream, and do
+                                         not let two calls on one context overlap.  The attention
+                                         calls only enqueue kernels (and at most one
+                                         host-to-device copy of a descriptor table from the
+                                         context's pinned memory), so a stream that is being
                                          captured into a HIP graph can take them, and the graph can be
                                          replayed while the context lives and timing is off. */
 
@@ -157,9 +167,13 @@ int lychee_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const void *q
  *               the next token, and before the workspace serves any other call.
  * While a selection is pending, the next deferred call must pass the same shape, lengths
  * pointer and workspace (else EINVAL: flush first), and every other call that is given that
- * workspace returns EINVAL.  With block_size 64 nothing is left
- * pending (the selection has no later launch to join and is enqueued with this call).
- * lychee_select_flush: enqueues a pending selection, if there is one; EINVAL for a NULL ctx.
+ * workspace returns EINVAL.
+ * Each such call is ONE kernel launch.  Inside it the pending selection runs on a few workgroups
+ * of its own, the layer's sparse heads wait (with a bounded wait) until it has published the set
+ * they read, and the workgroup that finishes a head's last piece merges the head's partials.
+ * lychee_select_flush: enqueues a pending selection, if there is one (one small launch); EINVAL
+ * for a NULL ctx.  A model that overlaps work on a second stream can flush there, off its
+ * critical path, as long as the flush is ordered before the next layer's call.
  */
 int lychee_decode_attn_deferred(lychee_ctx *ctx, const lychee_shape *shape, const void *q,
                                 const void *k_cache, const void *v_cache, const uint8_t *head_type_mask,
@@ -211,9 +225,10 @@ int lychee_dense_decode_attn(lychee_ctx *ctx, const lychee_shape *shape, const v
  *     thresholds of all layers, the retrieval streaming of all layers pooled in one launch,
  *     the selects, the sparse gathers of all layers, and the combines.  out[l] of every layer is complete only
  *     when the call's work has finished.
- *   LYCHEE_STEP_LAYERWISE  layer after layer, each as lychee_decode_attn (three dependent
- *     launches); out[l] is complete before layer l+1 starts, as a model that computes
- *     q[l+1] from out[l] needs.
+ *   LYCHEE_STEP_LAYERWISE  layer after layer, ONE launch per layer, each as
+ *     lychee_decode_attn_deferred (layer l's selection runs inside layer l+1's launch, the last
+ *     one alone); out[l] is complete before layer l+1 starts, as a model that computes q[l+1]
+ *     from out[l] needs.
  * Fewer than 128 layers; PHASED falls back to LAYERWISE when n_layers * batch > 2048, and a
  * single layer always runs as lychee_decode_attn does.
  */
@@ -235,9 +250,10 @@ int lychee_append_kv(lychee_ctx *ctx, const lychee_shape *shape, const void *k_n
 /* lychee_decode_step with each layer's cache append inside the call (Alg. 1: append, then
  * attend): k_new[l], v_new[l] (HOST arrays of n_layers device pointers, each bf16 [B][H_kv][128])
  * are written to row lengths[b] - 1 of layer l's caches before any of the step's attention
- * reads them.  The appends ride in the step's first launch (the selection thresholds, whose
- * sample never touches the newest row), so they cost no launch of their own; with block-granular
- * sets, which need no thresholds, they are one small launch. */
+ * reads them.  In the phased step the appends ride in the first launch (the selection
+ * thresholds, whose sample never touches the newest row), so they cost no launch of their own
+ * (with block-granular sets, which need no thresholds, they are one small launch); layer after
+ * layer, all layers' appends are one small launch in front of the first layer. */
 int lychee_decode_step_append(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers,
                               const void *const *q, const void *const *k_new,
                               const void *const *v_new, void *const *k_cache, void *const *v_cache,
@@ -254,25 +270,22 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
                              const void *const *v_cache, void *const *out, const int32_t *lengths,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Debug helper (synchronous): counts entries of idx [B][H_kv][k] that break the index
- * conventions (out of [0, L_b), duplicated, or valid after a -1) into *n_bad (HOST). */
-int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,
-                        const int32_t *lengths, int64_t *n_bad, void *hip_stream);
+const char *lychee_strerror(int code);
 
-/* Debug helper (synchronous): how many score rows, since the context was created, the select had
- * to rank from all of their scores because the sampled threshold let fewer than the budget
- * through (*too_few) or more than the candidate list holds (*too_many).  Both cost time, never
- * correctness; on smooth score distributions both stay 0. */
-int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, void *hip_stream);
+/* ==========================================================================================
+ * Tuning and diagnostics.  Nothing below is needed to run the path; results never depend on any
+ * of it beyond the fp32 rounding order of the split merge (index sets do not depend on it at all).
+ * ========================================================================================== */
 
-/* Options of a context.  Results never depend on them beyond fp32 rounding order of the
- * split merge (index sets do not depend on them at all).
+/* Options of a context.
+ *   DEFAULTS      puts every option back to its default (value ignored)
  *   WG_PER_CU     workgroups per compute unit in every launch (1..3, default 2)
  *   N_WG          workgroups per launch, overriding WG_PER_CU (0 = CUs x WG_PER_CU; at most 768)
  *   STEP_MODE     how lychee_decode_step orders its work (see there)
- *   TAIL_PERMILLE permille of a launch's streaming / gather rows that workgroups claim
- *                 dynamically, in small chunks, after their fixed share (0..1000, default 250; launches too short to hold several chunks per workgroup use none);
- *                 it levels out compute units that stream at different speeds
+ *   TAIL_PERMILLE permille of a phased launch's streaming / gather rows that workgroups claim
+ *                 dynamically, in small chunks, after their fixed share (0..1000, default 250;
+ *                 launches too short to hold several chunks per workgroup use none); it levels out
+ *                 compute units that stream at different speeds
  *   GATHER_BLOCK  set entries whose gather is balanced against 64 streamed rows (a multiple
  *                 of 16 in [16, 128], default 48: a gathered row costs more than a streamed one)
  *   SELECT_MARGIN tenths of a standard deviation by which the sampled selection threshold is
@@ -280,8 +293,11 @@ int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, vo
  *                 A larger margin makes more rows candidates of the exact select; a margin so
  *                 small that fewer than k rows pass, or so large that the candidate list
  *                 overflows, costs time (the row is then ranked from all of its scores) but
- *                 never changes a result */
-#define LYCHEE_OPT_DEFAULTS     0   /* puts every option back to its default (value ignored) */
+ *                 never changes a result
+ *   SELECT_LEAD   layer launches: blocks of 64 rows the device streams while a pending select
+ *                 runs (default 3000); the gathers that wait for that select get workgroups for
+ *                 the work that is left by then */
+#define LYCHEE_OPT_DEFAULTS     0
 #define LYCHEE_OPT_WG_PER_CU    1
 #define LYCHEE_OPT_STEP_MODE    2
 #define LYCHEE_OPT_GATHER_BLOCK 6
@@ -293,12 +309,29 @@ int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, vo
 #define LYCHEE_STEP_LAYERWISE   0
 int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
 
+/* Debug helper (synchronous): counts entries of idx [B][H_kv][k] that break the index
+ * conventions (out of [0, L_b), duplicated, or valid after a -1) into *n_bad (HOST). */
+int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,
+                        const int32_t *lengths, int64_t *n_bad, void *hip_stream);
+
+/* Debug helper (synchronous): how many score rows, since the context was created, the select had
+ * to rank from all of their scores because the sampled threshold let fewer than the budget
+ * through (*too_few) or more than the candidate list holds (*too_many).  Both cost time, never
+ * correctness; on smooth score distributions both stay 0. */
+int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, void *hip_stream);
+
+/* Debug helper (synchronous): how many bounded waits inside layer launches have given up since the
+ * context was created (a piece waiting for its row's threshold, a gather waiting for its set).
+ * It stays 0 unless the device cannot keep a launch's workgroups resident together; a piece that
+ * gives up on a threshold costs time only (its row is ranked whole), a gather that gives up on a
+ * set reads the set as it is. */
+int lychee_wait_timeouts(lychee_ctx *ctx, int64_t *timeouts, void *hip_stream);
+
 /* Per-launch timing with HIP events on the caller's stream.  While enabled, every launch of
- * the library's work-unit kernel is bracketed by an event pair.  lychee_timing_read waits for
- * the recorded events, adds up the milliseconds and launches per launch class since the last
- * read and clears the record.  Every launch runs the same kernel; its class says what it
- * carried (arrays of LYCHEE_N_KERNEL_CLASSES entries). */
-#define LYCHEE_KERNEL_STREAM  0   /* retrieval streaming (alone or with gather work)       */
+ * the library's kernels is bracketed by an event pair.  lychee_timing_read waits for the
+ * recorded events, adds up the milliseconds and launches per launch class since the last
+ * read and clears the record (arrays of LYCHEE_N_KERNEL_CLASSES entries). */
+#define LYCHEE_KERNEL_STREAM  0   /* retrieval streaming of a phased step; a layer launch       */
 #define LYCHEE_KERNEL_GATHER  1   /* sparse gather only                                     */
 #define LYCHEE_KERNEL_THRESHOLD 2 /* selection thresholds                                   */
 #define LYCHEE_KERNEL_SELECT  3   /* select / set copies only                               */
@@ -313,7 +346,7 @@ int lychee_timing_read(lychee_ctx *ctx, float *ms_per_class, int32_t *launches_p
 int lychee_probe_read(lychee_ctx *ctx, const void *src, size_t bytes, void *sink, void *hip_stream);
 int lychee_probe_copy(lychee_ctx *ctx, void *dst, const void *src, size_t bytes, void *hip_stream);
 
-const char *lychee_strerror(int code);
+
 
 #ifdef __cplusplus
 }

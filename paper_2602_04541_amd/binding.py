@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblychee.so")
 
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, EARENA = 0, -1, -2, -3, -4, -5
 KERNEL_STREAM, KERNEL_GATHER, KERNEL_THRESHOLD, KERNEL_SELECT, KERNEL_COMBINE = 0, 1, 2, 3, 4
 N_KERNEL_CLASSES = 5
 OPT_DEFAULTS = 0
@@ -33,6 +33,7 @@ EXPORTS = [
     "lychee_decode_attn", "lychee_decode_attn_static", "lychee_decode_attn_deferred", "lychee_select_flush",
     "lychee_dense_decode_attn", "lychee_decode_step",
     "lychee_dense_decode_step", "lychee_decode_step_append", "lychee_append_kv", "lychee_select_stats",
+    "lychee_wait_timeouts",
     "lychee_validate_idx", "lychee_set_option", "lychee_timing_enable",
     "lychee_timing_read", "lychee_probe_read", "lychee_probe_copy", "lychee_strerror",
 ]
@@ -79,6 +80,7 @@ def _load() -> ctypes.CDLL:
     lib.lychee_decode_step_append.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lychee_append_kv.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp]
     lib.lychee_select_stats.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), vp]
+    lib.lychee_wait_timeouts.argtypes = [vp, ctypes.POINTER(i64), vp]
     lib.lychee_validate_idx.argtypes = [vp, shp, vp, vp, ctypes.POINTER(i64), vp]
     lib.lychee_set_option.argtypes = [vp, i32, i32]
     lib.lychee_timing_enable.argtypes = [vp, ctypes.c_int]
@@ -265,6 +267,12 @@ class Context:
         _check(_lib.lychee_select_stats(self._h, ctypes.byref(a), ctypes.byref(b), _stream(stream)),
                "lychee_select_stats")
         return int(a.value), int(b.value)
+
+    def wait_timeouts(self, stream=None) -> int:
+        """Bounded waits inside layer launches that gave up since the context was created."""
+        n = ctypes.c_int64(-1)
+        _check(_lib.lychee_wait_timeouts(self._h, ctypes.byref(n), _stream(stream)), "lychee_wait_timeouts")
+        return int(n.value)
 
     def validate_idx(self, shape: Shape, idx, lengths, stream=None) -> int:
         n_bad = ctypes.c_int64(-1)

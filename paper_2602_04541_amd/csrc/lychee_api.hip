@@ -57,11 +57,13 @@ struct lychee_ctx {
     char *arena_dev = nullptr;
     char *arena_host = nullptr;  // pinned, same layout as the device arena
     size_t arena_used = 0;
+    bool arena_captured = false;  // some table was uploaded or used while a stream was being captured
     struct Cached {
         uint64_t hash;
         size_t offset, bytes;
     };
     std::vector<Cached> cache;
+    std::vector<LayerDesc> descs;  // a call's layer descriptors (capacity for the most layers a step takes)
     // A layer call whose select has been left for the next call (lychee_decode_attn_deferred).
     struct Pending {
         bool active = false;
@@ -251,15 +253,26 @@ static_assert(sizeof(LayerDesc) % 8 == 0, "tables are hashed word by word");
 
 // Returns the device address of a table with exactly these n descriptors, uploading it (one
 // asynchronous copy on `stream`) unless an identical table is already resident.
-const LayerDesc *resident_table(lychee_ctx *ctx, const LayerDesc *descs, size_t n, hipStream_t stream)
+const LayerDesc *resident_table(lychee_ctx *ctx, const LayerDesc *descs, size_t n, hipStream_t stream, bool *full)
 {
+    *full = false;
     const size_t bytes = n * sizeof(LayerDesc);
     if (bytes > kArenaBytes - kArenaReserved) return nullptr;
     const uint64_t h = hash_words(descs, bytes);
+    // A graph captured from this stream replays launches (and the table's upload, from the pinned
+    // mirror) that point into the arena for as long as the graph lives: once a capture has seen the
+    // arena, its tables are never recycled.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (stream != nullptr && hipStreamIsCapturing(stream, &capturing) != hipSuccess) return nullptr;
+    if (capturing != hipStreamCaptureStatusNone) ctx->arena_captured = true;
     for (const auto &e : ctx->cache)
         if (e.hash == h && e.bytes == bytes && memcmp(ctx->arena_host + e.offset, descs, bytes) == 0)
             return reinterpret_cast<const LayerDesc *>(ctx->arena_dev + e.offset);
     if (ctx->arena_used + bytes > kArenaBytes) {
+        if (ctx->arena_captured) {
+            *full = true;  // LYCHEE_EARENA: the caller needs a fresh context (or fewer distinct buffer sets)
+            return nullptr;
+        }
         // Arena full: start over.  Tables still in use by enqueued launches, and staging
         // bytes of copies still in flight, must not be overwritten, so wait for the stream.
         if (hipStreamSynchronize(stream) != hipSuccess) return nullptr;
@@ -357,11 +370,10 @@ struct Launcher {
         } else {
             // every call ends with a small-unit launch: it resets what the call's pooled
             // launches counted (a pooled launch is never followed by more than this many)
-            while (c.n_clear < 4 && !ctx->used_slots.empty()) {
+            while (c.n_clear < 4 && !ctx->used_slots.empty()) {  // (what does not fit waits for the next small launch)
                 c.clear_slot[c.n_clear++] = ctx->used_slots.back();
                 ctx->used_slots.pop_back();
             }
-            ctx->used_slots.clear();
         }
         p.layers = table;
         p.r_first = r.r_first, p.r_count = r.r_count;
@@ -391,13 +403,6 @@ struct Launcher {
             }
             if (8 * n_segs <= ctx->n_cu && t_max < 48ll * ctx->n_cu) c.n_wg = ctx->n_cu < kWsWg ? ctx->n_cu : kWsWg;
         }
-        {   // the pooled block space of a launch is indexed with 32-bit integers
-            const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
-            int64_t segs = 0;
-            for (int l = r.r_first; l < r.r_first + r.r_count; ++l) segs += host_table[l].n_rgroups;
-            for (int l = r.g_first; l < r.g_first + r.g_count; ++l) segs += host_table[l].n_sgroups;
-            if (segs * s.batch * (4 * seg_blocks + 8) >= (1ll << 31)) return LYCHEE_EUNSUPPORTED;  // (gathered blocks are shorter)
-        }
         for (int l = r.r_first; l < r.r_first + r.r_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
         for (int l = r.t_first; l < r.t_first + r.t_count; ++l) p.n_rseg[l] = (uint8_t)host_table[l].n_rgroups;
         for (int l = r.s_first; l < r.s_first + r.s_count; ++l) {
@@ -419,6 +424,18 @@ struct Launcher {
         return LYCHEE_OK;
     }
 };
+
+// The pooled block space of a phased step's launches (all layers' streamed rows in one launch, all
+// layers' gathered rows in another) is indexed with 32-bit integers: checked before the first launch.
+int check_pooled_space(const lychee_shape &s, const LayerDesc *descs, int n_layers)
+{
+    const int64_t seg_blocks = (s.max_len + kBlockRows - 1) / kBlockRows;
+    int64_t r_segs = 0, g_segs = 0;
+    for (int l = 0; l < n_layers; ++l) r_segs += descs[l].n_rgroups, g_segs += descs[l].n_sgroups;
+    const int64_t segs = r_segs > g_segs ? r_segs : g_segs;
+    if (segs * s.batch * (4 * seg_blocks + 8) >= (1ll << 31)) return LYCHEE_EUNSUPPORTED;  // (gathered blocks are shorter)
+    return LYCHEE_OK;
+}
 
 // The row spaces of a layer launch are indexed with 32-bit integers.
 int check_layer_space(const lychee_shape &s, const LayerDesc &d)
@@ -542,7 +559,8 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     const bool assemble = idx_out != nullptr;
     // the last layer's selection is only needed if the caller wants the final sets
     const int n_select = assemble ? n_layers : n_layers - 1;
-    std::vector<LayerDesc> descs((size_t)n_layers + 1);
+    std::vector<LayerDesc> &descs = ctx->descs;  // reserved at creation: no allocation here
+    descs.assign((size_t)n_layers + 1, LayerDesc{});
     const int32_t *cur[kMaxKvHeads];
     for (int g = 0; g < shape->n_kv_heads; ++g) cur[g] = idx_in;
     for (int l = 0; l < n_layers; ++l) {
@@ -583,8 +601,9 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
         for (int l = 0; l < n_layers; ++l)
             if ((rc = check_layer_space(*shape, descs[l])) != LYCHEE_OK) return rc;
         if (k_new != nullptr) {  // every layer's append first, in one small launch (they are all inputs of the call)
-            const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-            if (table == nullptr) return LYCHEE_EHIP;
+            bool full;
+            const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream, &full);
+            if (table == nullptr) return full ? LYCHEE_EARENA : LYCHEE_EHIP;
             const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
             Ranges t;
             t.a_first = 0, t.a_count = n_layers;
@@ -605,8 +624,10 @@ int decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t n_layers, co
     } else {
         // All layers at once, one launch per phase; each phase needs only earlier phases:
         //   A + T (appends, thresholds)  ->  R (streaming, every layer)  ->  S (select)  ->  G (gather)  ->  C (combine)
-        const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-        if (table == nullptr) return LYCHEE_EHIP;
+        if ((rc = check_pooled_space(*shape, descs.data(), n_layers)) != LYCHEE_OK) return rc;
+        bool full;
+        const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream, &full);
+        if (table == nullptr) return full ? LYCHEE_EARENA : LYCHEE_EHIP;
         const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
         Ranges t;
         t.t_first = 0, t.t_count = shape->block_size == 64 ? 0 : n_select;
@@ -684,6 +705,7 @@ int lychee_create(lychee_ctx **out, int device)
     if (ctx == nullptr) return LYCHEE_EHIP;
     ctx->cache.reserve(kArenaBytes / 1024 + 1);  // (a table is at least a descriptor: the hot calls never grow these)
     ctx->used_slots.reserve(kTicketRing);
+    ctx->descs.reserve(kMaxLayers + 1);
     ctx->device = device;
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     int cur = -1;
@@ -901,15 +923,17 @@ int lychee_append_kv(lychee_ctx *ctx, const lychee_shape *shape, const void *k_n
         return LYCHEE_EINVAL;
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    std::vector<LayerDesc> descs(1);
+    std::vector<LayerDesc> &descs = ctx->descs;
+    descs.assign(1, LayerDesc{});
     LayerDesc &d = descs[0];
     memset(&d, 0, sizeof d);
     d.k_cache = static_cast<const uint16_t *>(k_cache);
     d.v_cache = static_cast<const uint16_t *>(v_cache);
     d.k_new = static_cast<const uint16_t *>(k_new);
     d.v_new = static_cast<const uint16_t *>(v_new);
-    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-    if (table == nullptr) return LYCHEE_EHIP;
+    bool full;
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream, &full);
+    if (table == nullptr) return full ? LYCHEE_EARENA : LYCHEE_EHIP;
     const Workspace w = carve(*shape, 1);
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     Ranges a;
@@ -938,7 +962,8 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
     if ((rc = make_current(ctx)) != LYCHEE_OK) return rc;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Workspace w = carve(*shape, n_layers);
-    std::vector<LayerDesc> descs((size_t)n_layers);
+    std::vector<LayerDesc> &descs = ctx->descs;
+    descs.assign((size_t)n_layers, LayerDesc{});
     for (int l = 0; l < n_layers; ++l) {
         LayerDesc &d = descs[l];
         memset(&d, 0, sizeof d);
@@ -955,8 +980,10 @@ int lychee_dense_decode_step(lychee_ctx *ctx, const lychee_shape *shape, int32_t
             if ((rc = layer_launch(ctx, *shape, w, lengths, &descs[l], nullptr, stream)) != LYCHEE_OK) return rc;
         return LYCHEE_OK;
     }
-    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream);
-    if (table == nullptr) return LYCHEE_EHIP;
+    if ((rc = check_pooled_space(*shape, descs.data(), n_layers)) != LYCHEE_OK) return rc;
+    bool full;
+    const LayerDesc *table = resident_table(ctx, descs.data(), descs.size(), stream, &full);
+    if (table == nullptr) return full ? LYCHEE_EARENA : LYCHEE_EHIP;
     const Launcher L{ctx, *shape, w, lengths, table, descs.data(), stream};
     Ranges r;
     r.r_first = 0, r.r_count = n_layers;
@@ -999,6 +1026,19 @@ int lychee_select_stats(lychee_ctx *ctx, int64_t *too_few, int64_t *too_many, vo
         return LYCHEE_EHIP;
     *too_few = host[0];
     *too_many = host[1];
+    return LYCHEE_OK;
+}
+
+int lychee_wait_timeouts(lychee_ctx *ctx, int64_t *timeouts, void *hip_stream)
+{
+    if (ctx == nullptr || timeouts == nullptr) return LYCHEE_EINVAL;
+    if (make_current(ctx) != LYCHEE_OK) return LYCHEE_EHIP;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint32_t host = 0;
+    if (hipMemcpyAsync(&host, ctx->arena_dev + kArenaStats + 8, sizeof host, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return LYCHEE_EHIP;
+    *timeouts = host;
     return LYCHEE_OK;
 }
 
@@ -1108,6 +1148,7 @@ const char *lychee_strerror(int code)
     case LYCHEE_EUNSUPPORTED: return "unsupported shape (head_dim must be 128, at most 4 query heads per KV head, at most 64 KV heads, batch at most 256, fewer than 128 layers per step)";
     case LYCHEE_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LYCHEE_EHIP: return "HIP runtime error";
+    case LYCHEE_EARENA: return "the context's descriptor arena is full and a captured graph still uses it: use a new context";
     default: return "unknown error";
     }
 }

@@ -1,6 +1,6 @@
-// Device-side building blocks of the work-unit kernels (included by lychee_units.hip only):
+// Device-side building blocks of the work-unit kernels (included by lychee_units.hip and lychee_layer.hip):
 // the LDS layout of a workgroup, global-memory accessors, the bf16 dot product, wavefront and
-// workgroup reductions and scans, and the trace hooks of probe builds.
+// workgroup reductions and scans.
 #pragma once
 #include "lychee_internal.h"
 
@@ -290,29 +290,6 @@ __device__ __forceinline__ float block_sum(float v, float *scratch)
     return r;
 }
 
-#ifdef LYCHEE_TRACE
-__device__ unsigned long long g_trace[kMaxWg * 8];
-__device__ int g_trace_on = 1;
-#define TRACE(slot) do { if (threadIdx.x == 0 && g_trace_on) g_trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
-// Lap timer of a workgroup: adds the time since the previous lap to accumulator `which` (0..3);
-// which < 0 only restarts it, which == -2 also clears the accumulators.
-__device__ unsigned long long g_lap[kMaxWg * 4];
-__device__ __forceinline__ void trace_lap(int which)
-{
-    __shared__ unsigned long long mark;
-    if (threadIdx.x == 0) {
-        const unsigned long long now = wall_clock64();
-        if (which == -2)
-            for (int i = 0; i < 4; ++i) g_lap[blockIdx.x * 4 + i] = 0;
-        if (which >= 0) g_lap[blockIdx.x * 4 + which] += now - mark;
-        mark = now;
-    }
-}
-#define TRACE_LAP(which) trace_lap(which)
-#else
-#define TRACE(slot) do { } while (0)
-#define TRACE_LAP(which) do { } while (0)
-#endif
 
 
 }  // namespace

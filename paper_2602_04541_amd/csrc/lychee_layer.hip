@@ -98,7 +98,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
     const int W = c.n_wg;
     const int tid = threadIdx.x;
 
-    TRACE(0);
     // The generation is only ever used by thread 0 (it sets, polls and advances the flags), which
     // keeps it in a register: the load is not waited for before its first use, late in the launch.
     const uint32_t gen = tid == 0 ? load_agent(P.gen) : 0u;
@@ -158,7 +157,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         }
     }
 
-    TRACE(1);
     // ------------------------------------------------------------------ the two row spaces
     // Per sequence: blocks of 64 cache rows per retrieval KV head, blocks of gathered rows per
     // sparse KV head.  The workgroups after the front ones are split between the two in
@@ -192,6 +190,10 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         int64_t wg = (Wn * TG + rest - 1) / rest;
         const int64_t cap = (5 * Wn * TG + 2 * (TR + TG) - 1) / (2 * (TR + TG));
         wg = wg > cap ? cap : wg;
+        // a gather piece is a chain of latencies (flag, set entries, rows, merge) of about 10 us
+        // whatever its size: few gather blocks get a workgroup each rather than a queue on two
+        const int64_t floor_wg = TG < Wn / 8 ? TG : Wn / 8;
+        wg = wg < floor_wg ? floor_wg : wg;
         W_G = (int)(wg < 1 ? 1 : (wg > Wn - 1 ? Wn - 1 : wg));
         W_R = Wn - W_G;
     } else if (TG > 0) {
@@ -236,7 +238,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         }
         __syncthreads();
         const int T = pool.pre[c.batch];
-        TRACE(2);
 
         int x = wl * share;
         int x1 = x + share;
@@ -301,7 +302,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
                 dispatch_piece<true, true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{}, d_part_o, d_part_ml,
                                            d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sh.attn, nothing);
             }
-            TRACE(3);
             // The piece's partials are in device memory.  Count it in; whoever completes the
             // segment merges its partials (slots 0 .. pieces-1 of every head of the segment).
             __syncthreads();
@@ -327,7 +327,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
                 }
             }
             __syncthreads();
-            TRACE(4);
             x += len;
         }
     }
@@ -345,12 +344,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
 
 }  // namespace
 
-#ifdef LYCHEE_TRACE
-extern "C" int lychee_trace_read_layer(unsigned long long *host, int n_wg)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * n_wg) == hipSuccess ? 0 : -4;
-}
-#endif
 
 hipError_t launch_layer(const LayerLaunch &plan, int build, hipStream_t stream)
 {

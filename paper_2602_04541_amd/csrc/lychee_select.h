@@ -1,4 +1,4 @@
-// C, T, S and A units (included by lychee_units.hip only): the log-sum-exp merge of partials, the
+// C, T, S and A units (included by lychee_units.hip and lychee_layer.hip): the log-sum-exp merge of partials, the
 // sampled selection threshold, the exact radix select of Eq. 2 with the Ratio, Threshold and Top-p
 // rules of Sec. 4.4.1, the set copies, and the cache append of Alg. 1.
 #pragma once
@@ -67,17 +67,21 @@ __device__ __forceinline__ void combine_unit(const Common &c, const LayerDesc &p
 }
 
 // The same merge for all NH heads of a segment at once, by the workgroup that has just written the
-// segment's last partial: every load of a group of 64 slots - the (m, l) pairs and the partial
-// outputs of all heads - is issued before the first one is used, so that a segment costs about
-// one round trip to memory however many heads it has (the heads one after the other, each with
-// its own rounds of dependent loads, took 20 us for the four heads of a dense layer's segment).
-// Each wavefront keeps the running maximum and sum of every head itself (redundantly: no barrier
-// between groups); thread (o8, c4) sums slots o8, o8 + 8, ... for columns 4 c4 .. 4 c4 + 3, and
-// the eight sums per column are added in a fixed order at the end.
+// segment's last partial: every load of a group of slots - the (m, l) pairs and the partial
+// outputs of all heads - is issued before the first one is used, so that a group costs about one
+// round trip to memory however many heads it has (the heads one after the other, each with its
+// own rounds of dependent loads, took 20 us for the four heads of a dense layer's segment).  A
+// group is 64 slots for one or two heads and 32 for three or four: 64 registers of loads in
+// flight either way.  Each wavefront keeps the running maximum and sum of every head itself
+// (redundantly: no barrier between groups); thread (o8, c4) sums slots o8, o8 + 8, ... of a
+// group for columns 4 c4 .. 4 c4 + 3, and the eight sums per column are added in a fixed order
+// at the end.
 template <int NH>
 __device__ __forceinline__ void combine_segment(const Common &c, const LayerDesc &p, int b, int g, uint32_t hmask,
                                                 int count, SharedCombine &sh)
 {
+    constexpr int kU = NH <= 2 ? 8 : 4;  // slots per thread and group
+    constexpr int kSlots = 8 * kU;       // slots per group
     const int lane = threadIdx.x & 63;
     const int o8 = threadIdx.x >> 5;  // which eighth of a group's slots
     const int c4 = threadIdx.x & 31;  // which 4 columns
@@ -98,16 +102,17 @@ __device__ __forceinline__ void combine_segment(const Common &c, const LayerDesc
         Ls[h] = 0.0f;
         acc[h] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    for (int s0 = 0; s0 < count; s0 += 64) {
+    for (int s0 = 0; s0 < count; s0 += kSlots) {
         float2 ml[NH];
-        float4 v[NH][8];
-        const int sl = s0 + lane < count ? s0 + lane : count - 1;  // this lane's slot of the group
+        float4 v[NH][kU];
+        const bool mine = lane < kSlots && s0 + lane < count;  // this lane holds a slot of the group
+        const int sl = mine ? s0 + lane : count - 1;
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
             const float *pm = p.part_ml + (bh[h] * c.part_stride + sl) * 2;
             ml[h] = make_float2(gload(pm), gload(pm + 1));
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kU; ++u) {
                 int s = s0 + o8 + 8 * u;
                 s = s < count ? s : count - 1;
                 v[h][u] = gload_f4(p.part_o + (bh[h] * c.part_stride + s) * kHeadDim + c4 * 4);
@@ -115,7 +120,7 @@ __device__ __forceinline__ void combine_segment(const Common &c, const LayerDesc
         }
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
-            const bool live = s0 + lane < count && ml[h].y > 0.0f;  // (a piece without a valid row leaves l = 0)
+            const bool live = mine && ml[h].y > 0.0f;  // (a piece without a valid row leaves l = 0)
             float mg = live ? ml[h].x : kMinusBig;
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) mg = fmaxf(mg, __shfl_xor(mg, d));
@@ -129,7 +134,7 @@ __device__ __forceinline__ void combine_segment(const Common &c, const LayerDesc
             Ls[h] = Ls[h] * alpha + lg;
             acc[h].x *= alpha, acc[h].y *= alpha, acc[h].z *= alpha, acc[h].w *= alpha;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kU; ++u) {
                 const float wu = __shfl(wl, o8 + 8 * u);  // (slots past the end carry weight 0)
                 acc[h].x = fmaf(wu, v[h][u].x, acc[h].x);
                 acc[h].y = fmaf(wu, v[h][u].y, acc[h].y);
@@ -288,7 +293,6 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
     const float sel_mul = c.scale / (float)NH;
     for (int i = threadIdx.x; i < 4096; i += kThreads) sh.hist[i] = 0;
     __syncthreads();
-    TRACE(5);
 
     constexpr int kBatch = 8;  // groups of 16 sampled rows a wavefront has in flight
     // One row at a hashed offset in each of n_sample equal strata of rows 0 .. L-2 (the newest
@@ -346,7 +350,6 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
         }
     }
     __syncthreads();
-    TRACE(6);
     const float f = (float)n_sample * (float)n / (float)L;
     const float want = f + c.sel_margin * sqrtf(f) + 6.0f;
     const uint32_t target = want < 1.0f ? 1u : (want > (float)n_sample ? (uint32_t)n_sample : (uint32_t)want);
@@ -366,7 +369,6 @@ __device__ __forceinline__ void threshold_unit(const Common &c, const LayerDesc 
         t_key = (d1 << 20) | (d2 << 10);
     }
     emit(t_key);
-    TRACE(7);
 }
 
 // Writes the pooled score of every row of (b, g) into sel[0 .. L): what the select unit falls
@@ -520,7 +522,6 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
     const uint32_t T = radix_select(
         E, (uint32_t)n, [](uint32_t key, uint32_t) { return key; }, [](uint32_t, uint32_t) { return true; }, r_eq,
         sh, pool);
-    TRACE(7);
     uint32_t my_eq = 0;
     E.for_each([&](uint32_t key, uint32_t pos) { my_eq += (uint32_t)((key == T) & (pos != kNoEntry)); });
     uint32_t n_eq;
@@ -544,7 +545,6 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
             if (take) atomicOr(&sh.hist[rel >> 5], 1u << (rel & 31u));
         });
         __syncthreads();
-        TRACE(2);
         uint32_t words[kPer], cnt = 0;
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
@@ -553,7 +553,6 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         }
         uint32_t tot;
         const uint32_t at0 = base + block_scan(cnt, pool.scan, tot) - cnt;
-        TRACE(3);
         // The positions are put in order in LDS, kStage at a time, and copied out with coalesced
         // write-through stores: the set is in device memory once the unit's stores have
         // completed, whoever reads it next (a gather piece of the same launch, on another XCD,
@@ -581,7 +580,6 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         }
         base += tot;
     }
-    TRACE(4);
 }
 
 // A unit of one layer (Alg. 1, "C.append(k, v)"): the decoded token's key and value rows become
@@ -770,7 +768,6 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     // could clear it first).  Every thread has read it before any thread gets past the barriers
     // that follow, so one thread may clear it then.
     const bool clear_count = c.block_shift == 0;
-    TRACE(5);
     float lse = 0.0f;
     if (by_prob) {
         // the pieces of this KV head's segment, counted by its first retrieval head
@@ -783,7 +780,6 @@ __device__ __forceinline__ void select_unit(const Common &c, const LayerDesc &p,
     if (total >= n && total <= kThreads * kSelRegs && total <= c.list_row) {
         RegEntries E;
         E.load(list, total);
-        TRACE(6);
         if (PROB && by_prob) keep = rule_keeps(c, E, n, lse, sh, pool);
         select_from(E, keep, L, dst, sh, pool);
     } else if (total >= n && total <= c.list_row) {

@@ -1,4 +1,4 @@
-// R and G units (included by lychee_units.hip only): streaming a run of cache rows - or of the
+// R and G units (included by lychee_units.hip and lychee_layer.hip): streaming a run of cache rows - or of the
 // rows an inherited set names - through the online softmax (Eq. 1, Eq. 3, o = A V), collecting
 // the candidates of Eq. 2 on the way, and leaving one partial per head and piece.
 #pragma once
@@ -276,15 +276,9 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
     if (n_spans == 0) return;
     issue(t0, 0, 0);
     issue(t1, 0, 1);
-    TRACE(5);
-    TRACE_LAP(0);  // piece set-up, until its first loads are issued
     for (int span = 0; span < n_spans; ++span) {
         float sel0[4], sel1[4];
         consume(t0, sel0);
-        if (span == 0) {
-            TRACE(6);
-            TRACE_LAP(1);  // until the first tile has arrived and is consumed
-        }
         __builtin_amdgcn_sched_barrier(0);
         issue(t0, span + 1, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -435,8 +429,6 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     }
     const bool collects = !GATHER && em.list != nullptr && em.direct == 0;  // the same in every wavefront
 
-    TRACE(7);
-    TRACE_LAP(2);  // streaming
     at_rows_done();  // what the caller wants in flight while the partial is merged and written
     if (!LATE && collects && lane == 0) sh.cand_left[wave] = cand_left;
     // Merge the 4 row slots of the wavefront (lanes l, l^16, l^32, l^48).

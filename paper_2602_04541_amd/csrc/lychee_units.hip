@@ -67,7 +67,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
     const LayerDesc *layers = P.layers;
     const int w = blockIdx.x;
     const int W = c.n_wg;
-    TRACE(0);
     if (w == 0 && (int)threadIdx.x < c.n_clear) c.tickets[c.clear_slot[threadIdx.x]] = 0u;
     // the sequence lengths: asked for now, in LDS by the time the unit tables below are built
     if ((int)threadIdx.x < c.batch) pool.len[threadIdx.x] = clamp_len(c.lengths[threadIdx.x], c.max_len);
@@ -157,7 +156,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_small_kernel(const LaunchP
             __syncthreads();
         }
     }
-    TRACE(1);
 }
 
 // Launches that carry pooled R and G rows.  Two workgroups per CU must fit (the static shares
@@ -173,7 +171,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
     const LayerDesc *layers = P.layers;
     const int w = blockIdx.x;
     const int W = c.n_wg;
-    TRACE(0);
     const int n_items = (P.r_count + P.g_count) * c.batch;
     if (n_items == 0) return;
 
@@ -267,8 +264,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
     if (threadIdx.x == 0) {
         if (w == 0) c.tickets[(c.ticket_slot + kTicketRing / 2) % kTicketRing] = 0u;
     }
-    TRACE(2);
-    TRACE_LAP(-2);
 
     // A piece needs its layer's descriptor before it can issue its first load.  Read through
     // the table pointer that is a chain of dependent loads; instead the descriptor is staged
@@ -383,8 +378,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
                 held[cur ^ 1] = ahead_layer;
             }
             x += len;
-            TRACE(3);
-            TRACE_LAP(3);  // merging and writing the partial
         }
         // next chunk: every workgroup asks until it is told that none is left
         __syncthreads();
@@ -399,7 +392,6 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_pool_kernel(const LaunchPl
         x1 = x + chunk;
         x1 = x1 < T ? x1 : T;
     }
-    TRACE(4);
 }
 
 // ------------------------------------------------------------------------------ helpers
@@ -455,16 +447,6 @@ __global__ void validate_idx_kernel(const int32_t *idx, const int32_t *lengths, 
 
 }  // namespace
 
-#ifdef LYCHEE_TRACE
-extern "C" int lychee_trace_laps(unsigned long long *host, int n_wg)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(lychee::g_lap), sizeof(unsigned long long) * 4 * n_wg) == hipSuccess ? 0 : -4;
-}
-extern "C" int lychee_trace_read(unsigned long long *host, int n_wg)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * n_wg) == hipSuccess ? 0 : -4;
-}
-#endif
 
 hipError_t launch_units(const LaunchPlan &plan, hipStream_t stream)
 {

@@ -360,8 +360,13 @@ def test_c3_full_size_single_layers(ctx, layer):
 
 
 def test_c3_full_decode_step_in_the_benchmarked_configuration(ctx):
-    """The whole 36-layer 128K step exactly as bench.py launches it (phased mode), every
-    layer's output and the final sets against the oracle chain."""
+    """The whole 36-layer 128K step with the library's default options, against ONE oracle chain:
+    (a) exactly as bench.py times it - lychee_decode_step layer after layer, one launch per layer -,
+        every layer's output and the final sets;
+    (b) the same free-running chain as 36 lychee_decode_attn_deferred calls and a flush, which
+        expose EVERY layer's sets: each is compared with the oracle's set of that layer, and a
+        difference is only accepted where the oracle's scores tie (none is expected);
+    (c) the phased step (all queries given before the step), outputs and final sets."""
     lb = H.binding()
     w = wl.WORKLOADS["c3"]
     n_layers = w.n_layers
@@ -369,31 +374,65 @@ def test_c3_full_decode_step_in_the_benchmarked_configuration(ctx):
     masks = np.stack([ly.mask for ly in layers])
     lens_h = layers[0].lengths
     shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.max_len, w.k, kv=layers[0].k_cache)
-    ws = lb.alloc_workspace(shape, n_layers=n_layers)
-    outs = [torch.zeros_like(ly.q) for ly in layers]
-    idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
     lens = torch.from_numpy(lens_h).cuda()
-    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
-    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers],
-                    [ly.v_cache for ly in layers], masks, None, outs, idx_final, lens, ws)
-    torch.cuda.synchronize()
-    got_final = idx_final.cpu().numpy()
-    # oracle chain, one layer on the host at a time; remember which scores produced each set
     G = w.group
+    # the oracle chain, one layer on the host at a time
+    refs = []
     idx = None
-    last_sel = [None] * w.n_kv_heads
-    worst = 0.0
     for l, ly in enumerate(layers):
         out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, w.k, idx)
-        worst = max(worst, H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), out_ref, "c3 step layer %d" % l))
+        refs.append((out_ref, idx.copy(), {g: sel_ref[0, g, :w.max_len].copy() for g in range(w.n_kv_heads)
+                                           if ly.mask[g * G:(g + 1) * G].any()}))
+    last_sel = {}
+    for l in range(n_layers):
+        last_sel.update(refs[l][2])
+
+    def check_outputs(outs, what):
+        worst = 0.0
+        for l in range(n_layers):
+            worst = max(worst, H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "%s layer %d" % (what, l)))
+        _say("c3 %s: worst abs output error %.4g" % (what, worst))
+
+    def check_final(got, what):
         for g in range(w.n_kv_heads):
-            if ly.mask[g * G:(g + 1) * G].any():
-                last_sel[g] = sel_ref[0, g, :w.max_len].copy()
-    _say("c3 step: worst abs output error %.4g" % worst)
-    for g in range(w.n_kv_heads):
-        ok, n_diff, msg = H.index_sets_match(got_final[0, g], idx[0, g], last_sel[g], w.k, H.TIE_REL)
-        assert ok, "final set of KV head %d: %s" % (g, msg)
-        assert (np.diff(got_final[0, g]) > 0).all()
+            ok, n_diff, msg = H.index_sets_match(got[0, g], refs[-1][1][0, g], last_sel[g], w.k, H.TIE_REL)
+            assert ok, "%s: final set of KV head %d: %s" % (what, g, msg)
+            assert (np.diff(got[0, g]) > 0).all()
+
+    qs, ks, vs = [ly.q for ly in layers], [ly.k_cache for ly in layers], [ly.v_cache for ly in layers]
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    for mode, what in ((lb.STEP_LAYERWISE, "step, layer after layer"), (lb.STEP_PHASED, "phased step")):
+        outs = [torch.zeros_like(ly.q) for ly in layers]
+        idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
+        ctx.set_option(lb.OPT_STEP_MODE, mode)
+        ctx.decode_step(shape, qs, ks, vs, masks, None, outs, idx_final, lens, ws)
+        torch.cuda.synchronize()
+        check_outputs(outs, what)
+        check_final(idx_final.cpu().numpy(), what)
+    del ws
+    # (b) layer calls that leave their select pending: every layer's sets are visible
+    ws2 = lb.alloc_workspace(shape, n_layers=2)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    sets = [torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda") for _ in layers]
+    for l, ly in enumerate(layers):
+        ctx.decode_attn_deferred(shape, ly.q, ly.k_cache, ly.v_cache, ly.mask, sets[l - 1] if l else None,
+                                 outs[l], sets[l], lens, ws2)
+    ctx.select_flush()
+    torch.cuda.synchronize()
+    check_outputs(outs, "layer calls")
+    n_diff_total = 0
+    for l, ly in enumerate(layers):
+        got = sets[l].cpu().numpy()
+        for g in range(w.n_kv_heads):
+            if g in refs[l][2]:
+                ok, n_diff, msg = H.index_sets_match(got[0, g], refs[l][1][0, g], refs[l][2][g], w.k, H.TIE_REL)
+                assert ok, "layer %d, KV head %d: %s" % (l, g, msg)
+                assert (np.diff(got[0, g]) > 0).all()
+                n_diff_total += n_diff
+            else:
+                assert (got[0, g] == refs[l][1][0, g]).all(), "layer %d, KV head %d: inherited set not handed on" % (l, g)
+    assert n_diff_total == 0, "%d positions differ from the oracle's sets (inside its ties)" % n_diff_total
+    assert ctx.select_stats() is not None
 
 
 # ------------------------------------------------------------------ configuration 5: sweep
@@ -720,11 +759,12 @@ def test_decode_step_with_the_append_inside(ctx, mode, block):
 
 
 # ------------------------------------------------------------------ HIP graph capture and replay
-@pytest.mark.parametrize("block", [1, 64])
-def test_a_captured_decode_step_replays_correctly(ctx, block):
-    """The step's launches (and its one table upload) are captured into a graph and replayed
-    with new queries in the same buffers; every replay must equal the eager step."""
+@pytest.mark.parametrize("mode,block", [("phased", 1), ("phased", 64), ("layerwise", 1)])
+def test_a_captured_decode_step_replays_correctly(ctx, mode, block):
+    """The step's launches (and, phased, its one table upload) are captured into a graph and
+    replayed with new queries in the same buffers; every replay must equal the eager step."""
     lb = H.binding()
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED if mode == "phased" else lb.STEP_LAYERWISE)
     n_layers = 10
     k = 30 if block == 64 else 1500
     # many layers of a medium length: the pooled streaming launch then hands out dynamic chunks,
@@ -753,7 +793,7 @@ def test_a_captured_decode_step_replays_correctly(ctx, block):
     torch.cuda.synchronize()
     gen = torch.Generator(device="cuda").manual_seed(5)
     for rep in range(3):
-        _say("graph replay %d, block %d" % (rep, block))
+        _say("graph replay %d, %s, block %d" % (rep, mode, block))
         for qt in qs:                        # new queries in the captured buffers
             qt.copy_(torch.randn(qt.shape, generator=gen, device="cuda").to(torch.bfloat16))
         for o in outs:
@@ -774,6 +814,94 @@ def test_a_captured_decode_step_replays_correctly(ctx, block):
         ly.q.copy_(qs[l])
         out_ref, idx, _ = H.oracle_layer(ly, ly.mask, k, idx, block=block)
         H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), out_ref, "graph step layer %d" % l)
+
+
+def _arena_case(n_layers=48):
+    lb = H.binding()
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=1024, k=64, n_layers=n_layers, planted=16)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=1024) for l in range(n_layers)]
+    masks = np.stack([ly.mask for ly in layers])
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, 1024, w.k, kv=layers[0].k_cache)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    idx_final = torch.full((w.batch, w.n_kv_heads, w.k), -9, dtype=torch.int32, device="cuda")
+    return lb, w, layers, masks, shape, ws, lens, idx_final
+
+
+def test_descriptor_arena_recycles_after_many_distinct_buffer_sets():
+    """Phased steps keep their layer descriptors in a 4 MiB arena of the context.  Steps whose
+    output buffers differ each need a table of their own: after a few hundred the arena starts
+    over (the call waits for the stream once).  Every step, before and after that, must still
+    give the first step's result."""
+    lb, w, layers, masks, shape, ws, lens, idx_final = _arena_case()
+    n_layers = len(layers)
+    c = lb.Context(0)
+    try:
+        c.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+        n_sets = 300                        # tables of 49 descriptors, about 45 KB each: the arena holds some 90
+        pool = torch.zeros((n_sets, n_layers) + tuple(layers[0].q.shape), dtype=torch.bfloat16, device="cuda")
+        args = ([ly.q for ly in layers], [ly.k_cache for ly in layers], [ly.v_cache for ly in layers], masks, None)
+        first_idx = None
+        for i in range(n_sets):
+            if i % 100 == 0:
+                _say("arena: step %d" % i)
+            c.decode_step(shape, *args, [pool[i, l] for l in range(n_layers)], idx_final, lens, ws)
+            if i == 0:
+                torch.cuda.synchronize()
+                first_idx = idx_final.clone()
+        torch.cuda.synchronize()
+        assert torch.equal(idx_final, first_idx)
+        same = (pool == pool[0:1]).flatten(1).all(1)
+        assert bool(same.all()), "steps %s differ from the first" % torch.nonzero(~same).flatten().tolist()[:8]
+        out_ref, _, _ = H.oracle_layer(layers[0], layers[0].mask, w.k, None)
+        H.assert_outputs_close(H.bf16_tensor_to_f64(pool[n_sets - 1, 0]), out_ref, "layer 0 of the last step")
+    finally:
+        c.close()
+
+
+def test_descriptor_arena_is_not_recycled_under_a_captured_graph():
+    """A captured graph points into the arena for as long as it lives.  Once a capture has seen
+    the arena, a call that would have to recycle it returns LYCHEE_EARENA instead, and the graph
+    still replays correctly."""
+    lb, w, layers, masks, shape, ws, lens, idx_final = _arena_case()
+    n_layers = len(layers)
+    c = lb.Context(0)
+    try:
+        c.set_option(lb.OPT_STEP_MODE, lb.STEP_PHASED)
+        args = ([ly.q for ly in layers], [ly.k_cache for ly in layers], [ly.v_cache for ly in layers], masks, None)
+        outs = [torch.zeros_like(ly.q) for ly in layers]
+        c.decode_step(shape, *args, outs, idx_final, lens, ws)
+        torch.cuda.synchronize()
+        want = [o.clone() for o in outs]
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                c.decode_step(shape, *args, outs, idx_final, lens, ws)
+        torch.cuda.synchronize()
+        pool = torch.zeros((300, n_layers) + tuple(layers[0].q.shape), dtype=torch.bfloat16, device="cuda")
+        refused = None
+        for i in range(300):
+            try:
+                c.decode_step(shape, *args, [pool[i, l] for l in range(n_layers)], idx_final, lens, ws)
+            except lb.LycheeError as e:
+                refused = (i, e.code)
+                break
+        torch.cuda.synchronize()
+        assert refused is not None and refused[1] == lb.EARENA and refused[0] > 50, refused
+        _say("arena: refused at step %d" % refused[0])
+        for o in outs:
+            o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            assert torch.equal(outs[l], want[l]), "replay after the refusal differs at layer %d" % l
+        # the tables already resident still serve their calls
+        c.decode_step(shape, *args, [pool[0, l] for l in range(n_layers)], idx_final, lens, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(pool[0, 3], want[3])
+    finally:
+        c.close()
 
 
 def test_ratio_rule_counts_blocks_with_block_granular_sets(ctx):
