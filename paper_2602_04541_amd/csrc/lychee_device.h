@@ -27,6 +27,8 @@ struct SharedSelect {
     uint32_t hist[4096];                   // radix histograms; position bitmap of the ordered write
     uint32_t samp[kSampleTilesMax * 16];   // ordered keys of the threshold sample
     uint32_t found[2];
+    uint32_t chunk_at[kThreads];           // ordered write: output rank of the first position of each
+    uint16_t word_at[4096];                //   run of 16 bitmap words, and of each word within its run
 };
 struct SharedCombine {
     float w[kMaxWg];
@@ -174,6 +176,10 @@ __device__ __forceinline__ int budget_of(const Common &c, int L)
 // scalar address arithmetic in the streaming loop).
 constexpr int kDescWords = (int)(sizeof(LayerDesc) / 4);
 static_assert(sizeof(LayerDesc) % 4 == 0 && kDescWords <= kThreads, "one word per thread");
+
+// A value that is the same in every lane, said so to the compiler (a scalar register).
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
 __device__ __forceinline__ uint32_t desc_u32(const uint32_t *dw, size_t off)
 {

@@ -26,8 +26,8 @@
 // Partials cross from one XCD's L2 to another's without the agent-scope release fence (its
 // write-back of the whole L2, executed by every workgroup, costs more than the layer): they are
 // written with write-through stores, the writer waits until those have completed before it
-// counts itself in, and the merging workgroup takes an acquire fence.  The sets, written by a
-// handful of front units, are published with the ordinary release fence.
+// counts itself in, and the merging workgroup takes an acquire fence.  The sets are handed over
+// the same way: written through, waited for, then flagged.
 #include "lychee_internal.h"
 #include "lychee_device.h"
 #include "lychee_stream.h"
@@ -43,6 +43,10 @@ struct SharedLayer {
     unsigned long long scan64[kWaves + 1];
     float fred[kWaves + 1];
     int32_t flag;
+    int32_t role[2][4];            // per kind of piece: first workgroup, workgroups, segments per sequence, blocks
+    uint32_t nb[2][kMaxBatch];     // per kind: blocks of one segment of every sequence
+    int32_t run[3];                // the piece loop: next block of this workgroup's run, blocks per run, padded
+    uint32_t gen;                  // the generation of this launch's flags
 };
 union SharedRole {
     SharedAttn attn;  // a piece
@@ -159,175 +163,237 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
 
     // ------------------------------------------------------------------ the two row spaces
     // Per sequence: blocks of 64 cache rows per retrieval KV head, blocks of gathered rows per
-    // sparse KV head.  The workgroups after the front ones are split between the two in
-    // proportion to the blocks; when the gathers wait for a select, the streaming is
-    // lead_blocks ahead by the time they start, and they get workgroups for what is then left.
-    const int n_rseg = P.has_cur ? (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) : 0;
-    const int n_gseg = P.has_cur ? (int)desc_u32(dw, offsetof(LayerDesc, n_sgroups)) : 0;
-    uint32_t nb_r = 0, nb_g = 0;
-    if (tid < c.batch) {
-        const int L = pool.len[tid];
-        nb_r = n_rseg ? (uint32_t)((L + kBlockRows - 1) / kBlockRows) : 0u;
-        nb_g = n_gseg ? (uint32_t)((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c)) : 0u;
+    // sparse KV head.  The workgroups after the front ones are split between the two kinds.
+    // Everything the piece loop needs afterwards is left in LDS and read again after every
+    // piece: a piece wants every vector register, and whatever the schedule kept in registers
+    // across it was spilled to scratch memory by all workgroups (a launch with a scratch
+    // segment also starts its wavefronts more slowly).
+    // (A single sequence needs no scans over the batch: every thread evaluates it for itself.)
+    const bool single = c.batch == 1;
+    {
+        const int n_rseg = P.has_cur ? (int)desc_u32(dw, offsetof(LayerDesc, n_rgroups)) : 0;
+        const int n_gseg = P.has_cur ? (int)desc_u32(dw, offsetof(LayerDesc, n_sgroups)) : 0;
+        uint32_t nb_r = 0, nb_g = 0;
+        if (tid < c.batch || single) {
+            const int L = pool.len[single ? 0 : tid];
+            nb_r = n_rseg ? (uint32_t)((L + kBlockRows - 1) / kBlockRows) : 0u;
+            nb_g = n_gseg ? (uint32_t)((gather_rows(c, L) + gather_block(c) - 1) / gather_block(c)) : 0u;
+        }
+        unsigned long long tot64 = (unsigned long long)nb_r | ((unsigned long long)nb_g << 32);
+        if (!single) (void)block_scan64(tot64, pool.scan64, tot64);
+        const int64_t TR = (int64_t)(uint32_t)tot64 * n_rseg;
+        const int64_t TG = (int64_t)(uint32_t)(tot64 >> 32) * n_gseg;
+        const int first = W >= 8 ? P.n_front : 0;  // tiny grids: the front workgroups also take pieces
+        const int Wn = W - first;
+        int W_R = 0, W_G = 0;
+        if (Wn < 2) {  // a single workgroup does both kinds, one after the other
+            W_R = TR > 0;
+            W_G = TG > 0;
+        } else if (TR > 0 && TG > 0) {
+            // Gathers that wait for a select start late: by then every workgroup could have streamed
+            // a = lead_blocks / Wn blocks.  Both kinds end together when a streaming workgroup takes u
+            // blocks and a gathering one u - a:  TR / u + TG / (u - a) = Wn, the larger root of
+            // Wn u^2 - (Wn a + TR + TG) u + TR a = 0.  (Every workgroup evaluates the same correctly
+            // rounded operations on the same values, so all agree on the split.)
+            const double lead = P.has_prev && P.gate_mask != 0 ? (double)P.lead_blocks : 0.0;
+            const double a = lead / Wn;
+            const double half_b = 0.5 * (lead + (double)(TR + TG));
+            const double u = (half_b + __builtin_sqrt(half_b * half_b - (double)Wn * (double)TR * a)) / Wn;
+            int64_t wg = u - a > 0.0 ? (int64_t)((double)TG / (u - a) + 0.5) : Wn;
+            // a gather piece is a chain of latencies (flag, set entries, rows, merge) of about 10 us
+            // whatever its size: few gather blocks get a workgroup each rather than a queue on two
+            const int64_t floor_wg = TG < Wn / 8 ? TG : Wn / 8;
+            wg = wg < floor_wg ? floor_wg : wg;
+            // and the streaming keeps at least a third of the workgroups its share of the blocks would give it
+            const int64_t most = Wn - (Wn * TR + 3 * (TR + TG) - 1) / (3 * (TR + TG));
+            wg = wg > most ? most : wg;
+            W_G = (int)(wg < 1 ? 1 : (wg > Wn - 1 ? Wn - 1 : wg));
+            W_R = Wn - W_G;
+        } else if (TG > 0) {
+            W_G = Wn;
+        } else if (TR > 0) {
+            W_R = Wn;
+        }
+        if (tid == 0) {
+            pool.role[0][0] = first;
+            pool.role[0][1] = W_R;
+            pool.role[0][2] = n_rseg;
+            pool.role[0][3] = (int32_t)TR;
+            pool.role[1][0] = Wn < 2 ? first : first + W_R;
+            pool.role[1][1] = W_G;
+            pool.role[1][2] = n_gseg;
+            pool.role[1][3] = (int32_t)TG;
+            pool.gen = gen;  // (its load, issued when the kernel started, has long arrived)
+        }
+        if (tid < c.batch) {
+            pool.nb[0][tid] = nb_r;
+            pool.nb[1][tid] = nb_g;
+        }
     }
-    unsigned long long tot64;
-    (void)block_scan64((unsigned long long)nb_r | ((unsigned long long)nb_g << 32), pool.scan64, tot64);
-    const int64_t TR = (int64_t)(uint32_t)tot64 * n_rseg;
-    const int64_t TG = (int64_t)(uint32_t)(tot64 >> 32) * n_gseg;
-    const int first = W >= 8 ? P.n_front : 0;  // tiny grids: the front workgroups also take pieces
-    const int Wn = W - first;
-    int W_R = 0, W_G = 0;
-    if (Wn < 2) {  // a single workgroup does both kinds, one after the other
-        W_R = TR > 0;
-        W_G = TG > 0;
-    } else if (TR > 0 && TG > 0) {
-        // gathers that wait for a select start lead_blocks of streaming late: they get workgroups for
-        // the work that is left then, though never more than 2.5 times their share of the blocks
-        // (a layer with little to stream must not be left with a handful of streaming workgroups)
-        const int64_t lead = P.has_prev && P.gate_mask != 0 ? P.lead_blocks : 0;
-        int64_t rest = TR + TG - lead;
-        rest = rest < TG ? TG : rest;
-        int64_t wg = (Wn * TG + rest - 1) / rest;
-        const int64_t cap = (5 * Wn * TG + 2 * (TR + TG) - 1) / (2 * (TR + TG));
-        wg = wg > cap ? cap : wg;
-        // a gather piece is a chain of latencies (flag, set entries, rows, merge) of about 10 us
-        // whatever its size: few gather blocks get a workgroup each rather than a queue on two
-        const int64_t floor_wg = TG < Wn / 8 ? TG : Wn / 8;
-        wg = wg < floor_wg ? floor_wg : wg;
-        W_G = (int)(wg < 1 ? 1 : (wg > Wn - 1 ? Wn - 1 : wg));
-        W_R = Wn - W_G;
-    } else if (TG > 0) {
-        W_G = Wn;
-    } else if (TR > 0) {
-        W_R = Wn;
-    }
-    const int g_first = Wn < 2 ? first : first + W_R;
+    __syncthreads();
 
     for (int kind = 0; kind < 2; ++kind) {
         const bool gather = kind == 1;
-        const int role_first = gather ? g_first : first;
-        const int role_n = gather ? W_G : W_R;
-        const int wl = w - role_first;
-        if (role_n <= 0 || wl < 0 || wl >= role_n) continue;  // (uniform in the workgroup)
-        const int nseg = gather ? n_gseg : n_rseg;
-        const uint32_t nb_mine = gather ? nb_g : nb_r;
-        const int64_t T_real = gather ? TG : TR;
-        const int brows = gather ? gather_block(c) : kBlockRows;
-
-        // Equal contiguous runs of blocks; when the segments are few, every segment is padded to
-        // a whole number of runs, so that each workgroup has exactly one piece (a second piece
-        // costs a second start-up and merge, which a launch this short cannot level out).
-        int share = (int)((T_real + role_n - 1) / role_n);
-        int pad = 0;
-        if (8ll * nseg * c.batch <= role_n) {
-            const int s_last = share + (share / 8 > 1 ? share / 8 : 1);
-            int s = share;
-            for (; s <= s_last; ++s) {
-                uint32_t runs = nseg * ((nb_mine + s - 1) / s), all;
-                (void)block_scan(runs, pool.scan, all);
-                if ((int)all <= role_n) break;
-            }
-            if (s <= s_last) share = s, pad = 1;
-        }
         {
+            const int role_n = uni(pool.role[kind][1]);
+            const int wl = w - uni(pool.role[kind][0]);
+            if (role_n <= 0 || wl < 0 || wl >= role_n) continue;  // (uniform in the workgroup)
+            const int nseg = uni(pool.role[kind][2]);
+            const int T_real = uni(pool.role[kind][3]);
+            const uint32_t nb_mine = single ? pool.nb[kind][0] : (tid < c.batch ? pool.nb[kind][tid] : 0u);
+
+            // Equal contiguous runs of blocks; when the segments are few, every segment is padded to
+            // a whole number of runs, so that each workgroup has exactly one piece (a second piece
+            // costs a second start-up and merge, which a launch this short cannot level out).
+            int share = (T_real + role_n - 1) / role_n;
+            int pad = 0;
+            if (8ll * nseg * c.batch <= role_n) {
+                const int s_last = share + (share / 8 > 1 ? share / 8 : 1);
+                int s = share;
+                for (; s <= s_last; ++s) {
+                    uint32_t runs = nseg * ((nb_mine + s - 1) / s), all = runs;
+                    if (!single) (void)block_scan(runs, pool.scan, all);
+                    if ((int)all <= role_n) break;
+                }
+                if (s <= s_last) share = s, pad = 1;
+            }
             const uint32_t mine = pad ? nseg * ((nb_mine + share - 1) / share) * share : nseg * nb_mine;
             uint32_t all;
-            const uint32_t incl = block_scan(mine, pool.scan, all);
+            const uint32_t incl = single ? mine : block_scan(mine, pool.scan, all);
             if (tid < c.batch) pool.pre[tid + 1] = (int32_t)incl;
-            if (tid == 0) pool.pre[0] = 0;
+            if (tid == 0) {
+                pool.pre[0] = 0;
+                pool.run[0] = wl * share;  // the next block of this workgroup's run
+                pool.run[1] = share;
+                pool.run[2] = pad;
+            }
         }
         __syncthreads();
-        const int T = pool.pre[c.batch];
 
-        int x = wl * share;
-        int x1 = x + share;
-        x1 = x1 < T ? x1 : T;
-        while (x < x1) {
-            const int b = find_item(pool.pre, c.batch, x);
-            const int len_b = pool.len[b];
-            const int seg_rows = gather ? gather_rows(c, len_b) : len_b;
+        // One piece: where it lies, from the values in LDS alone.
+        struct Piece {
+            int b, g, len_b, r0, r1, slot, pieces, len;
+            uint32_t hmask;
+            bool ends, padding;
+        };
+        auto piece_at = [&](int x, int x1, int share, int pad) {
+            Piece pc;
+            const int brows = gather ? gather_block(c) : kBlockRows;
+            pc.b = uni(find_item(pool.pre, c.batch, x));
+            pc.len_b = uni(pool.len[pc.b]);
+            const int seg_rows = gather ? gather_rows(c, pc.len_b) : pc.len_b;
             const int nb = (seg_rows + brows - 1) / brows;
             const int nbv = pad ? (nb + share - 1) / share * share : nb;
-            const int xo = x - pool.pre[b];
+            const int pre_b = uni(pool.pre[pc.b]);
+            const int xo = x - pre_b;
             const int gi = xo / nbv;
             const int blk = xo % nbv;
-            if (blk >= nb) break;  // the run lies in a segment's padding
-            const int seg_start = pool.pre[b] + gi * nbv;
+            pc.padding = blk >= nb;  // the run lies in a segment's padding
+            const int seg_start = pre_b + gi * nbv;
             int len = x1 - x;
             len = len < nb - blk ? len : nb - blk;
-            const int r0 = blk * brows;
-            int r1 = (blk + len) * brows;
-            r1 = r1 < seg_rows ? r1 : seg_rows;
-            const int slot = x / share - seg_start / share;
-            const int pieces = (seg_start + nb - 1) / share - seg_start / share + 1;
-            const bool ends = blk + len == nb;
+            pc.len = len;
+            pc.r0 = blk * brows;
+            const int r1 = (blk + len) * brows;
+            pc.r1 = r1 < seg_rows ? r1 : seg_rows;
+            pc.slot = x / share - seg_start / share;
+            pc.pieces = (seg_start + nb - 1) / share - seg_start / share + 1;
+            pc.ends = blk + len == nb;
             const uint32_t gmask = (1u << c.group) - 1u;
-            auto nothing = []() {};
-            const uint16_t *dq = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, q));
-            const uint16_t *dk = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, k_cache));
-            const uint16_t *dv = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, v_cache));
-            float *d_part_o = desc_ptr<float>(dw, offsetof(LayerDesc, part_o));
-            float *d_part_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_ml));
-            int32_t *d_part_count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, part_count));
-            int g;
-            uint32_t hmask;
             if (!gather) {
-                g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
-                hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
-                Emit em{};
-                if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
-                    const int64_t row = (int64_t)b * n_rseg + gi;
-                    em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
-                    em.count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, list_count)) + row;
-                    em.cap = c.list_row;
-                    em.direct = c.block_shift != 0;
-                    if (c.prob_rule != 0)
-                        em.pool_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_pool)) + row * (2 * (int64_t)c.part_stride);
-                    // rows that need no sample have their threshold at once (what the T unit would say)
-                    const int n = budget_of(c, len_b);
-                    em.thr_known = n == len_b || len_b <= kDirectLen || 2 * (int64_t)n >= len_b;
-                    em.thr = n == len_b && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u;
-                    em.thr_flag = P.thr_flags + row;
-                    em.gen = gen;
-                    em.timeouts = timeouts;
-                }
-                dispatch_piece<false, true>(__builtin_popcount(hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
-                                            d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sh.attn, nothing);
+                pc.g = (int)desc_u8(dw, offsetof(LayerDesc, rgroup) + gi);
+                pc.hmask = desc_u8(dw, offsetof(LayerDesc, rmask) + pc.g) & gmask;
             } else {
-                g = (int)desc_u8(dw, offsetof(LayerDesc, sgroup) + gi);
-                hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + g) & gmask;
-                if ((P.gate_mask >> g) & 1ull) await_set(P.set_flags + b * c.n_kv_heads + g, gen, timeouts, pool);
-                const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)g) +
-                                         ((int64_t)b * c.n_kv_heads + g) * c.k;
-                dispatch_piece<true, true>(__builtin_popcount(hmask), c, dq, dk, dv, idx_src, Emit{}, d_part_o, d_part_ml,
-                                           d_part_count, b, g, hmask, len_b, r0, r1, slot, ends, sh.attn, nothing);
+                pc.g = (int)desc_u8(dw, offsetof(LayerDesc, sgroup) + gi);
+                pc.hmask = ~desc_u8(dw, offsetof(LayerDesc, rmask) + pc.g) & gmask;
+            }
+            return pc;
+        };
+
+        for (;;) {
+            int x, x1, share, pad;
+            auto where = [&]() {
+                x = uni(pool.run[0]);
+                share = uni(pool.run[1]);
+                pad = uni(pool.run[2]);
+                const int T = uni(pool.pre[c.batch]);
+                x1 = (w - uni(pool.role[kind][0])) * share + share;
+                x1 = x1 < T ? x1 : T;
+            };
+            where();
+            if (x >= x1) break;
+            {
+                const Piece pc = piece_at(x, x1, share, pad);
+                if (pc.padding) break;
+                auto nothing = []() {};
+                const uint16_t *dq = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, q));
+                const uint16_t *dk = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, k_cache));
+                const uint16_t *dv = desc_ptr<const uint16_t>(dw, offsetof(LayerDesc, v_cache));
+                float *d_part_o = desc_ptr<float>(dw, offsetof(LayerDesc, part_o));
+                float *d_part_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_ml));
+                int32_t *d_part_count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, part_count));
+                const uint32_t my_gen = pool.gen;
+                if (!gather) {
+                    const int n_rseg = uni(pool.role[0][2]);
+                    const int gi = (int)desc_u8(dw, offsetof(LayerDesc, rindex) + pc.g);
+                    Emit em{};
+                    if (COLLECT && desc_u32(dw, offsetof(LayerDesc, emit_sel))) {
+                        const int64_t row = (int64_t)pc.b * n_rseg + gi;
+                        em.list = desc_ptr<unsigned long long>(dw, offsetof(LayerDesc, list)) + row * c.list_row;
+                        em.count = desc_ptr<int32_t>(dw, offsetof(LayerDesc, list_count)) + row;
+                        em.cap = c.list_row;
+                        em.direct = c.block_shift != 0;
+                        if (c.prob_rule != 0)
+                            em.pool_ml = desc_ptr<float>(dw, offsetof(LayerDesc, part_pool)) + row * (2 * (int64_t)c.part_stride);
+                        // rows that need no sample have their threshold at once (what the T unit would say)
+                        const int n = budget_of(c, pc.len_b);
+                        em.thr_known = n == pc.len_b || pc.len_b <= kDirectLen || 2 * (int64_t)n >= pc.len_b;
+                        em.thr = n == pc.len_b && c.prob_rule == 0 ? 0xFFFFFFFFu : 0u;
+                        em.thr_flag = P.thr_flags + row;
+                        em.gen = my_gen;
+                        em.timeouts = timeouts;
+                    }
+                    dispatch_piece<false, true>(__builtin_popcount(pc.hmask), c, dq, dk, dv, nullptr, em, d_part_o, d_part_ml,
+                                                d_part_count, pc.b, pc.g, pc.hmask, pc.len_b, pc.r0, pc.r1, pc.slot, pc.ends,
+                                                sh.attn, nothing);
+                } else {
+                    if ((P.gate_mask >> pc.g) & 1ull)
+                        await_set(P.set_flags + pc.b * c.n_kv_heads + pc.g, my_gen, timeouts, pool);
+                    const int32_t *idx_src = desc_ptr<const int32_t>(dw, offsetof(LayerDesc, idx_src) + 8 * (size_t)pc.g) +
+                                             ((int64_t)pc.b * c.n_kv_heads + pc.g) * c.k;
+                    dispatch_piece<true, true>(__builtin_popcount(pc.hmask), c, dq, dk, dv, idx_src, Emit{}, d_part_o, d_part_ml,
+                                               d_part_count, pc.b, pc.g, pc.hmask, pc.len_b, pc.r0, pc.r1, pc.slot, pc.ends,
+                                               sh.attn, nothing);
+                }
             }
             // The piece's partials are in device memory.  Count it in; whoever completes the
             // segment merges its partials (slots 0 .. pieces-1 of every head of the segment).
             __syncthreads();
+            where();
+            const Piece pc = piece_at(x, x1, share, pad);
             if (tid == 0) {
                 int last = 1;
-                if (pieces > 1) {
-                    uint32_t *counter = P.seg_count + (((int64_t)b * c.n_kv_heads + g) * 2 + kind);
+                if (pc.pieces > 1) {
+                    uint32_t *counter = P.seg_count + (((int64_t)pc.b * c.n_kv_heads + pc.g) * 2 + kind);
                     const uint32_t old = __hip_atomic_fetch_add((LYCHEE_GLOBAL uint32_t *)counter, 1u, __ATOMIC_RELAXED,
                                                                 __HIP_MEMORY_SCOPE_AGENT);
-                    last = old == (uint32_t)pieces - 1u;
+                    last = old == (uint32_t)pc.pieces - 1u;
                     if (last) store_agent(counter, 0u);  // as every launch finds it
                 }
                 pool.flag = last;
+                pool.run[0] = x + pc.len;
             }
             __syncthreads();
             if (pool.flag) {
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                switch (__builtin_popcount(hmask)) {
-                case 1: combine_segment<1>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
-                case 2: combine_segment<2>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
-                case 3: combine_segment<3>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
-                default: combine_segment<4>(c, cur, b, g, hmask, pieces, sh.unit.comb); break;
+                switch (__builtin_popcount(pc.hmask)) {
+                case 1: combine_segment<1>(c, cur, pc.b, pc.g, pc.hmask, pc.pieces, sh.unit.comb); break;
+                case 2: combine_segment<2>(c, cur, pc.b, pc.g, pc.hmask, pc.pieces, sh.unit.comb); break;
+                case 3: combine_segment<3>(c, cur, pc.b, pc.g, pc.hmask, pc.pieces, sh.unit.comb); break;
+                default: combine_segment<4>(c, cur, pc.b, pc.g, pc.hmask, pc.pieces, sh.unit.comb); break;
                 }
             }
             __syncthreads();
-            x += len;
         }
     }
 
@@ -337,7 +403,7 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
                                                     __HIP_MEMORY_SCOPE_AGENT);
         if (old == (uint32_t)W - 1u) {
             store_agent(P.exit_count, 0u);
-            store_agent(P.gen, gen + 1u);
+            store_agent(P.gen, pool.gen + 1u);
         }
     }
 }

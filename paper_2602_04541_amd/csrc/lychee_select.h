@@ -545,31 +545,39 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
             if (take) atomicOr(&sh.hist[rel >> 5], 1u << (rel & 31u));
         });
         __syncthreads();
-        uint32_t words[kPer], cnt = 0;
-#pragma unroll
+        // Thread t counts bitmap words 16 t .. 16 t + 15; the scan gives the output rank of every
+        // run of 16 words and, inside a run, of every word.
+        uint32_t cnt = 0;
+#pragma unroll 4
         for (int j = 0; j < kPer; ++j) {
-            words[j] = sh.hist[threadIdx.x * kPer + j];
-            cnt += (uint32_t)__builtin_popcount(words[j]);
+            sh.word_at[threadIdx.x * kPer + j] = (uint16_t)cnt;  // (at most 16 * 32 positions before it)
+            cnt += (uint32_t)__builtin_popcount(sh.hist[threadIdx.x * kPer + j]);
         }
         uint32_t tot;
         const uint32_t at0 = base + block_scan(cnt, pool.scan, tot) - cnt;
+        sh.chunk_at[threadIdx.x] = at0;
+        __syncthreads();
         // The positions are put in order in LDS, kStage at a time, and copied out with coalesced
         // write-through stores: the set is in device memory once the unit's stores have
         // completed, whoever reads it next (a gather piece of the same launch, on another XCD,
         // after an acquire), and a store per position from every lane's own bit loop took four
-        // times as long beside a streaming launch as it does alone.
+        // times as long beside a streaming launch as it does alone.  Here thread t takes words
+        // t, t + 256, ...: selected positions come in clusters (the newest rows, a few hot spans),
+        // and a thread that held 16 neighbouring words would walk a cluster's hundreds of bits
+        // alone while the others wait.
         constexpr uint32_t kStage = (uint32_t)(sizeof(sh.samp) / sizeof(sh.samp[0]));
         uint32_t end = base + tot;
         end = end < (uint32_t)n ? end : (uint32_t)n;
         for (uint32_t c0 = base; c0 < end; c0 += kStage) {
-            uint32_t at = at0;
-#pragma unroll
+#pragma unroll 4
             for (int j = 0; j < kPer; ++j) {
-                uint32_t wd = words[j];
+                const uint32_t wi = (uint32_t)j * kThreads + threadIdx.x;
+                uint32_t wd = sh.hist[wi];
+                uint32_t at = sh.chunk_at[wi / kPer] + sh.word_at[wi];
                 while (wd != 0) {
                     const uint32_t bit = (uint32_t)__builtin_ctz(wd);
                     wd &= wd - 1u;
-                    if (at - c0 < kStage) sh.samp[at - c0] = w0 + (uint32_t)(threadIdx.x * kPer + j) * 32u + bit;
+                    if (at - c0 < kStage) sh.samp[at - c0] = w0 + wi * 32u + bit;
                     ++at;
                 }
             }

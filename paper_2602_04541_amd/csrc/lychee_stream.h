@@ -374,8 +374,13 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
                                           int r0, int r1, int slot, bool ends_segment,
                                           SharedAttn &sh, Hook &at_rows_done)
 {
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // The thread index is made opaque here: the LDS addresses below that derive from it were
+    // otherwise computed once per kernel, for every variant of this function, kept across
+    // everything and spilled.
+    uint32_t tix = threadIdx.x;
+    asm volatile("" : "+v"(tix));
+    const int lane = (int)(tix & 63u);
+    const int wave = (int)(tix >> 6);
     const int rs = lane >> 4;
     const int ch = lane & 15;
 
@@ -464,6 +469,20 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     }
     // Merge the 4 wavefronts through LDS and write the piece's partial.
     __syncthreads();  // red_o / idx_s readers of the previous piece are done
+    // (the accumulators go to LDS first: nothing below needs them, and kept in registers across
+    // the key filter they were spilled)
+    if (rs == 0) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            float *dst = sh.red_o + (wave * kMaxGroup + h) * kHeadDim + ch * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[e] = acc.o[h][e];
+            if (ch == 0) {
+                sh.red_ml[(wave * kMaxGroup + h) * 2 + 0] = acc.m[h];
+                sh.red_ml[(wave * kMaxGroup + h) * 2 + 1] = acc.l[h];
+            }
+        }
+    }
     int cand_base = 0;
     uint32_t late_thr = 0, late_mine = 0, late_incl = 0;
     // the piece's last window of keys: rows late_first .. r1 - 1
@@ -486,18 +505,6 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     if (pooled_lse && lane == 0) {
         sh.pool_ml[2 * wave] = pool_m;
         sh.pool_ml[2 * wave + 1] = pool_l;
-    }
-    if (rs == 0) {
-#pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            float *dst = sh.red_o + (wave * kMaxGroup + h) * kHeadDim + ch * 8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dst[e] = acc.o[h][e];
-            if (ch == 0) {
-                sh.red_ml[(wave * kMaxGroup + h) * 2 + 0] = acc.m[h];
-                sh.red_ml[(wave * kMaxGroup + h) * 2 + 1] = acc.l[h];
-            }
-        }
     }
     __syncthreads();
     if (collects && threadIdx.x == kThreads - 1) sh.cand_base = cand_base;
