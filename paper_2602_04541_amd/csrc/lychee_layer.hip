@@ -181,8 +181,9 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
         }
         unsigned long long tot64 = (unsigned long long)nb_r | ((unsigned long long)nb_g << 32);
         if (!single) (void)block_scan64(tot64, pool.scan64, tot64);
-        const int64_t TR = (int64_t)(uint32_t)tot64 * n_rseg;
-        const int64_t TG = (int64_t)(uint32_t)(tot64 >> 32) * n_gseg;
+        // (the totals are the same in every lane: scalar arithmetic from here on)
+        const int64_t TR = (int64_t)uni((uint32_t)tot64) * n_rseg;
+        const int64_t TG = (int64_t)uni((uint32_t)(tot64 >> 32)) * n_gseg;
         const int first = W >= 8 ? P.n_front : 0;  // tiny grids: the front workgroups also take pieces
         const int Wn = W - first;
         int W_R = 0, W_G = 0;
@@ -193,21 +194,26 @@ __global__ __launch_bounds__(kThreads, 2) void lychee_layer_kernel(const LayerLa
             // Gathers that wait for a select start late: by then every workgroup could have streamed
             // a = lead_blocks / Wn blocks.  Both kinds end together when a streaming workgroup takes u
             // blocks and a gathering one u - a:  TR / u + TG / (u - a) = Wn, the larger root of
-            // Wn u^2 - (Wn a + TR + TG) u + TR a = 0.  (Every workgroup evaluates the same correctly
-            // rounded operations on the same values, so all agree on the split.)
-            const double lead = P.has_prev && P.gate_mask != 0 ? (double)P.lead_blocks : 0.0;
-            const double a = lead / Wn;
-            const double half_b = 0.5 * (lead + (double)(TR + TG));
-            const double u = (half_b + __builtin_sqrt(half_b * half_b - (double)Wn * (double)TR * a)) / Wn;
-            int64_t wg = u - a > 0.0 ? (int64_t)((double)TG / (u - a) + 0.5) : Wn;
+            // Wn u^2 - (Wn a + TR + TG) u + TR a = 0.  Single precision is plenty (any split is a
+            // valid one), and every workgroup evaluates the same operations on the same values, so
+            // all agree on it.
+            const float tr = (float)TR, tg = (float)TG, wn = (float)Wn;
+            const float lead = P.has_prev && P.gate_mask != 0 ? (float)P.lead_blocks : 0.0f;
+            const float inv_wn = __builtin_amdgcn_rcpf(wn);
+            const float a = lead * inv_wn;
+            const float half_b = 0.5f * (lead + tr + tg);
+            float disc = half_b * half_b - tr * lead;
+            disc = disc > 0.0f ? disc : 0.0f;
+            const float u = (half_b + __builtin_amdgcn_sqrtf(disc)) * inv_wn;
+            int wg = u - a > 0.0f ? (int)(tg * __builtin_amdgcn_rcpf(u - a) + 0.5f) : Wn;
             // a gather piece is a chain of latencies (flag, set entries, rows, merge) of about 10 us
             // whatever its size: few gather blocks get a workgroup each rather than a queue on two
-            const int64_t floor_wg = TG < Wn / 8 ? TG : Wn / 8;
+            const int floor_wg = TG < Wn / 8 ? (int)TG : Wn / 8;
             wg = wg < floor_wg ? floor_wg : wg;
             // and the streaming keeps at least a third of the workgroups its share of the blocks would give it
-            const int64_t most = Wn - (Wn * TR + 3 * (TR + TG) - 1) / (3 * (TR + TG));
+            const int most = Wn - (int)(wn * tr * __builtin_amdgcn_rcpf(3.0f * (tr + tg)));
             wg = wg > most ? most : wg;
-            W_G = (int)(wg < 1 ? 1 : (wg > Wn - 1 ? Wn - 1 : wg));
+            W_G = wg < 1 ? 1 : (wg > Wn - 1 ? Wn - 1 : wg);
             W_R = Wn - W_G;
         } else if (TG > 0) {
             W_G = Wn;

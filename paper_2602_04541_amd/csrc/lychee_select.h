@@ -569,16 +569,25 @@ __device__ __forceinline__ void select_from(const Entries &E, int n, int L, int3
         uint32_t end = base + tot;
         end = end < (uint32_t)n ? end : (uint32_t)n;
         for (uint32_t c0 = base; c0 < end; c0 += kStage) {
-#pragma unroll 4
-            for (int j = 0; j < kPer; ++j) {
-                const uint32_t wi = (uint32_t)j * kThreads + threadIdx.x;
-                uint32_t wd = sh.hist[wi];
-                uint32_t at = sh.chunk_at[wi / kPer] + sh.word_at[wi];
-                while (wd != 0) {
-                    const uint32_t bit = (uint32_t)__builtin_ctz(wd);
-                    wd &= wd - 1u;
-                    if (at - c0 < kStage) sh.samp[at - c0] = w0 + wi * 32u + bit;
-                    ++at;
+            // (eight words at a time: their LDS reads overlap instead of each waiting in its own branch)
+#pragma unroll 1
+            for (int j0 = 0; j0 < kPer; j0 += 8) {
+                uint32_t wd[8], at[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t wi = (uint32_t)(j0 + u) * kThreads + threadIdx.x;
+                    wd[u] = sh.hist[wi];
+                    at[u] = sh.chunk_at[wi / kPer] + sh.word_at[wi] - c0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t first = w0 + ((uint32_t)(j0 + u) * kThreads + threadIdx.x) * 32u;
+                    while (wd[u] != 0) {
+                        const uint32_t bit = (uint32_t)__builtin_ctz(wd[u]);
+                        wd[u] &= wd[u] - 1u;
+                        if (at[u] < kStage) sh.samp[at[u]] = first + bit;
+                        ++at[u];
+                    }
                 }
             }
             __syncthreads();
