@@ -75,6 +75,37 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
+// x + (x of the lane 16 lanes away) and the same for 32 lanes, as x + __shfl_xor(x, 16 / 32) give
+// them (bit for bit: one addition of the same two numbers), without the LDS crossbar: gfx950's row
+// swaps are plain vector instructions.  v_permlane16_swap(a, b) exchanges the odd rows of 16 lanes of a
+// with the even rows of b, v_permlane32_swap(a, b) the upper half of a with the lower half of b; with
+// a = b = x the two results hold the even (lower) parts of x everywhere and the odd (upper) parts
+// everywhere.
+__device__ __forceinline__ float sum_rows16(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+__device__ __forceinline__ float sum_halves32(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+__device__ __forceinline__ float max_rows16(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+__device__ __forceinline__ float max_halves32(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr float kLog2e = 1.4426950408889634f;
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }

@@ -297,8 +297,7 @@ __device__ __forceinline__ void stream_rows(const Common &c, const uint16_t *kba
                 m = (r < r1) ? fmaxf(m, sel_value(sel0[j], sel_mul)) : m;
                 m = (r + 16 < r1) ? fmaxf(m, sel_value(sel1[j], sel_mul)) : m;
             }
-            m = fmaxf(m, __shfl_xor(m, 16));
-            m = fmaxf(m, __shfl_xor(m, 32));
+            m = max_halves32(max_rows16(m));
             block_best = (span & 1) ? fmaxf(block_best, m) : m;
             const int first = rb - 32;  // of the block, when this is its second span
             if ((span & 1) && first < r1 && lane == 0) {
@@ -440,19 +439,16 @@ __device__ __forceinline__ void run_piece(const Common &c, const uint16_t *q, co
     const float c_log2e = c.scale_log2e;
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-        float mw = fmaxf(acc.m[h], __shfl_xor(acc.m[h], 16));
-        mw = fmaxf(mw, __shfl_xor(mw, 32));
+        const float mw = max_halves32(max_rows16(acc.m[h]));
         const float a = fast_exp2((acc.m[h] - mw) * c_log2e);
         acc.m[h] = mw;
         float lw = acc.l[h] * a;
-        lw += __shfl_xor(lw, 16);
-        lw += __shfl_xor(lw, 32);
+        lw = sum_halves32(sum_rows16(lw));
         acc.l[h] = lw;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float ow = acc.o[h][e] * a;
-            ow += __shfl_xor(ow, 16);
-            ow += __shfl_xor(ow, 32);
+            ow = sum_halves32(sum_rows16(ow));
             acc.o[h][e] = ow;
         }
     }

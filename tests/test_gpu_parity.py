@@ -432,7 +432,7 @@ def test_c3_full_decode_step_in_the_benchmarked_configuration(ctx):
             else:
                 assert (got[0, g] == refs[l][1][0, g]).all(), "layer %d, KV head %d: inherited set not handed on" % (l, g)
     assert n_diff_total == 0, "%d positions differ from the oracle's sets (inside its ties)" % n_diff_total
-    assert ctx.select_stats() is not None
+    assert ctx.wait_timeouts() == 0, "a bounded wait inside a layer launch gave up"
 
 
 # ------------------------------------------------------------------ configuration 5: sweep
@@ -1060,6 +1060,48 @@ def test_layer_calls_that_leave_their_select_pending(ctx, margin, block):
     for l in range(n_layers):
         assert torch.equal(outs2[l], outs[l]), "two buffers in turn: layer %d differs" % l
     assert torch.equal(pair[(n_layers - 1) % 2], sets[-1])
+
+
+@pytest.mark.parametrize("L", [5000, 16384, 40000])
+def test_deferred_layer_calls_over_context_lengths(ctx, L):
+    """The layer launch splits its workgroups between streaming and gathering from the lengths it
+    finds on the device; contexts of a few thousand to tens of thousands of rows exercise the split
+    where gathers outweigh the streaming, about even it, and are outweighed.  Five deferred calls
+    with the c3 head layout against the oracle chain; no bounded wait may have given up."""
+    lb = H.binding()
+    n_layers = 5
+    k = 1024
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=L, k=k, n_layers=n_layers, planted=32)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=L) for l in range(n_layers)]
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, L, k, kv=layers[0].k_cache)
+    ws = lb.alloc_workspace(shape, n_layers=2)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    pair = [torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda") for _ in range(2)]
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    waits0 = ctx.wait_timeouts()
+    for l, ly in enumerate(layers):
+        _say("context %d: deferred layer call %d" % (L, l))
+        ctx.decode_attn_deferred(shape, ly.q, ly.k_cache, ly.v_cache, ly.mask,
+                                 pair[(l - 1) % 2] if l else None, outs[l], pair[l % 2], lens, ws)
+    ctx.select_flush()
+    torch.cuda.synchronize()
+    assert ctx.wait_timeouts() == waits0
+    G = w.group
+    for l, ly in enumerate(layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "context %d layer %d" % (L, l))
+    got = pair[(n_layers - 1) % 2].cpu().numpy()
+    last = layers[-1]
+    for g in range(w.n_kv_heads):
+        if last.mask[g * G:(g + 1) * G].any():
+            ok, _, msg = H.index_sets_match(got[0, g], refs[-1][1][0, g], refs[-1][2][0, g, :L], k, H.TIE_REL)
+            assert ok, "context %d head %d: %s" % (L, g, msg)
+        else:
+            assert (got[0, g] == refs[-1][1][0, g]).all()
 
 
 def test_a_pending_select_pins_its_workspace_and_shape(ctx):
