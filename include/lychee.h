@@ -310,7 +310,8 @@ const char *lychee_strerror(int code);
 int lychee_set_option(lychee_ctx *ctx, int32_t option, int32_t value);
 
 /* Debug helper (synchronous): counts entries of idx [B][H_kv][k] that break the index
- * conventions (out of [0, L_b), duplicated, or valid after a -1) into *n_bad (HOST). */
+ * conventions (out of [0, L_b), duplicated, or valid after a -1) into *n_bad (HOST).  The one call
+ * of the library that allocates (and frees) device memory, 8 bytes: not for a captured stream. */
 int lychee_validate_idx(lychee_ctx *ctx, const lychee_shape *shape, const int32_t *idx,
                         const int32_t *lengths, int64_t *n_bad, void *hip_stream);
 
