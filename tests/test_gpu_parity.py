@@ -1104,6 +1104,62 @@ def test_deferred_layer_calls_over_context_lengths(ctx, L):
             assert (got[0, g] == refs[-1][1][0, g]).all()
 
 
+def test_two_contexts_on_two_streams_run_layer_calls_side_by_side():
+    """Two contexts, each on a stream of its own, run deferred layer chains at the same time (two
+    model replicas on one GPU).  The launches share the GPU's workgroup slots; every wait inside a
+    launch is for a front unit of the same launch, which is dispatched before its waiters, so the
+    two must neither disturb nor stall each other.  Both chains against the oracle; no wait gave up."""
+    lb = H.binding()
+    n_layers = 4
+    k = 512
+    L = 20000
+    chains = []
+    for seed_shift in (0, 1):
+        w = wl.scaled(wl.WORKLOADS["c3"], max_len=L, k=k, n_layers=n_layers + seed_shift, planted=32)
+        layers = [wl.make_layer(w, layer=l + seed_shift, device="cuda", l_cap=L) for l in range(n_layers)]
+        if seed_shift:   # (layer 0 of a chain passes no inherited sets: every head must be a retrieval head there)
+            layers[0].mask[:] = 1
+        idx = None
+        refs = []
+        for ly in layers:
+            out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx)
+            refs.append((out_ref, idx, sel_ref))
+        shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, L, k, kv=layers[0].k_cache)
+        chains.append(dict(w=w, layers=layers, refs=refs, shape=shape, ctx=lb.Context(0), stream=torch.cuda.Stream(),
+                           ws=lb.alloc_workspace(shape, n_layers=2),
+                           outs=[torch.zeros_like(ly.q) for ly in layers],
+                           pair=[torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda") for _ in range(2)],
+                           lens=torch.from_numpy(layers[0].lengths).cuda()))
+    torch.cuda.synchronize()
+    try:
+        for rep in range(3):
+            for l in range(n_layers):
+                for ch in chains:   # alternate between the two streams: the launches overlap on the GPU
+                    ly = ch["layers"][l]
+                    ch["ctx"].decode_attn_deferred(ch["shape"], ly.q, ly.k_cache, ly.v_cache, ly.mask,
+                                                   ch["pair"][(l - 1) % 2] if l else None, ch["outs"][l], ch["pair"][l % 2],
+                                                   ch["lens"], ch["ws"], stream=ch["stream"])
+            for ch in chains:
+                ch["ctx"].select_flush(stream=ch["stream"])
+        torch.cuda.synchronize()
+        for i, ch in enumerate(chains):
+            assert ch["ctx"].wait_timeouts() == 0
+            for l in range(n_layers):
+                H.assert_outputs_close(H.bf16_tensor_to_f64(ch["outs"][l]), ch["refs"][l][0], "chain %d layer %d" % (i, l))
+            w, last = ch["w"], ch["layers"][-1]
+            got = ch["pair"][(n_layers - 1) % 2].cpu().numpy()
+            for g in range(w.n_kv_heads):
+                if last.mask[g * w.group:(g + 1) * w.group].any():
+                    ok, _, msg = H.index_sets_match(got[0, g], ch["refs"][-1][1][0, g], ch["refs"][-1][2][0, g, :L], k, H.TIE_REL)
+                    assert ok, "chain %d head %d: %s" % (i, g, msg)
+                else:
+                    assert (got[0, g] == ch["refs"][-1][1][0, g]).all()
+    finally:
+        torch.cuda.synchronize()
+        for ch in chains:
+            ch["ctx"].close()
+
+
 def test_a_pending_select_pins_its_workspace_and_shape(ctx):
     lb = H.binding()
     w = wl.scaled(wl.WORKLOADS["c1"], max_len=6000, k=100)
