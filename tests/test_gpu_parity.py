@@ -1280,6 +1280,59 @@ def test_seeded_sweep_of_shapes_masks_and_modes(ctx, case):
     H.check_layer(ctx, inp, mask, k, idx_in, "sweep%d" % i, keep_ppm=keep_ppm, block=block)
 
 
+@pytest.mark.parametrize("block", [1, 64])
+def test_a_serving_batch_of_many_short_sequences(ctx, block):
+    """64 sequences of 40 to 3000 rows in one call (a serving batch): hundreds of (sequence, KV head)
+    segments, more than the grid has workgroups, so the runs are unpadded and most workgroups cross
+    from one segment into the next.  A layer call, then a three-layer layer-after-layer step."""
+    lb = H.binding()
+    B, Hkv, G, l_cap = 64, 4, 2, 3000
+    k = 10 if block == 64 else 200
+    rng = np.random.default_rng(77)
+    lens = rng.integers(40, l_cap + 1, size=B).astype(np.int32)
+    lens[:3] = (1, l_cap, 64)
+    mask = np.array([1, 0, 0, 0, 0, 1, 0, 0], np.uint8)   # KV heads 0 and 2 hold a retrieval head
+    w = wl.scaled(wl.WORKLOADS["c1"], batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, max_len=l_cap, k=k,
+                  planted=1, retrieval_heads=(), config_id=950 + block)
+    inp = wl.make_layer(w, mask=mask, lens=lens, l_cap=l_cap)
+    idx_in = H.previous_layer_sets(inp, k, block=block)
+    _say("serving batch, block %d: layer call" % block)
+    H.check_layer(ctx, inp, mask, k, idx_in, "batch64", block=block)
+    # the step: layer 0 all-retrieval, then two hybrid layers
+    n_layers = 3
+    masks = np.stack([np.ones(Hkv * G, np.uint8), mask, mask[::-1].copy()])
+    layers = [wl.make_layer(wl.scaled(w, config_id=960 + 10 * block + l), mask=masks[l], lens=lens, l_cap=l_cap, device="cuda")
+              for l in range(n_layers)]
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx, block=block)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(B, Hkv * G, Hkv, l_cap, k, kv=layers[0].k_cache, block_size=block)
+    ws = lb.alloc_workspace(shape, n_layers=n_layers)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    idx_final = torch.full((B, Hkv, k), -9, dtype=torch.int32, device="cuda")
+    lens_d = torch.from_numpy(lens).cuda()
+    ctx.set_option(lb.OPT_STEP_MODE, lb.STEP_LAYERWISE)
+    _say("serving batch, block %d: step" % block)
+    ctx.decode_step(shape, [ly.q for ly in layers], [ly.k_cache for ly in layers], [ly.v_cache for ly in layers],
+                    masks, None, outs, idx_final, lens_d, ws)
+    torch.cuda.synchronize()
+    assert ctx.wait_timeouts() == 0
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "batch64 step layer %d" % l)
+    got = idx_final.cpu().numpy()
+    last = layers[-1]
+    for b in range(B):
+        for g in range(Hkv):
+            if last.mask[g * G:(g + 1) * G].any():
+                sc = H.unit_scores(refs[-1][2][b, g], int(lens[b]), block)
+                ok, _, msg = H.index_sets_match(got[b, g], refs[-1][1][b, g], sc, min(k, len(sc)), H.TIE_REL)
+                assert ok, "sequence %d head %d: %s" % (b, g, msg)
+            else:
+                assert (got[b, g] == refs[-1][1][b, g]).all()
+
+
 def _step_cases(n=10, seed=20260205):
     rng = np.random.default_rng(seed)
     cases = []
