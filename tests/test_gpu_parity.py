@@ -1104,6 +1104,51 @@ def test_deferred_layer_calls_over_context_lengths(ctx, L):
             assert (got[0, g] == refs[-1][1][0, g]).all()
 
 
+@pytest.mark.parametrize("n_wg", [1, 3, 7, 37])
+def test_deferred_layer_calls_on_tiny_grids(ctx, n_wg):
+    """A handful of workgroups for a whole layer launch: below 8 the front workgroups (the previous
+    call's select, this call's thresholds) take pieces themselves afterwards, a single workgroup does
+    everything in turn, and a piece is many thousand rows long, so it filters its key buffer several
+    times on the way.  Four deferred calls against the oracle chain."""
+    lb = H.binding()
+    n_layers, k, L = 4, 900, 21000
+    w = wl.scaled(wl.WORKLOADS["c3"], max_len=L, k=k, n_layers=n_layers, planted=32)
+    layers = [wl.make_layer(w, layer=l, device="cuda", l_cap=L) for l in range(n_layers)]
+    idx = None
+    refs = []
+    for ly in layers:
+        out_ref, idx, sel_ref = H.oracle_layer(ly, ly.mask, k, idx)
+        refs.append((out_ref, idx, sel_ref))
+    shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, L, k, kv=layers[0].k_cache)
+    ws = lb.alloc_workspace(shape, n_layers=2)
+    outs = [torch.zeros_like(ly.q) for ly in layers]
+    pair = [torch.full((w.batch, w.n_kv_heads, k), -9, dtype=torch.int32, device="cuda") for _ in range(2)]
+    lens = torch.from_numpy(layers[0].lengths).cuda()
+    waits0 = ctx.wait_timeouts()
+    ctx.set_option(lb.OPT_N_WG, n_wg)
+    try:
+        for l, ly in enumerate(layers):
+            _say("grid of %d: deferred layer call %d" % (n_wg, l))
+            ctx.decode_attn_deferred(shape, ly.q, ly.k_cache, ly.v_cache, ly.mask,
+                                     pair[(l - 1) % 2] if l else None, outs[l], pair[l % 2], lens, ws)
+        ctx.select_flush()
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_option(lb.OPT_N_WG, 0)
+    assert ctx.wait_timeouts() == waits0
+    G = w.group
+    for l in range(n_layers):
+        H.assert_outputs_close(H.bf16_tensor_to_f64(outs[l]), refs[l][0], "grid %d layer %d" % (n_wg, l))
+    got = pair[(n_layers - 1) % 2].cpu().numpy()
+    last = layers[-1]
+    for g in range(w.n_kv_heads):
+        if last.mask[g * G:(g + 1) * G].any():
+            ok, _, msg = H.index_sets_match(got[0, g], refs[-1][1][0, g], refs[-1][2][0, g, :L], k, H.TIE_REL)
+            assert ok, "grid %d head %d: %s" % (n_wg, g, msg)
+        else:
+            assert (got[0, g] == refs[-1][1][0, g]).all()
+
+
 def test_two_contexts_on_two_streams_run_layer_calls_side_by_side():
     """Two contexts, each on a stream of its own, run deferred layer chains at the same time (two
     model replicas on one GPU).  The launches share the GPU's workgroup slots; every wait inside a
@@ -1278,6 +1323,30 @@ def test_seeded_sweep_of_shapes_masks_and_modes(ctx, case):
     idx_in = None if mask.all() else H.previous_layer_sets(inp, k, block=block)
     _say("sweep %s lens=%s mask=%s" % (case[:5] + case[6:9], lens, mask.tolist()))
     H.check_layer(ctx, inp, mask, k, idx_in, "sweep%d" % i, keep_ppm=keep_ppm, block=block)
+
+
+@pytest.mark.parametrize("B,Hkv,G", [(256, 2, 1), (2, 64, 4), (256, 8, 4)])
+def test_largest_batch_and_head_counts(ctx, B, Hkv, G):
+    """The limits of a shape: 256 sequences (one per thread of the workgroup-wide scans over the batch), 64 KV
+    heads (the per-head tables of a layer descriptor), groups of 4, and both at once with 2048 query heads.
+    One further sequence or KV head is refused."""
+    lb = H.binding()
+    l_cap, k = 500, 24
+    rng = np.random.default_rng(1000 * B + Hkv)
+    lens = rng.integers(1, l_cap + 1, size=B).astype(np.int32)
+    lens[0], lens[-1] = l_cap, 1
+    mask = (rng.random(Hkv * G) < 0.3).astype(np.uint8)
+    mask[0], mask[-1] = 1, 0     # both kinds of head present
+    w = wl.scaled(wl.WORKLOADS["c1"], batch=B, n_q_heads=Hkv * G, n_kv_heads=Hkv, max_len=l_cap, k=k,
+                  planted=1, retrieval_heads=(), config_id=970 + Hkv)
+    inp = wl.make_layer(w, mask=mask, lens=lens, l_cap=l_cap)
+    idx_in = H.previous_layer_sets(inp, k)
+    _say("limits: batch %d, %d KV heads, group %d" % (B, Hkv, G))
+    dl = H.check_layer(ctx, inp, mask, k, idx_in, "limits B%d kv%d" % (B, Hkv))[0]
+    assert ctx.wait_timeouts() == 0
+    too_many = lb.make_shape(B + 1 if B == 256 else B, (Hkv + 1 if Hkv == 64 else Hkv) * G, Hkv + 1 if Hkv == 64 else Hkv,
+                             l_cap, k, kv=dl.k_cache)
+    assert lb.check_shape(too_many) == lb.EUNSUPPORTED
 
 
 @pytest.mark.parametrize("block", [1, 64])
