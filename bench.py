@@ -18,7 +18,8 @@ LYCHEE_STEP_LAYERWISE mode: one launch per layer.  Prints ONE JSON line.
 
 --secondary prints one JSON line per secondary configuration (c1, c2, c4, the c5 sweep, the
 kernel-study grid, the selection rules): cold (KV copies rotated past the 256 MB cache) and warm,
-median and minimum of >= 50 iterations, against the dense call on the same buffers.
+median and minimum of >= 50 iterations, against the dense call on the same buffers; then the model
+loop (deferred layer calls back to back) over context lengths from 8K to 128K.
 """
 from __future__ import annotations
 
@@ -439,7 +440,59 @@ def secondary(args) -> int:
             "speedup_vs_dense_cold": round(dcold[0] / cold[0], 3)}), flush=True)
         del copies, probe, ws
         torch.cuda.empty_cache()
-    print(json.dumps({"select_fallbacks": list(ctx.select_stats())}), flush=True)
+    # The model loop over context lengths: deferred layer calls back to back (each call's select inside the next
+    # call's launch), 8 layers of the c3 head layout (3 retrieval heads per layer), rotating through the layers'
+    # caches; against the dense call on the same caches.  Microseconds per layer, whole loop / layers.
+    c3 = wl.WORKLOADS["c3"]
+    for context in (8192, 16384, 32768, 65536, 131072):
+        for k in (1024, 4096):
+            if 2 * k > context:
+                continue
+            w = wl.scaled(c3, max_len=context, k=k, n_layers=9)
+            layers = [wl.make_layer(w, layer=l, device=dev, l_cap=context) for l in range(1, 9)]
+            lens = torch.from_numpy(layers[0].lengths).to(dev)
+            shape = lb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, context, k, kv=layers[0].k_cache)
+            ws = lb.alloc_workspace(shape, dev, n_layers=2)
+            out = torch.zeros_like(layers[0].q)
+            pair = [torch.zeros((w.batch, w.n_kv_heads, k), dtype=torch.int32, device=dev) for _ in range(2)]
+            for t in pair:
+                t[:] = torch.arange(k, dtype=torch.int32, device=dev) * (context // k)
+
+            def loop_hybrid():
+                for l, ly in enumerate(layers):
+                    ctx.decode_attn_deferred(shape, ly.q, ly.k_cache, ly.v_cache, ly.mask, pair[l & 1], out, pair[(l + 1) & 1], lens, ws)
+
+            def loop_dense():
+                for ly in layers:
+                    ctx.dense_decode_attn(shape, ly.q, ly.k_cache, ly.v_cache, out, lens, ws)
+
+            def per_layer(fn):
+                t = []
+                for rep in range(3 + 10):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(4):
+                        fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    if rep >= 3:
+                        t.append(e0.elapsed_time(e1) * 1e3 / (4 * len(layers)))
+                return round(float(np.median(t)), 1), round(float(min(t)), 1)
+
+            hyb = per_layer(loop_hybrid)
+            ctx.select_flush()
+            den = per_layer(loop_dense)
+            mask_bytes = np.mean([wl.algorithmic_bytes(w, ly.mask, ly.lengths) for ly in layers])
+            print(json.dumps({
+                "config": "model loop L%d k%d" % (context, k),
+                "shape": "B1 32q/8kv, 8 layers with 3 retrieval heads each, deferred calls back to back",
+                "hybrid_us_per_layer_median_min": list(hyb), "dense_us_per_layer_median_min": list(den),
+                "algorithmic_bytes_per_layer": int(mask_bytes),
+                "hybrid_hbm_frac": round(mask_bytes / hyb[0] / 1e3 / HBM_PEAK_GBPS, 4),
+                "speedup_vs_dense": round(den[0] / hyb[0], 3)}), flush=True)
+            del layers, ws
+            torch.cuda.empty_cache()
+    print(json.dumps({"select_fallbacks": list(ctx.select_stats()), "wait_timeouts": ctx.wait_timeouts()}), flush=True)
     ctx.close()
     return 0
 
